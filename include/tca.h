@@ -1,0 +1,231 @@
+/*
+ * tca.h - C ABI of the MI355X (gfx950) hot path of TCA-Attention
+ * (Training-free Context-adaptive Attention, arxiv 2512.09238).
+ *
+ * The library implements, for one attention layer on one GPU:
+ *   - offline head-specific sparsity determination   (Alg. 1, Eq. 3, Eq. 4)
+ *   - online core-context selection                   (Alg. 2 lines 1-6, Eq. 5-8)
+ *     followed by compaction of the retained K/V rows (App. C, "parallel tokens gathering")
+ *   - causal prefill attention over [K^G; K^L]        (Alg. 2 line 7, Eq. 2)
+ *   - single-token decode over the compacted cache,
+ *     with selection of each block completed while decoding (Sec. IV-B, last paragraph)
+ *
+ * Conventions
+ *   - "device" pointers are GPU memory owned by the caller; "host" pointers are
+ *     ordinary CPU memory owned by the caller.  The library never allocates or
+ *     frees device memory.  Scratch comes in through (ws, ws_bytes); query the
+ *     size with the matching tca_*_workspace_bytes().  ws must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it; only tca_calibrate_budgets waits for it.
+ *   - Tensors are dense, row-major, innermost dimension head_dim:
+ *       Q, O : [n_q_heads , rows, head_dim]
+ *       K, V : [n_kv_heads, kv_stride rows, head_dim]  (kv_stride >= rows used)
+ *     Element type per tca_params.dtype: TCA_BF16 (bfloat16) or TCA_F32 (float).
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).  Every query head
+ *     owns its own selection (the method is applied to each head independently, Sec. IV).
+ *   - Compacted global subset: idx / Kg / Vg hold, for head h, rows
+ *     offs[h] .. offs[h] + n_rows[h] - 1 of a flat buffer (offs = capacity prefix
+ *     sums, host array of n_q_heads+1 entries; App. C "flatten all head tokens
+ *     into a single contiguous buffer and precompute offsets").  idx is the
+ *     absolute token position of each row, ascending within a head.
+ *   - Positions are 0-based.  The local subset of the query at position i is the
+ *     window (i-w, i]; a global row at position j is visible to it iff j <= i-w,
+ *     so no key is counted twice (Sec. IV, "no overlap").
+ *   - Return value: 0 on success, a negative TCA_ERR_* otherwise; nothing is
+ *     launched when an argument check fails.  tca_last_error() returns a
+ *     thread-local description of the last failure.
+ *
+ * Limits: head_dim in {64, 128}; block b a power of two, 2 <= b <= 256;
+ * window w >= b and a multiple of b; n_q_heads <= 128, group size
+ * n_q_heads/n_kv_heads <= 8; at most 4096 blocks per tca_select call.
+ */
+#ifndef TCA_H
+#define TCA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TCA_BF16 0
+#define TCA_F32  1
+
+#define TCA_OK               0
+#define TCA_ERR_INVALID     -1   /* null pointer, inconsistent sizes, p not a distribution ... */
+#define TCA_ERR_UNSUPPORTED -2   /* head_dim / block / dtype / size outside the limits above  */
+#define TCA_ERR_WORKSPACE   -3   /* ws_bytes too small or ws misaligned                       */
+#define TCA_ERR_HIP         -4   /* a HIP runtime call failed (see tca_last_error)            */
+
+#define TCA_MAX_HEADS   128
+#define TCA_MAX_GROUP   8
+#define TCA_MAX_COUNTS  9        /* log2(256) + 1 */
+#define TCA_MAX_BLOCKS  4096
+
+typedef struct tca_params {
+  int32_t n_q_heads;   /* Hq                                                  */
+  int32_t n_kv_heads;  /* Hkv, divides Hq                                      */
+  int32_t head_dim;    /* d_h                                                 */
+  int32_t block;       /* b, block size of Sec. IV-A (paper: 128)             */
+  int32_t window;      /* w, local window of Sec. IV (paper: 4096)            */
+  int32_t dtype;       /* TCA_BF16 or TCA_F32: type of Q, K, V, O, Kg, Vg     */
+  double  alpha;       /* balance of Eq. 6 (paper: 0.5)                       */
+  double  scale;       /* logit scale; 0 selects 1/sqrt(head_dim) of Eq. 1    */
+} tca_params;
+
+/* ------------------------------------------------------------------ host --
+ * Small fp64 host routines: configurations (Eq. 3), the rank->budget map
+ * (Eq. 7) and the sizes that follow from them.  No GPU is touched. */
+
+/* Number of entries of a configuration p: |K| = log2(b)+1 for K={1,2,4,..,b}
+ * (Sec. IV-A).  Returns TCA_ERR_UNSUPPORTED if b is not a supported block size. */
+int tca_num_counts(int b);
+
+/* Eq. 3: M candidates, mu^i = log2(1 + (i-1)(b-1)/(M-1)), fixed sigma.
+ * p_out: host [M][nk], row i = p^{i+1}.  M >= 1, sigma > 0. */
+int tca_make_candidates(int b, int M, double sigma, double* p_out);
+
+/* Configuration of the Eq. 3 family (fixed sigma, mu found by bisection)
+ * whose mean budget sum_k k p_k equals frac*b.  frac >= 1: one-hot at k=b;
+ * above the family's largest mean: the mu=log2(b) member; below its smallest
+ * mean: one-hot at k=1.  p_out: host [nk]. */
+int tca_config_from_budget(int b, double sigma, double frac, double* p_out);
+
+/* Eq. 7: c_k = floor(m p_k) entries of value k in Psi; the m - sum c_k
+ * blocks left over take the minimum budget (added to c_1).  p: host [nk]
+ * (non-negative, sums to 1 within 1e-9).  counts_out: host [nk]. */
+int tca_psi_counts(int b, int64_t m, const double* p, int64_t* counts_out);
+
+/* Rows one tca_select call over n_blocks full blocks appends per head:
+ * sum_k k c_k, independent of the data.  p: host [Hq][nk].  rows_out: host
+ * [Hq] (nullable).  Returns the total over heads, or a negative error. */
+int64_t tca_select_rows(const tca_params* prm, int64_t n_blocks, const double* p, int64_t* rows_out);
+
+/* t = floor(sum_k k p_k): rows kept from a block completed during decoding
+ * (Sec. IV-B, last paragraph).  p: host [nk].  Negative on error. */
+int tca_decode_budget(int b, const double* p);
+
+size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens);
+size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries);
+/* max_head_rows: the largest capacity of one head's region, max_h (offs[h+1]-offs[h]). */
+size_t tca_decode_workspace_bytes(const tca_params* prm, int batch, int64_t max_head_rows);
+size_t tca_calibrate_workspace_bytes(const tca_params* prm, int64_t L_cal, int M);
+
+/* ---------------------------------------------------------------- device --*/
+
+/* Online core-context selection + compaction (Alg. 2 lines 1-6; Eq. 5-8).
+ *
+ * Scores tokens [pos0, pos0+n_tokens) of K with the query q_last:
+ *   x_j = scale * q_last . k_j,  s = softmax(x) over these n_tokens keys   (Eq. 5)
+ * splits them into m = n_tokens / b full blocks (a tail of n_tokens mod b
+ * tokens only takes part in the softmax normaliser and is never selected),
+ * evaluates h_j (Eq. 6), ranks the blocks by h (ties: lower block first),
+ * gives the block of rank r (0 = smallest h) the r-th entry of the ascending
+ * list Psi (Eq. 7), keeps each block's t_j highest-scoring tokens (ties: lower
+ * position first; Eq. 8) and appends their K and V rows and positions, in
+ * ascending position order, to each head's region of idx / Kg / Vg, starting
+ * at row offs[h] + n_rows[h]; n_rows[h] grows by tca_select_rows()[h].
+ * Rows that would pass offs[h+1] are dropped (never written).
+ *
+ *   q_last : device [Hq, d]
+ *   K, V   : device [Hkv, kv_stride, d]; pos0 is a multiple of b; pos0+n_tokens <= kv_stride
+ *   p      : host [Hq][nk]
+ *   offs   : host [Hq+1]
+ *   n_rows : device int32 [Hq], in/out (zero it before the first call)
+ *   idx    : device int32 [offs[Hq]]; Kg, Vg: device [offs[Hq], d]
+ * All scoring arithmetic is fp64, so the selected sets agree with an fp64
+ * reference except at exact ties.  Does not synchronise. */
+int tca_select(const tca_params* prm, const void* q_last, const void* K, const void* V,
+               int64_t kv_stride, int64_t pos0, int64_t n_tokens,
+               const double* p, const int64_t* offs, int32_t* n_rows,
+               int32_t* idx, void* Kg, void* Vg,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* Causal prefill attention over the global and local subsets (Eq. 2; Alg. 2 line 7).
+ *
+ * Query row r of Q sits at position i = q_pos0 + r and attends to
+ *   { global rows g of its head with idx[g] <= i-w }  U  { dense keys max(0,i-w+1) .. i }
+ * with one softmax over the union; O gets the weighted sum of the matching V rows.
+ *
+ *   Q, O   : device [Hq, n_queries, d]
+ *   K, V   : device [Hkv, kv_stride, d], dense rows; q_pos0 + n_queries <= kv_stride
+ *   idx, Kg, Vg, offs, n_rows : as written by tca_select (n_rows: device int32 [Hq])
+ *   lse    : device float [Hq, n_queries] or NULL: natural-log sum of exp of the scaled logits
+ * TCA_BF16: bf16 MFMA products, fp32 softmax and accumulation.  TCA_F32: fp32 throughout.
+ * Does not synchronise. */
+int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_queries,
+                const void* K, const void* V, int64_t kv_stride,
+                const int32_t* idx, const void* Kg, const void* Vg,
+                const int64_t* offs, const int32_t* n_rows,
+                void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* KV cache of a batch of sequences that share one set of per-head budgets
+ * (budgets belong to the model, Sec. IV-A).  All pointers are device memory. */
+typedef struct tca_cache {
+  int32_t  batch;      /* B                                                            */
+  int64_t  cap_rows;   /* rows of the flat global buffer per sequence (= offs[Hq])      */
+  int32_t* idx;        /* [B, cap_rows]     positions of the global rows                */
+  void*    Kg;         /* [B, cap_rows, d]                                              */
+  void*    Vg;         /* [B, cap_rows, d]                                              */
+  int32_t* n_rows;     /* [B, Hq]           rows filled per head (updated by the library) */
+  void*    ringK;      /* [B, Hkv, w, d]    last w dense rows, position P at slot P mod w */
+  void*    ringV;      /* [B, Hkv, w, d]                                                */
+  int64_t* length;     /* [B]               tokens seen so far (updated by the library)  */
+} tca_cache;
+
+/* Hand a prefilled sequence over to the decode cache: copies dense rows
+ * [max(0,L-w), L) of K and V into sequence `seq`'s ring (slot = position mod w)
+ * and sets length[seq] = L.  The global region of that sequence is whatever
+ * tca_select wrote there (pass idx + seq*cap_rows etc. to tca_select).
+ * K, V: device [Hkv, kv_stride, d].  Does not synchronise. */
+int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq,
+                          const void* K, const void* V, int64_t kv_stride, int64_t L, void* stream);
+
+/* One decode step for every sequence of the batch (Sec. IV-B, last paragraph).
+ *
+ * For sequence s with T = length[s]: the new row (k_new[s], v_new[s]) becomes
+ * position T (ring slot T mod w); query q[s,h] attends to the head's global
+ * rows with idx <= T-w and to dense positions max(0,T-w+1) .. T (Eq. 2 for one
+ * query); if T+1 is a multiple of b, block T/b is complete: its b rows are
+ * scored with this step's query (Eq. 5 restricted to the block) and the
+ * t = floor(sum_k k p_k) best (ties: lower position), in ascending position
+ * order, are appended to the head's global region (dropped beyond capacity);
+ * finally length[s] = T+1.
+ *
+ *   q      : device [B, Hq, d];  k_new, v_new: device [B, Hkv, d];  O: device [B, Hq, d]
+ *   offs   : host [Hq+1] (capacity prefix sums, offs[Hq] == cache->cap_rows)
+ *   p      : host [Hq][nk]
+ * Does not synchronise; lengths live on the device, so steps can be queued back to back. */
+int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs,
+               const void* q, const void* k_new, const void* v_new, const double* p,
+               void* O, void* ws, size_t ws_bytes, void* stream);
+
+/* Offline head-specific sparsity determination (Alg. 1) on one calibration sequence.
+ *
+ * For every query head: column means of the dense causal attention matrix
+ * A = softmax(scale * Q K^T) (mean of column k over the L_cal - k rows that can
+ * see it; Eq. 4 inner term), the selection S_i of each of the M candidates of
+ * Eq. 3 (same procedure as tca_select, scored by the last query of the sample),
+ * a_i = sum over S_i of the column means (Eq. 4), and the valid candidate
+ * (a_i >= tau) that keeps the fewest rows (ties: lower i).  If none is valid the
+ * last candidate is returned and fallback[h] = 1.
+ *
+ *   Qcal : device [Hq, L_cal, d];  Kcal: device [Hkv, L_cal, d]
+ *   p_star   : host [Hq][nk]   chosen configuration
+ *   cand_idx : host [Hq]       its 0-based index
+ *   a_out    : host [Hq][M] or NULL: a_i;  n_out: host int64 [Hq][M] or NULL: |S_i|
+ *   fallback : host [Hq] or NULL
+ * Waits for `stream` before returning (results are host arrays). */
+int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, const void* Kcal, int64_t L_cal,
+                          int M, double sigma, double tau,
+                          double* p_star, int32_t* cand_idx, double* a_out, int64_t* n_out,
+                          int32_t* fallback, void* ws, size_t ws_bytes, void* stream);
+
+const char* tca_strerror(int code);
+const char* tca_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCA_H */

@@ -1,0 +1,224 @@
+"""ctypes binding of libtca.so: argument marshalling only.
+
+Every function has the name and the argument order of its C declaration in
+include/tca.h.  Device arrays are torch CUDA tensors (used for memory and
+streams only); host arrays are numpy.  Nothing here computes any step of the
+method, and there is no CPU fallback: if the library is missing, importing
+this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtca.so")
+
+TCA_BF16, TCA_F32 = 0, 1
+TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2512_09238_amd.build` "
+        "(or __graft_entry__.build()).  There is no fallback path."
+    )
+lib = C.CDLL(LIB_PATH)
+
+
+class tca_params(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("block", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32),
+        ("alpha", C.c_double), ("scale", C.c_double),
+    ]
+
+
+class tca_cache(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("cap_rows", C.c_int64),
+        ("idx", C.c_void_p), ("Kg", C.c_void_p), ("Vg", C.c_void_p), ("n_rows", C.c_void_p),
+        ("ringK", C.c_void_p), ("ringV", C.c_void_p), ("length", C.c_void_p),
+    ]
+
+
+_P = C.POINTER
+_dbl_p, _i64_p, _i32_p = _P(C.c_double), _P(C.c_int64), _P(C.c_int32)
+
+EXPORTS = {
+    "tca_num_counts": (C.c_int, [C.c_int]),
+    "tca_make_candidates": (C.c_int, [C.c_int, C.c_int, C.c_double, _dbl_p]),
+    "tca_config_from_budget": (C.c_int, [C.c_int, C.c_double, C.c_double, _dbl_p]),
+    "tca_psi_counts": (C.c_int, [C.c_int, C.c_int64, _dbl_p, _i64_p]),
+    "tca_select_rows": (C.c_int64, [_P(tca_params), C.c_int64, _dbl_p, _i64_p]),
+    "tca_decode_budget": (C.c_int, [C.c_int, _dbl_p]),
+    "tca_select_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64]),
+    "tca_prefill_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64]),
+    "tca_decode_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int, C.c_int64]),
+    "tca_calibrate_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64, C.c_int]),
+    "tca_select": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                             C.c_int64, _dbl_p, _i64_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                             C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_prefill": (C.c_int, [_P(tca_params), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                              C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, _i64_p, C.c_void_p,
+                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_cache_load_window": (C.c_int, [_P(tca_params), _P(tca_cache), C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_int64, C.c_int64, C.c_void_p]),
+    "tca_decode": (C.c_int, [_P(tca_params), _P(tca_cache), _i64_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                             _dbl_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_calibrate_budgets": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
+                                        C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_strerror": (C.c_char_p, [C.c_int]),
+    "tca_last_error": (C.c_char_p, []),
+}
+for _name, (_res, _args) in EXPORTS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+class TcaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"{lib.tca_strerror(code).decode()} ({code}): {lib.tca_last_error().decode()}")
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise TcaError(int(rc))
+    return int(rc)
+
+
+def _dp(t):
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device arguments must be contiguous CUDA tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _host(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(int(stream))
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha=0.5, scale=0.0) -> tca_params:
+    return tca_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha, scale)
+
+
+# ---------------------------------------------------------------- host --
+def tca_num_counts(b: int) -> int:
+    return _check(lib.tca_num_counts(b))
+
+
+def tca_make_candidates(b: int, M: int, sigma: float) -> np.ndarray:
+    out = np.empty((M, tca_num_counts(b)), np.float64)
+    _check(lib.tca_make_candidates(b, M, sigma, out.ctypes.data_as(_dbl_p)))
+    return out
+
+
+def tca_config_from_budget(b: int, sigma: float, frac: float) -> np.ndarray:
+    out = np.empty(tca_num_counts(b), np.float64)
+    _check(lib.tca_config_from_budget(b, sigma, frac, out.ctypes.data_as(_dbl_p)))
+    return out
+
+
+def tca_psi_counts(b: int, m: int, p) -> np.ndarray:
+    p = _host(p, np.float64)
+    out = np.empty(tca_num_counts(b), np.int64)
+    _check(lib.tca_psi_counts(b, m, p.ctypes.data_as(_dbl_p), out.ctypes.data_as(_i64_p)))
+    return out
+
+
+def tca_select_rows(prm: tca_params, n_blocks: int, p):
+    p = _host(p, np.float64)
+    rows = np.empty(prm.n_q_heads, np.int64)
+    total = _check(lib.tca_select_rows(C.byref(prm), n_blocks, p.ctypes.data_as(_dbl_p), rows.ctypes.data_as(_i64_p)))
+    return total, rows
+
+
+def tca_decode_budget(b: int, p) -> int:
+    p = _host(p, np.float64)
+    return _check(lib.tca_decode_budget(b, p.ctypes.data_as(_dbl_p)))
+
+
+def tca_select_workspace_bytes(prm, n_tokens: int) -> int:
+    return int(lib.tca_select_workspace_bytes(C.byref(prm), n_tokens))
+
+
+def tca_prefill_workspace_bytes(prm, n_queries: int) -> int:
+    return int(lib.tca_prefill_workspace_bytes(C.byref(prm), n_queries))
+
+
+def tca_decode_workspace_bytes(prm, batch: int, max_head_rows: int) -> int:
+    return int(lib.tca_decode_workspace_bytes(C.byref(prm), batch, max_head_rows))
+
+
+def tca_calibrate_workspace_bytes(prm, L_cal: int, M: int) -> int:
+    return int(lib.tca_calibrate_workspace_bytes(C.byref(prm), L_cal, M))
+
+
+# -------------------------------------------------------------- device --
+def _ws_args(ws):
+    if ws is None:
+        return None, 0
+    return _dp(ws), ws.numel() * ws.element_size()
+
+
+def tca_select(prm, q_last, K, V, kv_stride, pos0, n_tokens, p, offs, n_rows, idx, Kg, Vg, ws, stream=None):
+    p = _host(p, np.float64)
+    offs = _host(offs, np.int64)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_select(C.byref(prm), _dp(q_last), _dp(K), _dp(V), kv_stride, pos0, n_tokens,
+                          p.ctypes.data_as(_dbl_p), offs.ctypes.data_as(_i64_p), _dp(n_rows), _dp(idx),
+                          _dp(Kg), _dp(Vg), wsp, wsb, _stream(stream)))
+
+
+def tca_prefill(prm, Q, q_pos0, n_queries, K, V, kv_stride, idx, Kg, Vg, offs, n_rows, O, lse, ws, stream=None):
+    offs = _host(offs, np.int64)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_prefill(C.byref(prm), _dp(Q), q_pos0, n_queries, _dp(K), _dp(V), kv_stride, _dp(idx),
+                           _dp(Kg), _dp(Vg), offs.ctypes.data_as(_i64_p), _dp(n_rows), _dp(O), _dp(lse),
+                           wsp, wsb, _stream(stream)))
+
+
+def make_cache(batch, cap_rows, idx, Kg, Vg, n_rows, ringK, ringV, length) -> tca_cache:
+    return tca_cache(batch, cap_rows, idx.data_ptr(), Kg.data_ptr(), Vg.data_ptr(), n_rows.data_ptr(),
+                     ringK.data_ptr(), ringV.data_ptr(), length.data_ptr())
+
+
+def tca_cache_load_window(prm, cache, seq, K, V, kv_stride, L, stream=None):
+    _check(lib.tca_cache_load_window(C.byref(prm), C.byref(cache), seq, _dp(K), _dp(V), kv_stride, L,
+                                     _stream(stream)))
+
+
+def tca_decode(prm, cache, offs, q, k_new, v_new, p, O, ws, stream=None):
+    p = _host(p, np.float64)
+    offs = _host(offs, np.int64)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_decode(C.byref(prm), C.byref(cache), offs.ctypes.data_as(_i64_p), _dp(q), _dp(k_new),
+                          _dp(v_new), p.ctypes.data_as(_dbl_p), _dp(O), wsp, wsb, _stream(stream)))
+
+
+def tca_calibrate_budgets(prm, Qcal, Kcal, L_cal, M, sigma, tau, ws, stream=None):
+    """Returns dict(p_star [Hq,nk], cand_idx [Hq], a [Hq,M], n [Hq,M], fallback [Hq])."""
+    Hq, nk = prm.n_q_heads, tca_num_counts(prm.block)
+    p_star = np.empty((Hq, nk), np.float64)
+    cand = np.empty(Hq, np.int32)
+    a = np.empty((Hq, M), np.float64)
+    n = np.empty((Hq, M), np.int64)
+    fb = np.empty(Hq, np.int32)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_calibrate_budgets(C.byref(prm), _dp(Qcal), _dp(Kcal), L_cal, M, sigma, tau,
+                                     p_star.ctypes.data_as(_dbl_p), cand.ctypes.data_as(_i32_p),
+                                     a.ctypes.data_as(_dbl_p), n.ctypes.data_as(_i64_p),
+                                     fb.ctypes.data_as(_i32_p), wsp, wsb, _stream(stream)))
+    return {"p_star": p_star, "cand_idx": cand, "a": a, "n": n, "fallback": fb}

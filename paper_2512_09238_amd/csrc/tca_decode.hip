@@ -1,0 +1,410 @@
+// Single-token decode over the compacted KV cache, and selection of blocks
+// completed while decoding (Sec. IV-B, "Online Token Selection in Decoding Stage").
+//
+// One step = four launches on the caller's stream:
+//   prep    : write the new K/V row into the ring; per head, count the global
+//             rows that have left the window (idx <= T-w; idx is ascending so
+//             this is a prefix).
+//   partial : split-K attention.  grid (slot, head, sequence); a slot is a chunk
+//             of kChunk rows of the head's global region or of the ring.  The
+//             256 threads form sixteen 16-lane groups, each streaming whole rows
+//             with 16-byte loads and keeping its own online softmax; groups are
+//             merged into one (max, sum, acc[D]) partial per slot.  HBM-bound:
+//             every K/V row is read once per query head.
+//   merge   : log-sum-exp merge of a head's partials -> O.  If the new token
+//             completes a block, the same workgroup scores the block's b rows
+//             with this step's query in fp64 (Eq. 5 restricted to the block),
+//             ranks them and appends the top t = floor(sum k p_k) to the head's
+//             global region in position order.
+//   advance : length += 1.
+#include <hip/hip_runtime.h>
+
+#include "tca_common.h"
+#include "tca_device.h"
+
+namespace tca {
+
+constexpr int kChunk = 1024;          // rows per split-K slot
+constexpr int kDecThreads = 256;
+
+struct DecodeHeads {
+  int64_t offs[TCA_MAX_HEADS + 1];
+  int32_t t_dec[TCA_MAX_HEADS];
+};
+
+struct DecodeWs {
+  int32_t* n_vis;    // [B][Hq]
+  float* part;       // [B][Hq][n_slots][D+2]
+  size_t bytes;
+};
+
+static DecodeWs carve_decode_ws(void* ws, int B, int Hq, int D, int n_slots) {
+  DecodeWs w;
+  char* base = (char*)ws;
+  size_t off = 0;
+  w.n_vis = (int32_t*)(base + off); off = align_up(off + (size_t)B * Hq * sizeof(int32_t), 256);
+  w.part = (float*)(base + off);    off = align_up(off + (size_t)B * Hq * n_slots * (D + 2) * sizeof(float), 256);
+  w.bytes = off;
+  return w;
+}
+
+static int window_slots(int w) { return (w + kChunk - 1) / kChunk; }
+static int global_slots(int64_t max_head_rows) { return (int)((max_head_rows + kChunk - 1) / kChunk); }
+
+__device__ __forceinline__ int count_le_dev(const int32_t* idx, int n, int64_t bound) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)idx[mid] <= bound) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// grid (B); block 256
+template <typename T>
+__global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hq, int Hkv, int D, int w,
+                                   const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                   int32_t* __restrict__ n_vis) {
+  const int s = blockIdx.x;
+  const int64_t Tpos = c.length[s];
+  const int slot = (int)(Tpos % w);
+  T* rk = (T*)c.ringK;
+  T* rv = (T*)c.ringV;
+  for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+    const int kvh = e / D, dd = e - kvh * D;
+    const size_t dst = (((size_t)s * Hkv + kvh) * w + slot) * D + dd;
+    rk[dst] = k_new[(size_t)s * Hkv * D + e];
+    rv[dst] = v_new[(size_t)s * Hkv * D + e];
+  }
+  for (int h = threadIdx.x; h < Hq; h += blockDim.x) {
+    const int32_t* ix = c.idx + (size_t)s * c.cap_rows + dh.offs[h];
+    n_vis[s * Hq + h] = count_le_dev(ix, c.n_rows[s * Hq + h], Tpos - w);
+  }
+}
+
+// grid (n_slots, Hq, B); block 256
+template <typename T, int D>
+__global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
+    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
+    const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
+  constexpr int EL = D / 16;
+  __shared__ float red[kDecThreads / kWave][16][EL + 2];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int grp = tid >> 4, sub = tid & 15;           // 16 groups of 16 lanes
+  const int slot = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
+  const int G = Hq / Hkv, kvh = h / G;
+  float* out = part + (((size_t)s * Hq + h) * n_slots + slot) * (D + 2);
+  const int64_t Tpos = c.length[s];
+
+  const T *kbase, *vbase;
+  int r_begin, r_end;            // rows of this chunk, relative to kbase
+  bool is_window = slot >= g_slots;
+  if (!is_window) {
+    const int nv = n_vis[s * Hq + h];
+    r_begin = slot * kChunk;
+    r_end = min(nv, r_begin + kChunk);
+    const size_t base = (size_t)s * c.cap_rows + dh.offs[h];
+    kbase = (const T*)c.Kg + base * D;
+    vbase = (const T*)c.Vg + base * D;
+  } else {
+    r_begin = (slot - g_slots) * kChunk;
+    r_end = min(w, r_begin + kChunk);
+    const size_t base = ((size_t)s * Hkv + kvh) * w;
+    kbase = (const T*)c.ringK + base * D;
+    vbase = (const T*)c.ringV + base * D;
+  }
+  if (r_begin >= r_end) {
+    if (tid == 0) { out[0] = -INFINITY; out[1] = 0.f; }
+    return;
+  }
+
+  float qv[EL];
+  load_slice<T, EL>(q + ((size_t)s * Hq + h) * D + sub * EL, qv);
+#pragma unroll
+  for (int e = 0; e < EL; ++e) qv[e] *= scale;
+
+  float m = -INFINITY, l = 0.f, acc[EL];
+#pragma unroll
+  for (int e = 0; e < EL; ++e) acc[e] = 0.f;
+
+  for (int r0 = r_begin; r0 < r_end; r0 += 16) {
+    const int r = r0 + grp;
+    bool ok = r < r_end;
+    if (ok && is_window) {
+      // slot r of the ring holds position Tpos - ((Tpos - r) mod w); empty while Tpos < w
+      const int64_t back = ((Tpos - r) % w + w) % w;
+      ok = Tpos - back >= 0;
+    }
+    float sc = 0.f;
+    float kv[EL];
+    if (ok) {
+      load_slice<T, EL>(kbase + (size_t)r * D + sub * EL, kv);
+#pragma unroll
+      for (int e = 0; e < EL; ++e) sc = fmaf(qv[e], kv[e], sc);
+    }
+    sc = group_sum(sc, 16);
+    if (ok) {
+      float vv[EL];
+      load_slice<T, EL>(vbase + (size_t)r * D + sub * EL, vv);
+      const float mn = fmaxf(m, sc);
+      const float corr = __expf(m - mn), pr = __expf(sc - mn);
+      l = l * corr + pr;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc[e] = acc[e] * corr + pr * vv[e];
+      m = mn;
+    }
+  }
+  // merge the 4 groups of a wave, then the 4 waves through LDS
+  for (int o = 16; o < 64; o <<= 1) {
+    const float mo = __shfl_xor(m, o, kWave), lo = __shfl_xor(l, o, kWave);
+    const float mn = fmaxf(m, mo);
+    const float ca = (m == -INFINITY) ? 0.f : __expf(m - mn);
+    const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
+    l = l * ca + lo * cb;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[e] = acc[e] * ca + __shfl_xor(acc[e], o, kWave) * cb;
+    m = mn;
+  }
+  if (lane < 16) {
+    red[wv][lane][0] = m;
+    red[wv][lane][1] = l;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) red[wv][lane][2 + e] = acc[e];
+  }
+  __syncthreads();
+  if (tid < 16) {
+    float M = -INFINITY;
+    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[x][tid][0]);
+    float L = 0.f, a[EL];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) a[e] = 0.f;
+    for (int x = 0; x < kDecThreads / kWave; ++x) {
+      const float mx = red[x][tid][0];
+      const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+      L += red[x][tid][1] * cf;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) a[e] += red[x][tid][2 + e] * cf;
+    }
+    if (tid == 0) { out[0] = M; out[1] = L; }
+#pragma unroll
+    for (int e = 0; e < EL; ++e) out[2 + tid * EL + e] = a[e];
+  }
+}
+
+// grid (Hq, B); block 256
+template <typename T, int D>
+__global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
+    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int b, int n_slots, double scale,
+    const T* __restrict__ q, const float* __restrict__ part, T* __restrict__ O) {
+  constexpr int EL = D / 16;
+  __shared__ double xs[256];
+  __shared__ int32_t sel[256];
+  __shared__ int32_t wave_cnt[kDecThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int h = blockIdx.x, s = blockIdx.y;
+  const int G = Hq / Hkv, kvh = h / G;
+  const float* pp = part + ((size_t)s * Hq + h) * n_slots * (D + 2);
+
+  if (tid < D) {
+    float M = -INFINITY;
+    for (int x = 0; x < n_slots; ++x)
+      if (pp[(size_t)x * (D + 2) + 1] > 0.f) M = fmaxf(M, pp[(size_t)x * (D + 2)]);
+    float L = 0.f, a = 0.f;
+    for (int x = 0; x < n_slots; ++x) {
+      const float lx = pp[(size_t)x * (D + 2) + 1];
+      if (lx > 0.f) {
+        const float cf = __expf(pp[(size_t)x * (D + 2)] - M);
+        L += lx * cf;
+        a += pp[(size_t)x * (D + 2) + 2 + tid] * cf;
+      }
+    }
+    store_f32(O + ((size_t)s * Hq + h) * D + tid, a / L);
+  }
+
+  // block completed by this token?
+  const int64_t Tpos = c.length[s];
+  if ((Tpos + 1) % b != 0) return;
+  const int64_t p0 = Tpos + 1 - b;                     // first position of the block
+  const int slot0 = (int)(p0 % w);                     // contiguous in the ring: w is a multiple of b
+  const T* kb = (const T*)c.ringK + (((size_t)s * Hkv + kvh) * w + slot0) * D;
+  const T* vb = (const T*)c.ringV + (((size_t)s * Hkv + kvh) * w + slot0) * D;
+  const int grp = tid >> 4, sub = tid & 15;
+  float qf[EL];
+  load_slice<T, EL>(q + ((size_t)s * Hq + h) * D + sub * EL, qf);
+  for (int r0 = 0; r0 < b; r0 += 16) {
+    const int r = r0 + grp;
+    double a = 0.0;
+    if (r < b) {
+      float kf[EL];
+      load_slice<T, EL>(kb + (size_t)r * D + sub * EL, kf);
+#pragma unroll
+      for (int e = 0; e < EL; ++e) a = fma((double)kf[e], (double)qf[e], a);
+    }
+    a = group_sum(a, 16);
+    if (r < b && sub == 0) xs[r] = a * scale;
+  }
+  __syncthreads();
+  const int t = dh.t_dec[h];
+  bool keep = false;
+  if (tid < b) {
+    const double xi = xs[tid];
+    int cnt = 0;
+    for (int o = 0; o < b; ++o) {
+      const double xo = xs[o];
+      cnt += (xo > xi) || (xo == xi && o < tid);
+    }
+    keep = cnt < t;
+  }
+  const unsigned long long mask = __ballot(keep);
+  if (lane == 0) wave_cnt[wv] = __popcll(mask);
+  __syncthreads();
+  int before = __popcll(mask & ((1ull << lane) - 1ull));
+  for (int x = 0; x < wv; ++x) before += wave_cnt[x];
+  if (keep) sel[before] = tid;
+  __syncthreads();
+  const int64_t cap = dh.offs[h + 1] - dh.offs[h];
+  const int32_t fill = c.n_rows[s * Hq + h];
+  const size_t base = (size_t)s * c.cap_rows + dh.offs[h];
+  T* Kg = (T*)c.Kg;
+  T* Vg = (T*)c.Vg;
+  for (int k = grp; k < t; k += 16) {
+    const int64_t row = (int64_t)fill + k;
+    if (row >= cap) break;
+    const int src = sel[k];
+    for (int e = 0; e < EL; ++e) {
+      Kg[(base + row) * D + sub * EL + e] = kb[(size_t)src * D + sub * EL + e];
+      Vg[(base + row) * D + sub * EL + e] = vb[(size_t)src * D + sub * EL + e];
+    }
+    if (sub == 0) c.idx[base + row] = (int32_t)(p0 + src);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int64_t nf = (int64_t)fill + t;
+    c.n_rows[s * Hq + h] = (int32_t)(nf > cap ? cap : nf);
+  }
+}
+
+__global__ void decode_advance_kernel(int64_t* length, int B) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < B) length[s] += 1;
+}
+
+// grid (ceil(rows/16), Hkv); block 256: 16 rows per iteration
+template <typename T>
+__global__ void load_window_kernel(tca_cache c, int seq, int Hkv, int D, int w, const T* __restrict__ K,
+                                   const T* __restrict__ V, int64_t kv_stride, int64_t L) {
+  const int kvh = blockIdx.y;
+  const int64_t first = L - w > 0 ? L - w : 0;
+  const int64_t pos = first + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) c.length[seq] = L;
+  if (pos >= L) return;
+  const int slot = (int)(pos % w);
+  const T* ks = K + ((size_t)kvh * kv_stride + pos) * D;
+  const T* vs = V + ((size_t)kvh * kv_stride + pos) * D;
+  T* kd = (T*)c.ringK + (((size_t)seq * Hkv + kvh) * w + slot) * D;
+  T* vd = (T*)c.ringV + (((size_t)seq * Hkv + kvh) * w + slot) * D;
+  for (int e = threadIdx.x & 15; e < D; e += 16) { kd[e] = ks[e]; vd[e] = vs[e]; }
+}
+
+static int check_cache(const tca_params* prm, const tca_cache* c) {
+  if (!c) return fail(TCA_ERR_INVALID, "cache is NULL");
+  if (c->batch < 1 || c->cap_rows < 0) return fail(TCA_ERR_INVALID, "cache: batch=%d cap_rows=%lld", c->batch,
+                                                   (long long)c->cap_rows);
+  if (!c->idx || !c->Kg || !c->Vg || !c->n_rows || !c->ringK || !c->ringV || !c->length)
+    return fail(TCA_ERR_INVALID, "cache: NULL pointer member");
+  (void)prm;
+  return TCA_OK;
+}
+
+template <typename T, int D>
+static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHeads& dh, int64_t max_rows,
+                      const T* q, const T* k_new, const T* v_new, T* O, void* ws, hipStream_t st) {
+  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, B = c->batch, w = prm->window;
+  const int g_slots = global_slots(max_rows), n_slots = g_slots + window_slots(w);
+  DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
+  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B), dim3(256), 0, st, *c, dh, Hq, Hkv, D, w, k_new, v_new,
+                     dw.n_vis);
+  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(n_slots, Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq,
+                     Hkv, w, g_slots, n_slots, (float)logit_scale(prm), q, dw.n_vis, dw.part);
+  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq, Hkv, w,
+                     prm->block, n_slots, logit_scale(prm), q, dw.part, O);
+  hipLaunchKernelGGL(decode_advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, c->length, B);
+  return TCA_OK;
+}
+
+}  // namespace tca
+
+using namespace tca;
+
+extern "C" size_t tca_decode_workspace_bytes(const tca_params* prm, int batch, int64_t max_head_rows) {
+  if (check_params(prm) != TCA_OK || batch < 1 || max_head_rows < 0) return 0;
+  const int n_slots = global_slots(max_head_rows) + window_slots(prm->window);
+  return carve_decode_ws(nullptr, batch, prm->n_q_heads, prm->head_dim, n_slots).bytes;
+}
+
+extern "C" int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq, const void* K,
+                                     const void* V, int64_t kv_stride, int64_t L, void* stream) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  rc = check_cache(prm, cache);
+  if (rc) return rc;
+  if (!K || !V || seq < 0 || seq >= cache->batch || L < 0 || L > kv_stride)
+    return fail(TCA_ERR_INVALID, "tca_cache_load_window: seq=%d L=%lld kv_stride=%lld", seq, (long long)L,
+                (long long)kv_stride);
+  const int w = prm->window;
+  const int64_t rows = L < w ? L : w;
+  dim3 grid((unsigned)((rows + 15) / 16 > 0 ? (rows + 15) / 16 : 1), prm->n_kv_heads);
+  hipStream_t st = (hipStream_t)stream;
+  if (prm->dtype == TCA_BF16)
+    hipLaunchKernelGGL((load_window_kernel<bf16_t>), grid, dim3(256), 0, st, *cache, seq, prm->n_kv_heads,
+                       prm->head_dim, w, (const bf16_t*)K, (const bf16_t*)V, kv_stride, L);
+  else
+    hipLaunchKernelGGL((load_window_kernel<float>), grid, dim3(256), 0, st, *cache, seq, prm->n_kv_heads,
+                       prm->head_dim, w, (const float*)K, (const float*)V, kv_stride, L);
+  TCA_HIP_CHECK(hipGetLastError());
+  return TCA_OK;
+}
+
+extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs, const void* q,
+                          const void* k_new, const void* v_new, const double* p, void* O, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  rc = check_cache(prm, cache);
+  if (rc) return rc;
+  if (!offs || !q || !k_new || !v_new || !p || !O || !ws)
+    return fail(TCA_ERR_INVALID, "tca_decode: NULL pointer argument");
+  const int Hq = prm->n_q_heads, b = prm->block, nk = block_log2(b) + 1;
+  if (offs[0] != 0 || offs[Hq] != cache->cap_rows)
+    return fail(TCA_ERR_INVALID, "tca_decode: offs[0] must be 0 and offs[Hq] must equal cap_rows");
+  DecodeHeads dh;
+  int64_t max_rows = 0;
+  for (int h = 0; h < Hq; ++h) {
+    if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_decode: offs not ascending at %d", h);
+    if (offs[h + 1] - offs[h] > INT32_MAX) return fail(TCA_ERR_UNSUPPORTED, "head region beyond int32 rows");
+    if (offs[h + 1] - offs[h] > max_rows) max_rows = offs[h + 1] - offs[h];
+    if (!valid_config(p + (size_t)h * nk, nk))
+      return fail(TCA_ERR_INVALID, "tca_decode: p[%d] is not a distribution", h);
+    dh.offs[h] = offs[h];
+    dh.t_dec[h] = tca_decode_budget(b, p + (size_t)h * nk);
+  }
+  dh.offs[Hq] = offs[Hq];
+  const size_t need = tca_decode_workspace_bytes(prm, cache->batch, max_rows);
+  if (ws_bytes < need || ((uintptr_t)ws & 255))
+    return fail(TCA_ERR_WORKSPACE, "tca_decode: workspace needs %zu bytes, 256-byte aligned", need);
+  hipStream_t st = (hipStream_t)stream;
+  if (prm->dtype == TCA_BF16) {
+    using T = bf16_t;
+    rc = prm->head_dim == 128
+             ? run_decode<T, 128>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st)
+             : run_decode<T, 64>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st);
+  } else {
+    using T = float;
+    rc = prm->head_dim == 128
+             ? run_decode<T, 128>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st)
+             : run_decode<T, 64>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st);
+  }
+  if (rc) return rc;
+  TCA_HIP_CHECK(hipGetLastError());
+  return TCA_OK;
+}

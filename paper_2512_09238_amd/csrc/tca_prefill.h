@@ -1,0 +1,24 @@
+// Internal launchers of the two prefill kernels (Eq. 2).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "tca_common.h"
+#include "tca_device.h"
+
+namespace tca {
+
+// One wavefront per query, fp32 arithmetic; any storage type.
+template <typename T>
+int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64_t n_queries, const T* K,
+                        const T* V, int64_t kv_stride, const int32_t* idx, const T* Kg, const T* Vg,
+                        const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st);
+
+// bf16 MFMA flash kernel.
+size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries);
+int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
+                        const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
+                        const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,
+                        bf16_t* O, float* lse, void* ws, hipStream_t st);
+
+}  // namespace tca

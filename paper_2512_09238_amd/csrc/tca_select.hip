@@ -1,0 +1,400 @@
+// Online core-context selection and compaction (Alg. 2 lines 1-6; Eq. 5-8).
+//
+// Three kernels, K is read from HBM exactly once and logits never leave the chip:
+//   score_kernel  : one workgroup per (KV head, block of b tokens).  Streams the
+//                   block's K rows with 16-byte loads, forms the logits of all G
+//                   query heads of the group in fp64 (Eq. 5 numerator), reduces
+//                   them to the block statistics max / sum e^x / sum e^2x that
+//                   Eq. 6 needs, and ranks the b tokens inside the block (the
+//                   in-block rank does not depend on the budget, so Eq. 8 becomes
+//                   "rank < t_j" later).  Writes 1 byte per (head, token).
+//   assign_kernel : one workgroup per query head.  Global softmax normaliser,
+//                   h_j (Eq. 6), rank of every block, t_j = Psi[rank] (Eq. 7),
+//                   exclusive scan of t_j -> destination row of every block.
+//   gather_kernel : one workgroup per (head, block).  Keeps tokens with
+//                   rank < t_j in position order and copies their K/V rows and
+//                   positions into the head's flat region (App. C).
+#include <hip/hip_runtime.h>
+
+#include "tca_common.h"
+#include "tca_device.h"
+
+namespace tca {
+
+constexpr int kScoreThreads = 256;
+constexpr int kAssignThreads = 1024;
+constexpr int kGatherThreads = 256;
+constexpr int kHeadsPerLaunch = 32;
+
+struct SelectWs {
+  uint8_t* tokrank;   // [Hq][n_blocks*b]
+  double* stats;      // [Hq][nbt][3]
+  int32_t* blk_t;     // [Hq][n_blocks]
+  int32_t* blk_dst;   // [Hq][n_blocks] row inside the head's region
+  size_t bytes;
+};
+
+static SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
+  int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
+  size_t off = 0;
+  SelectWs w;
+  char* base = (char*)ws;
+  w.tokrank = (uint8_t*)(base + off); off = align_up(off + (size_t)Hq * nb * b, 256);
+  w.stats = (double*)(base + off);    off = align_up(off + (size_t)Hq * nbt * 3 * sizeof(double), 256);
+  w.blk_t = (int32_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
+  w.blk_dst = (int32_t*)(base + off); off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
+  w.bytes = off;
+  return w;
+}
+
+// ---------------------------------------------------------------- scoring --
+// grid (nbt, Hkv); block 256.  T storage type, D head dim, G query heads per KV head.
+template <typename T, int D, int G>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(
+    const T* __restrict__ K, const T* __restrict__ q_last, int64_t kv_stride, int64_t pos0,
+    int64_t n_tokens, int b, int64_t n_blocks, int64_t nbt, int Hq, double scale,
+    uint8_t* __restrict__ tokrank, double* __restrict__ stats) {
+  constexpr int EPL = Vec16<T>::N;            // elements per lane per load
+  constexpr int LPR = D / EPL;                // lanes per row
+  constexpr int RPW = kWave / LPR;            // rows per wave per load
+  constexpr int RPI = RPW * (kScoreThreads / kWave);   // rows per workgroup iteration
+  __shared__ double xs[G][256];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t j = blockIdx.x;
+  const int kvh = blockIdx.y;
+  const int sub = lane % LPR, rsub = lane / LPR;
+
+  double qv[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float tmp[EPL];
+    Vec16<T>::load(q_last + (size_t)(kvh * G + g) * D + sub * EPL, tmp);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qv[g][e] = (double)tmp[e];
+  }
+
+  const T* Kb = K + ((size_t)kvh * kv_stride + pos0 + j * b) * D;
+  const int64_t left = n_tokens - j * b;                  // tokens from the block start to the end
+  const int rows_here = left < b ? (int)left : b;
+  for (int r0 = 0; r0 < b; r0 += RPI) {
+    const int r = r0 + wv * RPW + rsub;
+    const bool ok = r < rows_here;
+    double acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) acc[g] = 0.0;
+    if (ok) {
+      float kv[EPL];
+      Vec16<T>::load(Kb + (size_t)r * D + sub * EPL, kv);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const double kd = (double)kv[e];
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g] = fma(kd, qv[g][e], acc[g]);
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      double v = group_sum(acc[g], LPR);
+      if (sub == 0 && r < b) xs[g][r] = ok ? v * scale : -INFINITY;
+    }
+  }
+  __syncthreads();
+
+  // block statistics: one wave per head
+  for (int g = wv; g < G; g += kScoreThreads / kWave) {
+    double mx = -INFINITY;
+    for (int i = lane; i < b; i += kWave) mx = fmax(mx, xs[g][i]);
+    mx = group_max(mx, kWave);
+    double e1 = 0.0, e2 = 0.0;
+    for (int i = lane; i < b; i += kWave) {
+      const double e = exp(xs[g][i] - mx);
+      e1 += e;
+      e2 += e * e;
+    }
+    e1 = group_sum(e1, kWave);
+    e2 = group_sum(e2, kWave);
+    if (lane == 0) {
+      double* st = stats + ((size_t)(kvh * G + g) * nbt + j) * 3;
+      st[0] = mx; st[1] = e1; st[2] = e2;
+    }
+  }
+
+  // rank inside the block: number of tokens that beat token i (higher logit, or
+  // the same logit at a lower position).  Full blocks only.
+  if (j < n_blocks) {
+    for (int pi = tid; pi < G * b; pi += kScoreThreads) {
+      const int g = pi / b, i = pi - g * b;
+      const double xi = xs[g][i];
+      int cnt = 0;
+      for (int o = 0; o < b; ++o) {
+        const double xo = xs[g][o];
+        cnt += (xo > xi) || (xo == xi && o < i);
+      }
+      tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)cnt;
+    }
+  }
+}
+
+// ----------------------------------------------------------------- assign --
+struct AssignArgs {
+  int32_t cum[kHeadsPerLaunch][TCA_MAX_COUNTS];   // cumulative Psi counts: rank < cum[e] -> budget 2^e
+  int64_t cap[kHeadsPerLaunch];                   // capacity of the head's region
+};
+
+__device__ __forceinline__ double block_reduce_max(double v, double* red) {
+  v = group_max(v, kWave);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  double r = red[0];
+  for (int i = 1; i < kAssignThreads / kWave; ++i) r = fmax(r, red[i]);
+  return r;
+}
+__device__ __forceinline__ double block_reduce_sum(double v, double* red) {
+  v = group_sum(v, kWave);
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wv] = v;
+  __syncthreads();
+  double r = 0.0;
+  for (int i = 0; i < kAssignThreads / kWave; ++i) r += red[i];
+  return r;
+}
+
+// grid (heads in this launch); block 1024.
+__global__ __launch_bounds__(kAssignThreads) void assign_kernel(
+    AssignArgs args, int head0, int nk, int m, int nbt, double alpha,
+    const double* __restrict__ stats, int32_t* __restrict__ n_rows,
+    int32_t* __restrict__ blk_t, int32_t* __restrict__ blk_dst) {
+  __shared__ double hs[TCA_MAX_BLOCKS];
+  __shared__ int32_t ts[TCA_MAX_BLOCKS];
+  __shared__ double red[kAssignThreads / kWave];
+  __shared__ int32_t scan[kAssignThreads];
+  const int tid = threadIdx.x;
+  const int hl = blockIdx.x, h = head0 + hl;
+  const double* st = stats + (size_t)h * nbt * 3;
+
+  // global normaliser of Eq. 5 over every scored token, tail included
+  double mx = -INFINITY;
+  for (int j = tid; j < nbt; j += kAssignThreads) mx = fmax(mx, st[j * 3]);
+  mx = block_reduce_max(mx, red);
+  double z = 0.0;
+  for (int j = tid; j < nbt; j += kAssignThreads) z += st[j * 3 + 1] * exp(st[j * 3] - mx);
+  z = block_reduce_sum(z, red);
+
+  // Eq. 6
+  for (int j = tid; j < m; j += kAssignThreads) {
+    const double e1 = st[j * 3 + 1], e2 = st[j * 3 + 2];
+    const double mass = e1 * exp(st[j * 3] - mx) / z;
+    const double hhi = e2 / (e1 * e1);
+    hs[j] = (1.0 - alpha) * mass + alpha * (1.0 - hhi);
+  }
+  __syncthreads();
+
+  // rank of each block in ascending h (ties: lower block first), then Eq. 7
+  for (int j = tid; j < m; j += kAssignThreads) {
+    const double hj = hs[j];
+    int rank = 0;
+    for (int o = 0; o < m; ++o) {
+      const double ho = hs[o];
+      rank += (ho < hj) || (ho == hj && o < j);
+    }
+    int e = 0;
+    while (e < nk - 1 && rank >= args.cum[hl][e]) ++e;
+    ts[j] = 1 << e;
+  }
+  __syncthreads();
+
+  // exclusive scan of t_j in block order: thread t owns a run of `per` blocks
+  const int per = (m + kAssignThreads - 1) / kAssignThreads;
+  const int j0 = tid * per;
+  int local = 0;
+  for (int j = j0; j < j0 + per && j < m; ++j) local += ts[j];
+  scan[tid] = local;
+  __syncthreads();
+  for (int o = 1; o < kAssignThreads; o <<= 1) {
+    int v = tid >= o ? scan[tid - o] : 0;
+    __syncthreads();
+    scan[tid] += v;
+    __syncthreads();
+  }
+  const int32_t fill = n_rows[h];
+  int run = fill + scan[tid] - local;
+  for (int j = j0; j < j0 + per && j < m; ++j) {
+    blk_t[(size_t)h * m + j] = ts[j];
+    blk_dst[(size_t)h * m + j] = run;
+    run += ts[j];
+  }
+  __syncthreads();
+  if (tid == kAssignThreads - 1) {
+    int64_t total = (int64_t)fill + scan[tid];
+    if (total > args.cap[hl]) total = args.cap[hl];
+    n_rows[h] = (int32_t)total;
+  }
+}
+
+// ----------------------------------------------------------------- gather --
+// grid (n_blocks, Hq); block 256.
+template <typename T, int D>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, int64_t kv_stride, int64_t pos0, int b,
+    int64_t n_blocks, int G, const uint8_t* __restrict__ tokrank,
+    const int32_t* __restrict__ blk_t, const int32_t* __restrict__ blk_dst,
+    const int64_t* __restrict__ offs_dev, int32_t* __restrict__ idx, T* __restrict__ Kg,
+    T* __restrict__ Vg) {
+  constexpr int EPL = Vec16<T>::N;
+  constexpr int LPR = D / EPL;
+  constexpr int RPI = kGatherThreads / LPR;
+  __shared__ int32_t sel[256];
+  __shared__ int32_t wave_cnt[kGatherThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t j = blockIdx.x;
+  const int h = blockIdx.y, kvh = h / G;
+  const int t = blk_t[(size_t)h * n_blocks + j];
+  const int64_t base = offs_dev[h], cap = offs_dev[h + 1] - base;
+  const int64_t dst0 = blk_dst[(size_t)h * n_blocks + j];
+
+  // compact the kept positions, in ascending position order
+  bool keep = false;
+  if (tid < b) keep = tokrank[(size_t)h * (n_blocks * b) + j * b + tid] < t;
+  const unsigned long long mask = __ballot(keep);
+  if (lane == 0) wave_cnt[wv] = __popcll(mask);
+  __syncthreads();
+  int before = __popcll(mask & ((1ull << lane) - 1ull));
+  for (int w = 0; w < wv; ++w) before += wave_cnt[w];
+  if (keep) sel[before] = tid;
+  __syncthreads();
+
+  const int sub = tid % LPR;
+  for (int k = tid / LPR; k < t; k += RPI) {
+    const int64_t row = dst0 + k;
+    if (row >= cap) break;
+    const int64_t pos = pos0 + j * b + sel[k];
+    const size_t src = ((size_t)kvh * kv_stride + pos) * D + sub * EPL;
+    const size_t dst = (size_t)(base + row) * D + sub * EPL;
+    *reinterpret_cast<uint4*>(Kg + dst) = *reinterpret_cast<const uint4*>(K + src);
+    *reinterpret_cast<uint4*>(Vg + dst) = *reinterpret_cast<const uint4*>(V + src);
+    if (sub == 0) idx[base + row] = (int32_t)pos;
+  }
+}
+
+// offsets of the heads' regions, placed in the workspace by a tiny kernel so
+// that no host->device copy is needed
+struct OffsArgs { int64_t offs[TCA_MAX_HEADS + 1]; };
+__global__ void put_offsets_kernel(OffsArgs a, int n, int64_t* out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = a.offs[i];
+}
+
+template <typename T, int D>
+static void launch_score(int G, dim3 grid, hipStream_t st, const T* K, const T* q, int64_t kv_stride,
+                         int64_t pos0, int64_t n_tokens, int b, int64_t nb, int64_t nbt, int Hq,
+                         double scale, uint8_t* tokrank, double* stats) {
+#define TCA_SCORE_CASE(GG)                                                                      \
+  case GG:                                                                                      \
+    hipLaunchKernelGGL((score_kernel<T, D, GG>), grid, dim3(kScoreThreads), 0, st, K, q,        \
+                       kv_stride, pos0, n_tokens, b, nb, nbt, Hq, scale, tokrank, stats);       \
+    break;
+  switch (G) {
+    TCA_SCORE_CASE(1) TCA_SCORE_CASE(2) TCA_SCORE_CASE(3) TCA_SCORE_CASE(4)
+    TCA_SCORE_CASE(5) TCA_SCORE_CASE(6) TCA_SCORE_CASE(7) TCA_SCORE_CASE(8)
+  }
+#undef TCA_SCORE_CASE
+}
+
+template <typename T, int D>
+static int run_select(const tca_params* prm, const T* q_last, const T* K, const T* V,
+                      int64_t kv_stride, int64_t pos0, int64_t n_tokens, const double* p,
+                      const int64_t* offs, int32_t* n_rows, int32_t* idx, T* Kg, T* Vg, void* ws,
+                      hipStream_t st) {
+  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
+  const int nk = block_log2(b) + 1;
+  const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
+  SelectWs w = carve_select_ws(ws, Hq, b, n_tokens);
+  int64_t* offs_dev = (int64_t*)((char*)ws + w.bytes);
+
+  OffsArgs oa;
+  for (int h = 0; h <= Hq; ++h) oa.offs[h] = offs[h];
+  hipLaunchKernelGGL(put_offsets_kernel, dim3(1), dim3(TCA_MAX_HEADS + 1), 0, st, oa, Hq + 1, offs_dev);
+
+  launch_score<T, D>(G, dim3((unsigned)nbt, Hkv), st, K, q_last, kv_stride, pos0, n_tokens, b, nb, nbt,
+                     Hq, logit_scale(prm), w.tokrank, w.stats);
+  if (nb == 0) return TCA_OK;
+
+  for (int h0 = 0; h0 < Hq; h0 += kHeadsPerLaunch) {
+    const int nh = Hq - h0 < kHeadsPerLaunch ? Hq - h0 : kHeadsPerLaunch;
+    AssignArgs aa;
+    for (int hl = 0; hl < nh; ++hl) {
+      int64_t c[TCA_MAX_COUNTS];
+      psi_counts(nk, nb, p + (size_t)(h0 + hl) * nk, c);
+      int64_t run = 0;
+      for (int e = 0; e < nk; ++e) { run += c[e]; aa.cum[hl][e] = (int32_t)run; }
+      aa.cap[hl] = offs[h0 + hl + 1] - offs[h0 + hl];
+    }
+    hipLaunchKernelGGL(assign_kernel, dim3(nh), dim3(kAssignThreads), 0, st, aa, h0, nk, (int)nb,
+                       (int)nbt, prm->alpha, w.stats, n_rows, w.blk_t, w.blk_dst);
+  }
+  hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hq), dim3(kGatherThreads), 0, st, K, V,
+                     kv_stride, pos0, b, nb, G, w.tokrank, w.blk_t, w.blk_dst, offs_dev, idx, Kg, Vg);
+  return TCA_OK;
+}
+
+}  // namespace tca
+
+using namespace tca;
+
+extern "C" size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens) {
+  if (check_params(prm) != TCA_OK || n_tokens < 0) return 0;
+  SelectWs w = carve_select_ws(nullptr, prm->n_q_heads, prm->block, n_tokens);
+  return w.bytes + align_up((TCA_MAX_HEADS + 1) * sizeof(int64_t), 256);
+}
+
+extern "C" int tca_select(const tca_params* prm, const void* q_last, const void* K, const void* V,
+                          int64_t kv_stride, int64_t pos0, int64_t n_tokens, const double* p,
+                          const int64_t* offs, int32_t* n_rows, int32_t* idx, void* Kg, void* Vg,
+                          void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  if (!q_last || !K || !V || !p || !offs || !n_rows || !idx || !Kg || !Vg || !ws)
+    return fail(TCA_ERR_INVALID, "tca_select: NULL pointer argument");
+  const int b = prm->block, Hq = prm->n_q_heads;
+  if (n_tokens < 0 || pos0 < 0 || pos0 % b != 0 || pos0 + n_tokens > kv_stride)
+    return fail(TCA_ERR_INVALID, "tca_select: pos0=%lld n_tokens=%lld kv_stride=%lld (pos0 must be a "
+                "multiple of b and the range must fit)", (long long)pos0, (long long)n_tokens,
+                (long long)kv_stride);
+  if (pos0 + n_tokens > INT32_MAX) return fail(TCA_ERR_UNSUPPORTED, "positions beyond int32");
+  if (n_tokens / b > TCA_MAX_BLOCKS)
+    return fail(TCA_ERR_UNSUPPORTED, "tca_select: %lld blocks exceed the limit of %d per call",
+                (long long)(n_tokens / b), TCA_MAX_BLOCKS);
+  const int nk = block_log2(b) + 1;
+  for (int h = 0; h < Hq; ++h) {
+    if (!valid_config(p + (size_t)h * nk, nk))
+      return fail(TCA_ERR_INVALID, "tca_select: p[%d] is not a distribution", h);
+    if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_select: offs not ascending at %d", h);
+  }
+  if (offs[0] != 0) return fail(TCA_ERR_INVALID, "tca_select: offs[0] must be 0");
+  if (ws_bytes < tca_select_workspace_bytes(prm, n_tokens) || ((uintptr_t)ws & 255))
+    return fail(TCA_ERR_WORKSPACE, "tca_select: workspace needs %zu bytes, 256-byte aligned",
+                tca_select_workspace_bytes(prm, n_tokens));
+  if (n_tokens == 0) return TCA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const int D = prm->head_dim;
+  if (prm->dtype == TCA_BF16) {
+    using T = bf16_t;
+    rc = D == 128 ? run_select<T, 128>(prm, (const T*)q_last, (const T*)K, (const T*)V, kv_stride, pos0,
+                                       n_tokens, p, offs, n_rows, idx, (T*)Kg, (T*)Vg, ws, st)
+                  : run_select<T, 64>(prm, (const T*)q_last, (const T*)K, (const T*)V, kv_stride, pos0,
+                                      n_tokens, p, offs, n_rows, idx, (T*)Kg, (T*)Vg, ws, st);
+  } else {
+    using T = float;
+    rc = D == 128 ? run_select<T, 128>(prm, (const T*)q_last, (const T*)K, (const T*)V, kv_stride, pos0,
+                                       n_tokens, p, offs, n_rows, idx, (T*)Kg, (T*)Vg, ws, st)
+                  : run_select<T, 64>(prm, (const T*)q_last, (const T*)K, (const T*)V, kv_stride, pos0,
+                                      n_tokens, p, offs, n_rows, idx, (T*)Kg, (T*)Vg, ws, st);
+  }
+  if (rc) return rc;
+  TCA_HIP_CHECK(hipGetLastError());
+  return TCA_OK;
+}

@@ -1,0 +1,82 @@
+"""The C-ABI library loads, exports every symbol include/tca.h declares, and
+its host-side routines (no GPU) agree with the oracle and reject bad input."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import tca_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tca.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tca_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2512_09238_amd.binding as tb
+    names = _declared_symbols()
+    assert "tca_select" in names and "tca_prefill" in names and "tca_decode" in names
+    assert "tca_calibrate_budgets" in names
+    for n in names:
+        assert hasattr(tb.lib, n), n
+        assert n in tb.EXPORTS, f"{n} has no ctypes signature"
+    assert set(tb.EXPORTS) == set(names)
+
+
+def test_host_candidates_match_oracle():
+    import paper_2512_09238_amd.binding as tb
+    for b, M, sigma in [(128, 14, 1.0), (32, 5, 0.7), (4, 3, 1.0), (256, 1, 2.0)]:
+        got = tb.tca_make_candidates(b, M, sigma)
+        np.testing.assert_allclose(got, orc.candidates(b, M, sigma), rtol=1e-13, atol=1e-300)
+    for f in (0.001, 0.05, 0.1, 0.25, 0.5, 0.7, 0.77, 0.99, 1.0, 1.5):
+        for b in (32, 128):
+            np.testing.assert_allclose(tb.tca_config_from_budget(b, 1.0, f), orc.config_from_budget(b, 1.0, f),
+                                       rtol=1e-12, atol=1e-15)
+
+
+def test_host_counts_rows_and_decode_budget_match_oracle():
+    import paper_2512_09238_amd.binding as tb
+    rng = np.random.default_rng(0)
+    b = 128
+    prm = tb.make_params(4, 2, 128, b, 512, tb.TCA_BF16)
+    for m in (0, 1, 7, 256, 1024, 4096):
+        P = np.stack([orc.config_from_budget(b, 1.0, f) for f in rng.uniform(0.02, 0.9, 4)])
+        for p in P:
+            assert list(tb.tca_psi_counts(b, m, p)) == list(orc.psi_counts(m, p))
+            assert tb.tca_decode_budget(b, p) == orc.decode_budget(b, p)
+        total, rows = tb.tca_select_rows(prm, m, P)
+        assert list(rows) == [orc.selected_rows(b, m, p) for p in P] and total == rows.sum()
+    assert list(tb.tca_psi_counts(2, 8, [0.25, 0.75])) == [2, 6]
+
+
+def test_argument_errors_are_codes_not_crashes():
+    import paper_2512_09238_amd.binding as tb
+    with pytest.raises(tb.TcaError) as e:
+        tb.tca_num_counts(48)
+    assert e.value.code == tb.TCA_ERR_UNSUPPORTED
+    with pytest.raises(tb.TcaError) as e:
+        tb.tca_psi_counts(4, 8, [0.5, 0.1, 0.1])
+    assert e.value.code == tb.TCA_ERR_INVALID
+    bad = tb.make_params(6, 4, 128, 128, 4096, tb.TCA_BF16)
+    with pytest.raises(tb.TcaError):
+        tb.tca_select_rows(bad, 4, np.ones((6, 8)) / 8)
+    assert tb.tca_select_workspace_bytes(bad, 1024) == 0
+    for prm in (tb.make_params(4, 2, 96, 128, 4096, tb.TCA_BF16), tb.make_params(4, 2, 128, 128, 100, tb.TCA_BF16),
+                tb.make_params(4, 2, 128, 128, 4096, 7), tb.make_params(256, 256, 128, 128, 4096, 0)):
+        with pytest.raises(tb.TcaError):
+            tb.tca_select_rows(prm, 4, np.ones((prm.n_q_heads, 8)) / 8)
+    # NULL device pointers are rejected before any launch
+    ok = tb.make_params(4, 2, 128, 128, 4096, tb.TCA_BF16)
+    p = np.ones((4, 8)) / 8
+    offs = np.arange(5, dtype=np.int64) * 10
+    rc = tb.lib.tca_select(ctypes.byref(ok), None, None, None, 128, 0, 128, p.ctypes.data_as(tb._dbl_p),
+                           offs.ctypes.data_as(tb._i64_p), None, None, None, None, None, 0, None)
+    assert rc == tb.TCA_ERR_INVALID and b"NULL" in tb.lib.tca_last_error()
+    assert tb.lib.tca_strerror(-3) == b"workspace too small or misaligned"
+    assert tb.tca_select_workspace_bytes(ok, 131072) > 4 * 131072

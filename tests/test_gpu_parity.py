@@ -1,0 +1,247 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Index work is compared exactly (sub-margin ties
+excepted), outputs within max-abs 2e-2 (bf16) / 1e-4 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import tca_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    import paper_2512_09238_amd.binding as tb
+    return tb
+
+
+@pytest.fixture(scope="module")
+def bufs():
+    import paper_2512_09238_amd.buffers as bufs
+    return bufs
+
+
+def budgets_to_configs(tb, b, fracs, sigma=1.0):
+    """GPU side takes its configurations from the library's own host routine,
+    the oracle from its own; the two are compared in tests/test_abi.py."""
+    P_gpu = np.stack([tb.tca_config_from_budget(b, sigma, f) for f in fracs])
+    P_orc = np.stack([orc.config_from_budget(b, sigma, f) for f in fracs])
+    return P_gpu, P_orc
+
+
+SELECT_CASES = [
+    # kind, Hq, Hkv, d, L, dtype, b, w, seed
+    ("centroid", 4, 1, 64, 1024, "f32", 32, 128, 1001),          # config 1
+    ("lowrank", 8, 2, 128, 4096 + 77, "bf16", 128, 512, 11),      # several tiles + ragged tail
+    ("lowrank", 6, 2, 64, 1000, "bf16", 8, 64, 12),               # G=3, small blocks
+    ("centroid", 7, 1, 128, 2048 + 5, "f32", 256, 256, 13),       # G=7, largest block
+    ("lowrank", 2, 2, 128, 300, "bf16", 2, 16, 14),               # smallest block, G=1
+    ("lowrank", 8, 1, 64, 640, "f32", 64, 128, 15),               # G=8
+]
+
+
+@pytest.mark.parametrize("case", SELECT_CASES, ids=lambda c: f"{c[0]}-Hq{c[1]}-Hkv{c[2]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}")
+def test_select_matches_oracle(tb, bufs, case):
+    kind, Hq, Hkv, d, L, dtype, b, w, seed = case
+    print("case", case, flush=True)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    sels = orc.select_all_heads(wl.to_f64(x["Q"][:, L - 1]), wl.to_f64(x["K"]), b, P_orc, 0.5)
+    Kh, Vh = x["K"], x["V"]
+    for h in range(Hq):
+        got = H.head_indices(gb, h)
+        H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}")
+        assert len(got) == gb.offs[h + 1] - gb.offs[h]
+        # compaction is a byte copy of the selected rows
+        g = h // (Hq // Hkv)
+        o = int(gb.offs[h])
+        kg = gb.Kg[o:o + len(got)].cpu()
+        vg = gb.Vg[o:o + len(got)].cpu()
+        kref = bufs.to_device(Kh[g][got], "cpu")
+        vref = bufs.to_device(Vh[g][got], "cpu")
+        assert torch.equal(kg, kref) and torch.equal(vg, vref)
+
+
+def test_select_degenerate_inputs(tb, bufs):
+    # Q = 0: uniform scores, every decision is a tie -> decided by index order
+    Hq, Hkv, d, L, b, w = 2, 1, 64, 256 + 3, 16, 32
+    x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "f32", 21)
+    x["Q"][:] = 0
+    P_gpu, P_orc = budgets_to_configs(tb, b, [0.2, 0.6])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "f32")
+    gb, *_ = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    sels = orc.select_all_heads(wl.to_f64(x["Q"][:, L - 1]), wl.to_f64(x["K"]), b, P_orc, 0.5)
+    for h in range(Hq):
+        assert np.array_equal(H.head_indices(gb, h), sels[h].S)
+    # L < b: nothing selected, nothing written
+    x2 = wl.prefill_inputs("lowrank", Hq, Hkv, d, 10, "f32", 22)
+    gb2, *_ = H.gpu_select(tb, bufs, prm, x2, P_gpu)
+    assert gb2.n_rows.cpu().tolist() == [0, 0]
+    # one-hot at b: everything kept
+    P_full = np.zeros((Hq, 5)); P_full[:, -1] = 1
+    gb3, *_ = H.gpu_select(tb, bufs, prm, x, P_full)
+    for h in range(Hq):
+        assert np.array_equal(H.head_indices(gb3, h), np.arange((L // b) * b))
+    # determinism: same call twice gives identical bytes
+    gb4, *_ = H.gpu_select(tb, bufs, prm, x, P_full)
+    assert torch.equal(gb3.idx, gb4.idx) and torch.equal(gb3.Kg, gb4.Kg)
+
+
+PREFILL_CASES = [
+    ("centroid", 4, 1, 64, 1024, "f32", 32, 128, 1001),          # config 1, every row
+    ("lowrank", 8, 2, 128, 1500, "bf16", 128, 256, 31),
+    ("lowrank", 4, 2, 64, 700, "bf16", 16, 64, 32),
+    ("centroid", 2, 2, 128, 513, "f32", 64, 128, 33),
+]
+
+
+@pytest.mark.parametrize("case", PREFILL_CASES, ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}-w{c[7]}")
+def test_prefill_matches_oracle_every_row(tb, bufs, case):
+    kind, Hq, Hkv, d, L, dtype, b, w, seed = case
+    print("case", case, flush=True)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = [0.25] * Hq if seed == 1001 else wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    O = torch.full_like(Qd, float("nan"))
+    lse = torch.full((Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, lse, ws)
+    torch.cuda.synchronize()
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    for h in range(Hq):
+        got = H.head_indices(gb, h)
+        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+            g = h // (Hq // Hkv)
+            Oref[h] = orc.tca_attention(Qf[h], Kf[g], Vf[g], got, w)
+    Og = bufs.to_host_f64(O)
+    assert not np.isnan(Og).any(), "some output rows were never written"
+    err = np.abs(Og - Oref).max()
+    print("max abs err", err, flush=True)
+    assert err <= H.TOL[dtype]
+    # log-sum-exp of the visible logits, for a few rows
+    lg = lse.cpu().numpy()
+    for h in (0, Hq - 1):
+        g = h // (Hq // Hkv)
+        for i in (0, w - 1, w, L // 2, L - 1):
+            T = orc.visible_keys(i, sels[h].S if np.array_equal(H.head_indices(gb, h), sels[h].S) else H.head_indices(gb, h), w)
+            lref = np.log(np.exp(Kf[g][T] @ Qf[h, i] / np.sqrt(d)).sum())
+            assert abs(lg[h, i] - lref) <= (5e-2 if dtype == "bf16" else 1e-3)
+
+
+def test_prefill_full_budget_is_dense_and_chunked_queries(tb, bufs):
+    """One-hot at k=b keeps everything: the result is dense causal attention
+    (Eq. 1).  Also runs the queries in two calls (q_pos0 > 0)."""
+    Hq, Hkv, d, L, b, w = 2, 1, 64, 384, 32, 64
+    x = wl.prefill_inputs("centroid", Hq, Hkv, d, L, "f32", 41)
+    P = np.zeros((Hq, 6)); P[:, -1] = 1
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "f32")
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P)
+    O = torch.empty_like(Qd)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L))
+    half = 200
+    Qa, Qb = Qd[:, :half].contiguous(), Qd[:, half:].contiguous()
+    Oa, Ob = torch.empty_like(Qa), torch.empty_like(Qb)
+    tb.tca_prefill(prm, Qa, 0, half, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, Oa, None, ws)
+    tb.tca_prefill(prm, Qb, half, L - half, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, Ob, None, ws)
+    torch.cuda.synchronize()
+    Og = np.concatenate([bufs.to_host_f64(Oa), bufs.to_host_f64(Ob)], axis=1)
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    for h in range(Hq):
+        dense = orc.dense_causal_attention(Qf[h], Kf[0], Vf[0])
+        assert np.abs(Og[h] - dense).max() <= 1e-4
+
+
+DECODE_CASES = [
+    # Hq, Hkv, d, L, dtype, b, w, steps, seed
+    (4, 1, 64, 1024, "f32", 32, 128, 40, 1001),      # config 1 + decode across a block completion
+    (8, 2, 128, 1500 + 100, "bf16", 128, 256, 140, 51),
+    (4, 4, 64, 90, "bf16", 8, 32, 30, 52),           # shorter than... several completions, L < 3w
+]
+
+
+@pytest.mark.parametrize("case", DECODE_CASES, ids=lambda c: f"Hq{c[0]}-d{c[2]}-L{c[3]}-{c[4]}-b{c[5]}-w{c[6]}-n{c[7]}")
+def test_decode_after_prefill_matches_oracle(tb, bufs, case):
+    Hq, Hkv, d, L, dtype, b, w, steps, seed = case
+    print("case", case, flush=True)
+    kind = "centroid" if dtype == "f32" else "lowrank"
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    # capacity: prefill rows + rows added by blocks completed while decoding
+    _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
+    extra = np.array([tb.tca_decode_budget(b, p) for p in P_gpu]) * ((L + steps) // b - L // b + 1)
+    cache = bufs.DecodeCache(prm, 1, rows + extra)
+    Kd, Vd, Qd = bufs.to_device(x["K"]), bufs.to_device(x["V"]), bufs.to_device(x["Q"])
+    ws = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P_gpu, cache.offs, cache.n_rows[0],
+                  cache.idx[0], cache.Kg[0], cache.Vg[0], ws)
+    tb.tca_cache_load_window(prm, cache.view, 0, Kd, Vd, L, L)
+    torch.cuda.synchronize()
+    assert int(cache.length[0].item()) == L
+
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    sels = orc.select_all_heads(Qf[:, L - 1], Kf, b, P_orc, 0.5)
+    for h in range(Hq):
+        o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
+        assert np.array_equal(cache.idx[0, o:o + n].cpu().numpy(), sels[h].S)
+    ocache = orc.cache_after_prefill(Kf, Vf, sels)
+
+    dec = wl.decode_inputs(Hq, Hkv, d, steps, dtype, seed + 2, batch=1, gains=x["gains"])
+    qd, kd, vd = (bufs.to_device(dec[k]) for k in ("q", "k_new", "v_new"))
+    wsd = bufs.workspace(tb.tca_decode_workspace_bytes(prm, 1, cache.max_head_rows))
+    O = torch.empty(steps, 1, Hq, d, dtype=qd.dtype, device="cuda")
+    for s in range(steps):                      # queued back to back, no host sync in between
+        tb.tca_decode(prm, cache.view, cache.offs, qd[s], kd[s], vd[s], P_gpu, O[s], wsd)
+    torch.cuda.synchronize()
+    Og = bufs.to_host_f64(O)
+    worst = 0.0
+    for s in range(steps):
+        ref = orc.decode_step(ocache, wl.to_f64(dec["q"][s, 0]), wl.to_f64(dec["k_new"][s, 0]),
+                              wl.to_f64(dec["v_new"][s, 0]), b, w, P_orc)
+        worst = max(worst, np.abs(Og[s, 0] - ref).max())
+    print("max abs err over steps", worst, flush=True)
+    assert worst <= H.TOL[dtype]
+    assert int(cache.length[0].item()) == L + steps
+    # the global subsets after decoding: prefill set + per-block top-t, bit-exact
+    for h in range(Hq):
+        o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
+        assert np.array_equal(cache.idx[0, o:o + n].cpu().numpy(), ocache.S[h]), f"head {h}"
+        g = h // (Hq // Hkv)
+        kref = torch.from_numpy(ocache.K[g][ocache.S[h]]).to(cache.Kg.dtype)
+        assert torch.equal(cache.Kg[0, o:o + n].cpu(), kref)
+
+
+def test_decode_from_empty_cache_batched(tb, bufs):
+    """Batch of 3 sequences decoded from scratch (no prefill): ring wrap-around,
+    block completions on every sequence, per-sequence state stays separate."""
+    Hq, Hkv, d, b, w, steps, B = 4, 2, 64, 8, 16, 50, 3
+    P_gpu, P_orc = budgets_to_configs(tb, b, [0.2, 0.4, 0.6, 0.9])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "f32")
+    cap = np.array([tb.tca_decode_budget(b, p) for p in P_gpu]) * (steps // b + 1)
+    cache = bufs.DecodeCache(prm, B, cap)
+    dec = wl.decode_inputs(Hq, Hkv, d, steps, "f32", 61, batch=B)
+    qd, kd, vd = (bufs.to_device(dec[k]) for k in ("q", "k_new", "v_new"))
+    wsd = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache.max_head_rows))
+    O = torch.empty(steps, B, Hq, d, dtype=torch.float32, device="cuda")
+    for s in range(steps):
+        tb.tca_decode(prm, cache.view, cache.offs, qd[s], kd[s], vd[s], P_gpu, O[s], wsd)
+    torch.cuda.synchronize()
+    Og = bufs.to_host_f64(O)
+    for sq in range(B):
+        oc = orc.HeadCache(S=[np.zeros(0, np.int64) for _ in range(Hq)])
+        for s in range(steps):
+            ref = orc.decode_step(oc, dec["q"][s, sq], dec["k_new"][s, sq], dec["v_new"][s, sq], b, w, P_orc)
+            assert np.abs(Og[s, sq] - ref).max() <= 1e-4, (sq, s)
+        for h in range(Hq):
+            o, n = int(cache.offs[h]), int(cache.n_rows[sq, h].item())
+            assert np.array_equal(cache.idx[sq, o:o + n].cpu().numpy(), oc.S[h])
