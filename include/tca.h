@@ -107,7 +107,8 @@ int64_t tca_select_rows(const tca_params* prm, int64_t n_blocks, const double* p
 int tca_decode_budget(int b, const double* p);
 
 size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens);
-size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries);
+/* cap_rows: total rows of the flat global buffer (offs[Hq]). */
+size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows);
 /* max_head_rows: the largest capacity of one head's region, max_h (offs[h+1]-offs[h]). */
 size_t tca_decode_workspace_bytes(const tca_params* prm, int batch, int64_t max_head_rows);
 size_t tca_calibrate_workspace_bytes(const tca_params* prm, int64_t L_cal, int M);

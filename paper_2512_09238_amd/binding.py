@@ -54,7 +54,7 @@ EXPORTS = {
     "tca_select_rows": (C.c_int64, [_P(tca_params), C.c_int64, _dbl_p, _i64_p]),
     "tca_decode_budget": (C.c_int, [C.c_int, _dbl_p]),
     "tca_select_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64]),
-    "tca_prefill_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64]),
+    "tca_prefill_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64, C.c_int64]),
     "tca_decode_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int, C.c_int64]),
     "tca_calibrate_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64, C.c_int]),
     "tca_select": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
@@ -154,8 +154,8 @@ def tca_select_workspace_bytes(prm, n_tokens: int) -> int:
     return int(lib.tca_select_workspace_bytes(C.byref(prm), n_tokens))
 
 
-def tca_prefill_workspace_bytes(prm, n_queries: int) -> int:
-    return int(lib.tca_prefill_workspace_bytes(C.byref(prm), n_queries))
+def tca_prefill_workspace_bytes(prm, n_queries: int, cap_rows: int) -> int:
+    return int(lib.tca_prefill_workspace_bytes(C.byref(prm), n_queries, cap_rows))
 
 
 def tca_decode_workspace_bytes(prm, batch: int, max_head_rows: int) -> int:

@@ -15,7 +15,7 @@ int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64
                         const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st);
 
 // bf16 MFMA flash kernel.
-size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries);
+size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows);
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
                         const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
                         const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,

@@ -7,9 +7,10 @@
 
 using namespace tca;
 
-extern "C" size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries) {
-  if (check_params(prm) != TCA_OK || n_queries < 0) return 0;
-  return prefill_mfma_workspace_bytes(prm, n_queries);
+extern "C" size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows) {
+  if (check_params(prm) != TCA_OK || n_queries < 0 || cap_rows < 0) return 0;
+  if (prm->dtype != TCA_BF16) return 0;
+  return prefill_mfma_workspace_bytes(prm, n_queries, cap_rows);
 }
 
 extern "C" int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_queries,
@@ -27,7 +28,7 @@ extern "C" int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0,
   if (offs[0] != 0) return fail(TCA_ERR_INVALID, "tca_prefill: offs[0] must be 0");
   for (int h = 0; h < prm->n_q_heads; ++h)
     if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_prefill: offs not ascending at %d", h);
-  const size_t need = tca_prefill_workspace_bytes(prm, n_queries);
+  const size_t need = tca_prefill_workspace_bytes(prm, n_queries, offs[prm->n_q_heads]);
   if (need && (!ws || ws_bytes < need || ((uintptr_t)ws & 255)))
     return fail(TCA_ERR_WORKSPACE, "tca_prefill: workspace needs %zu bytes, 256-byte aligned", need);
   if (n_queries == 0) return TCA_OK;

@@ -1,18 +1,407 @@
-// bf16 prefill attention (Eq. 2).  Placeholder dispatch: the row kernel.
+// bf16 MFMA flash-attention prefill over the global and local subsets (Eq. 2;
+// Alg. 2 line 7) for gfx950.
+//
+// Work decomposition.  One workgroup = 4 wavefronts = one tile of BM = 128*QT
+// consecutive queries of one query head; wave v owns 32*QT of them.  The
+// workgroup walks 64-key tiles: first the head's compacted global rows (tiles
+// of the head's region of Kg), then the dense keys of the sliding window
+// (absolute 64-key tiles of K).  Visibility is a prefix test in both parts:
+//   global row g of the region : g  < nvis(i) = #{idx <= i-w}   (idx ascends)
+//   dense key j                : i-w < j <= i
+// so only boundary tiles evaluate a mask.
+//
+// MFMA mapping (v_mfma_f32_32x32x16_bf16, 64 lanes; lane = (hh = lane/32, c = lane%32)):
+//   S^T = K Q^T  : A = K rows (key = c, 8 consecutive d), B = Q (query = c, same 8 d),
+//                  C[key = 8*(r/4)+4*hh+r%4][query = c].  A lane therefore holds 16
+//                  keys of ONE query per 32-key sub-tile: the softmax max/sum are
+//                  in-register reductions plus one exchange between the two halves.
+//   O^T = V^T P^T: B = P^T taken straight from the C registers of S^T (registers
+//                  8g..8g+7 -> one bf16x8), A = V^T (d = c, the same 8 keys).  V^T
+//                  tiles are produced once per call by a transposing pre-pass into
+//                  the workspace, with the 64 keys of a tile stored in the order
+//                  the C registers hold them, so the A operand is one 16-byte LDS read.
+//   O^T accumulators: C[d = 32*s + 8*(r/4)+4*hh+r%4][query = c]: every register of
+//                  a lane belongs to the same query, so rescaling is a per-lane scalar.
+//
+// LDS: K tile [64][D] with 16 bytes of row padding, V^T tile [D][64] with 16
+// bytes of row padding: both make the 16-lane b128 reads conflict-free.
 #include <hip/hip_runtime.h>
 
 #include "tca_prefill.h"
 
 namespace tca {
 
-size_t prefill_mfma_workspace_bytes(const tca_params*, int64_t) { return 0; }
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+constexpr int kBN = 64;              // keys per tile
+constexpr int kPfThreads = 256;
+
+struct PrefillHeads {
+  int64_t offs[TCA_MAX_HEADS + 1];      // row offsets of the heads' regions
+  int32_t tile_off[TCA_MAX_HEADS + 1];  // V^T tile offsets of the heads' regions
+};
+
+// position p (0..63) inside a stored V^T tile -> key (0..63) of the tile
+__host__ __device__ inline int vt_key_of_pos(int p) {
+  const int sub = p >> 5, q = p & 31;
+  const int g = q >> 4, hh = (q >> 3) & 1, e = q & 7;
+  return sub * 32 + 16 * g + 8 * (e >> 2) + 4 * hh + (e & 3);
+}
+
+// ---------------------------------------------------------------- pre-pass --
+// Transposes 64-row tiles of a row-major [rows, D] bf16 matrix into
+// [D][64] tiles (keys permuted by vt_key_of_pos); rows >= n_valid become zero.
+// grid (tiles, groups); block 256.
+template <int D>
+__global__ __launch_bounds__(256) void transpose_tiles_kernel(
+    const uint16_t* __restrict__ src, int64_t group_stride_rows, const int32_t* group_valid,
+    int64_t valid_all, int64_t first_row, uint16_t* __restrict__ dst, int tiles_per_group,
+    PrefillHeads ph, int mode) {
+  // mode 0: global regions (group = query head; rows from ph.offs, valid rows from group_valid)
+  // mode 1: dense K/V (group = KV head; absolute rows first_row + 64*tile, valid while < valid_all)
+  __shared__ uint16_t tile[kBN][D + 8];
+  const int g = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
+  int64_t row0;
+  int64_t n_valid;
+  size_t out_tile;
+  if (mode == 0) {
+    const int64_t cap = ph.offs[g + 1] - ph.offs[g];
+    const int ntile = (int)((cap + kBN - 1) / kBN);
+    if (t >= ntile) return;
+    row0 = ph.offs[g] + (int64_t)t * kBN;
+    n_valid = (int64_t)group_valid[g] - (int64_t)t * kBN;
+    out_tile = (size_t)ph.tile_off[g] + t;
+  } else {
+    row0 = (int64_t)g * group_stride_rows + first_row + (int64_t)t * kBN;
+    n_valid = valid_all - (first_row + (int64_t)t * kBN);
+    out_tile = (size_t)g * tiles_per_group + t;
+  }
+  constexpr int CPR = D / 8;                       // 16-byte chunks per row
+  for (int c = tid; c < kBN * CPR; c += 256) {
+    const int r = c / CPR, part = c - r * CPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < n_valid) v = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + r) * D + part * 8);
+    *reinterpret_cast<uint4*>(&tile[r][part * 8]) = v;
+  }
+  __syncthreads();
+  uint16_t* out = dst + out_tile * (size_t)(D * kBN);
+  for (int c = tid; c < D * (kBN / 8); c += 256) {
+    const int dd = c / (kBN / 8), part = c - dd * (kBN / 8);
+    uint16_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[vt_key_of_pos(part * 8 + e)][dd];
+    uint4 pk;
+    pk.x = v[0] | ((uint32_t)v[1] << 16);
+    pk.y = v[2] | ((uint32_t)v[3] << 16);
+    pk.z = v[4] | ((uint32_t)v[5] << 16);
+    pk.w = v[6] | ((uint32_t)v[7] << 16);
+    *reinterpret_cast<uint4*>(out + (size_t)dd * kBN + part * 8) = pk;
+  }
+}
+
+// ------------------------------------------------------------- main kernel --
+__device__ __forceinline__ int64_t i64min(int64_t a, int64_t b) { return a < b ? a : b; }
+
+__device__ __forceinline__ int count_le_i32(const int32_t* idx, int n, int64_t bound) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)idx[mid] <= bound) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+template <int D, int QT>
+__global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
+    const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
+    int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
+    const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
+    int64_t dense_tile0, int dense_tiles, PrefillHeads ph, int Hq, int G, int w, float scale,
+    uint16_t* __restrict__ O, float* __restrict__ lse) {
+  constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
+  constexpr int DS = D / 32;             // 32-row slices of O^T
+  constexpr int BMW = 32 * QT;           // queries per wave
+  constexpr int BM = 4 * BMW;            // queries per workgroup
+  constexpr int KSTR = D * 2 + 16;       // bytes per K row in LDS
+  constexpr int VSTR = kBN * 2 + 16;     // bytes per V^T row in LDS
+  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kBN * KSTR];
+  __shared__ __attribute__((aligned(16))) unsigned char lds_v[D * VSTR];
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int hh = lane >> 5, c = lane & 31;
+  const int n_qt = (int)((n_queries + BM - 1) / BM);
+  const int bid = blockIdx.x;
+  const int h = bid % Hq;
+  const int qtile = n_qt - 1 - bid / Hq;           // longest tiles first
+  const int kvh = h / G;
+  const int64_t r0 = (int64_t)qtile * BM;          // first query row of the workgroup
+  const int64_t last_row = n_queries - 1;
+  const float sl2e = scale * 1.4426950408889634f;
+
+  // ---- per-lane query state
+  int64_t qpos[QT];
+  int nvis[QT];
+  bf16x8_t qf[QT][KK];
+  const int64_t base = ph.offs[h];
+  const int nr = n_rows[h];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    int64_t r = r0 + wv * BMW + t * 32 + c;
+    if (r > last_row) r = last_row;                 // clamped rows compute a duplicate; never stored
+    qpos[t] = q_pos0 + r;
+    nvis[t] = count_le_i32(idx + base, nr, qpos[t] - w);
+    const uint16_t* qrow = Q + ((size_t)h * n_queries + r) * D;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      qf[t][kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
+  }
+  // wave-level visibility bounds (queries ascend with the lane index c; clamped rows repeat the last)
+  const int64_t wave_first = q_pos0 + i64min(r0 + wv * BMW, last_row);
+  const int64_t wave_last = q_pos0 + i64min(r0 + wv * BMW + BMW - 1, last_row);
+  const int64_t wg_last = q_pos0 + i64min(r0 + BM - 1, last_row);
+  const int64_t wg_first = q_pos0 + r0;
+  const int nv_wave_lo = count_le_i32(idx + base, nr, wave_first - w);   // visible to every query of the wave
+  const int nv_wave_hi = count_le_i32(idx + base, nr, wave_last - w);    // visible to at least one
+  const int nv_wg_hi = count_le_i32(idx + base, nr, wg_last - w);
+  const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
+  const int64_t win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
+  const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
+  const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
+
+  f32x16_t o[QT][DS];
+  float m[QT], l[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m[t] = -INFINITY;
+    l[t] = 0.f;
+#pragma unroll
+    for (int s = 0; s < DS; ++s)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
+  }
+
+  for (int it = 0; it < n_tiles; ++it) {
+    const bool is_glob = it < n_gt;
+    // ---- stage the K tile and the V^T tile
+    const uint16_t* ksrc;
+    const uint16_t* vsrc;
+    int64_t krow_max;            // last row that may be read, relative to ksrc
+    int64_t key0;                // global: first region row of the tile; dense: first absolute key
+    if (is_glob) {
+      key0 = (int64_t)it * kBN;
+      ksrc = Kg + (size_t)(base + key0) * D;
+      krow_max = (int64_t)nr - 1 - key0;
+      vsrc = Vgt + ((size_t)ph.tile_off[h] + it) * (size_t)(D * kBN);
+    } else {
+      const int64_t at = wt0 + (it - n_gt);
+      key0 = at * kBN;
+      ksrc = K + ((size_t)kvh * kv_stride + key0) * D;
+      krow_max = q_pos0 + last_row - key0;
+      vsrc = Vt + ((size_t)kvh * dense_tiles + (at - dense_tile0)) * (size_t)(D * kBN);
+    }
+    __syncthreads();             // previous tile fully consumed
+    constexpr int CPR = D / 8;
+    for (int ch = tid; ch < kBN * CPR; ch += kPfThreads) {
+      int r = ch / CPR;
+      const int part = ch - r * CPR;
+      const int rr = r > krow_max ? (int)krow_max : r;      // stay inside the buffer; such keys are masked
+      const uint4 v = *reinterpret_cast<const uint4*>(ksrc + (size_t)rr * D + part * 8);
+      *reinterpret_cast<uint4*>(lds_k + r * KSTR + part * 16) = v;
+    }
+    for (int ch = tid; ch < D * (kBN / 8); ch += kPfThreads) {
+      const int dd = ch / (kBN / 8), part = ch - dd * (kBN / 8);
+      const uint4 v = *reinterpret_cast<const uint4*>(vsrc + (size_t)dd * kBN + part * 8);
+      *reinterpret_cast<uint4*>(lds_v + dd * VSTR + part * 16) = v;
+    }
+    __syncthreads();
+
+    // ---- does this wave have anything to do in the tile, and does it need a mask?
+    bool active, masked;
+    if (is_glob) {
+      active = key0 < nv_wave_hi;
+      masked = key0 + kBN > nv_wave_lo;
+    } else {
+      active = key0 <= wave_last && key0 + kBN - 1 > wave_first - w;
+      masked = !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
+    }
+    if (!active) continue;
+
+    // ---- S^T = K Q^T for the 64 keys (two 32-key sub-tiles)
+    f32x16_t s[QT][2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[t][sub][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lds_k + (sub * 32 + c) * KSTR + (kk * 16 + hh * 8) * 2);
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+          s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][kk], s[t][sub], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax per query (lane column), P^T packed to bf16
+    bf16x8_t pf[QT][2][2];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+      if (masked) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int64_t key = key0 + sub * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            const bool vis = is_glob ? key < nvis[t] : (key <= qpos[t] && key > qpos[t] - w);
+            if (!vis) s[t][sub][r] = -INFINITY;
+          }
+      }
+      float mx = s[t][0][0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[t][0][r]);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][1][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m[t], mx);
+      if (__any(m_new > m[t])) {
+        const float alpha = (m_new > m[t]) ? __builtin_amdgcn_exp2f((m[t] - m_new) * sl2e) : 1.f;
+        l[t] *= alpha;
+#pragma unroll
+        for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[t][sl][r] *= alpha;
+        m[t] = m_new;
+      }
+      const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
+      float ls = 0.f;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          bf16x8_t pk;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[t][sub][8 * g + e], sl2e, -mb));
+            ls += p;
+            pk[e] = (__bf16)p;
+          }
+          pf[t][sub][g] = pk;
+        }
+      l[t] += ls;
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(lds_v + (sl * 32 + c) * VSTR + (sub * 32 + g * 16 + hh * 8) * 2);
+#pragma unroll
+          for (int t = 0; t < QT; ++t)
+            o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][sub][g], o[t][sl], 0, 0, 0);
+        }
+  }
+
+  // ---- normalise and store
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int64_t r = r0 + wv * BMW + t * 32 + c;
+    const float lt = l[t] + __shfl_xor(l[t], 32, 64);
+    if (r > last_row) continue;
+    const float inv = 1.f / lt;
+    uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
+#pragma unroll
+    for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        uint2 pk;
+        pk.x = f32_to_bf16(o[t][sl][4 * q4] * inv) | ((uint32_t)f32_to_bf16(o[t][sl][4 * q4 + 1] * inv) << 16);
+        pk.y = f32_to_bf16(o[t][sl][4 * q4 + 2] * inv) | ((uint32_t)f32_to_bf16(o[t][sl][4 * q4 + 3] * inv) << 16);
+        *reinterpret_cast<uint2*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
+      }
+    if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m[t] * scale + __logf(lt);
+  }
+}
+
+// ------------------------------------------------------------------ host side --
+struct MfmaWs {
+  uint16_t* Vgt;       // [g_tiles][D][64]
+  uint16_t* Vt;        // [Hkv][dense_tiles][D][64]
+  size_t bytes;
+};
+
+static int64_t max_region_tiles(int Hq, int64_t cap_rows) { return (cap_rows + kBN - 1) / kBN + Hq; }
+static int64_t max_dense_tiles(int64_t n_queries, int w) { return (n_queries + w) / kBN + 2; }
+
+static MfmaWs carve_mfma_ws(void* ws, const tca_params* prm, int64_t g_tiles, int64_t d_tiles) {
+  MfmaWs m;
+  char* b = (char*)ws;
+  size_t off = 0;
+  const size_t tile_bytes = (size_t)prm->head_dim * kBN * 2;
+  m.Vgt = (uint16_t*)(b + off); off = align_up(off + (size_t)g_tiles * tile_bytes, 256);
+  m.Vt = (uint16_t*)(b + off);  off = align_up(off + (size_t)prm->n_kv_heads * d_tiles * tile_bytes, 256);
+  m.bytes = off;
+  return m;
+}
+
+size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows) {
+  return carve_mfma_ws(nullptr, prm, max_region_tiles(prm->n_q_heads, cap_rows),
+                       max_dense_tiles(n_queries, prm->window)).bytes;
+}
+
+template <int D>
+static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, int64_t n_queries,
+                     const uint16_t* K, const uint16_t* V, int64_t kv_stride, const int32_t* idx,
+                     const uint16_t* Kg, const uint16_t* Vg, const int64_t* offs, const int32_t* n_rows,
+                     uint16_t* O, float* lse, void* ws, hipStream_t st) {
+  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, w = prm->window;
+  PrefillHeads ph;
+  int32_t run = 0;
+  int max_tiles = 0;
+  for (int h = 0; h < Hq; ++h) {
+    ph.offs[h] = offs[h];
+    ph.tile_off[h] = run;
+    const int nt = (int)((offs[h + 1] - offs[h] + kBN - 1) / kBN);
+    run += nt;
+    if (nt > max_tiles) max_tiles = nt;
+  }
+  ph.offs[Hq] = offs[Hq];
+  ph.tile_off[Hq] = run;
+  const int64_t win_lo = q_pos0 - w + 1 > 0 ? q_pos0 - w + 1 : 0;
+  const int64_t dt0 = win_lo / kBN, dt1 = (q_pos0 + n_queries - 1) / kBN;
+  const int d_tiles = (int)(dt1 - dt0 + 1);
+  MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hq, offs[Hq]), max_dense_tiles(n_queries, w));
+
+  if (max_tiles > 0)
+    hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hq), dim3(256), 0, st, Vg, (int64_t)0,
+                       n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0);
+  hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
+                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
+
+  constexpr int QT = 1;
+  constexpr int BM = 128 * QT;
+  const int n_qt = (int)((n_queries + BM - 1) / BM);
+  hipLaunchKernelGGL((prefill_mfma_kernel<D, QT>), dim3((unsigned)n_qt * Hq), dim3(kPfThreads), 0, st, Q,
+                     q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
+                     Hq / Hkv, w, (float)logit_scale(prm), O, lse);
+}
 
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
                         const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
                         const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,
-                        bf16_t* O, float* lse, void*, hipStream_t st) {
-  return launch_prefill_rows<bf16_t>(prm, Q, q_pos0, n_queries, K, V, kv_stride, idx, Kg, Vg, offs, n_rows,
-                                     O, lse, st);
+                        bf16_t* O, float* lse, void* ws, hipStream_t st) {
+  auto u = [](const bf16_t* p) { return reinterpret_cast<const uint16_t*>(p); };
+  if (prm->head_dim == 128)
+    run_mfma<128>(prm, u(Q), q_pos0, n_queries, u(K), u(V), kv_stride, idx, u(Kg), u(Vg), offs, n_rows,
+                  reinterpret_cast<uint16_t*>(O), lse, ws, st);
+  else
+    run_mfma<64>(prm, u(Q), q_pos0, n_queries, u(K), u(V), kv_stride, idx, u(Kg), u(Vg), offs, n_rows,
+                 reinterpret_cast<uint16_t*>(O), lse, ws, st);
+  return TCA_OK;
 }
 
 }  // namespace tca
