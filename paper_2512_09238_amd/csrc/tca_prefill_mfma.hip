@@ -23,8 +23,9 @@
 //   O^T accumulators: C[d = 32*s + 8*(r/4)+4*hh+r%4][query = c]: every register of
 //                  a lane belongs to the same query, so rescaling is a per-lane scalar.
 //
-// LDS: K tile [64][D] with 16 bytes of row padding, V^T tile [D][64] with 16
-// bytes of row padding: both make the 16-lane b128 reads conflict-free.
+// Pipeline: two LDS stages of {K tile [64][D], V^T tile [D][64]} with XOR-swizzled
+// 16-byte chunks (conflict-free b128 reads without padding); the tile after next
+// is in flight in registers while the current one is computed; one barrier per tile.
 #include <hip/hip_runtime.h>
 
 #include "tca_prefill.h"
@@ -112,8 +113,83 @@ __device__ __forceinline__ int count_le_i32(const int32_t* idx, int n, int64_t b
   return lo;
 }
 
+// Cross-half exchange: returns max over the two 32-lane halves, in every lane.
+__device__ __forceinline__ float half_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Where the 64-key tiles of one workgroup come from: first n_gt tiles of the
+// head's compacted region, then absolute dense tiles wt0, wt0+1, ...
+struct TileWalk {
+  int n_gt;
+  int64_t wt0, base, vgt_tile0, kv_stride, last_pos, dense_tile0;
+  int nr, kvh, dense_tiles;
+  __device__ __forceinline__ int64_t key0(int it) const {
+    return it < n_gt ? (int64_t)it * kBN : (wt0 + (it - n_gt)) * kBN;
+  }
+};
+
+// LDS byte offset of 16-byte chunk `ch` of K row r / V^T row dd (XOR swizzle, no padding)
+template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
+  const int swz = (D / 8 == 16) ? (r & 15) : ((r >> 1) & 7);
+  return r * (D * 2) + ((ch ^ swz) << 4);
+}
+__device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + ((ch ^ ((dd >> 1) & 7)) << 4); }
+
+template <int D, int KLD, int VLD>
+__device__ __forceinline__ void load_tile(const TileWalk& tw, int it, int tid, const uint16_t* __restrict__ Kg,
+                                          const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
+                                          const uint16_t* __restrict__ Vt, uint4 (&kreg)[KLD], uint4 (&vreg)[VLD]) {
+  constexpr int CPR = D / 8;
+  const uint16_t* ksrc;
+  const uint16_t* vsrc;
+  int64_t krow_max;                       // last row that may be read, relative to ksrc
+  const int64_t key0 = tw.key0(it);
+  if (it < tw.n_gt) {
+    ksrc = Kg + (size_t)(tw.base + key0) * D;
+    krow_max = (int64_t)tw.nr - 1 - key0;
+    vsrc = Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN);
+  } else {
+    ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
+    krow_max = tw.last_pos - key0;
+    vsrc = Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+  }
+#pragma unroll
+  for (int i = 0; i < KLD; ++i) {
+    const int id = tid + i * kPfThreads;
+    const int r = id / CPR, ch = id % CPR;
+    const int rr = r > krow_max ? (int)krow_max : r;    // stay inside the buffer; such keys are masked
+    kreg[i] = *reinterpret_cast<const uint4*>(ksrc + (size_t)rr * D + ch * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < VLD; ++i)
+    vreg[i] = *reinterpret_cast<const uint4*>(vsrc + (size_t)(tid + i * kPfThreads) * 8);
+}
+
+template <int D, int KLD, int VLD>
+__device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const uint4 (&kreg)[KLD],
+                                           const uint4 (&vreg)[VLD]) {
+  constexpr int CPR = D / 8;
+  unsigned char* vb = stage + kBN * D * 2;
+#pragma unroll
+  for (int i = 0; i < KLD; ++i) {
+    const int id = tid + i * kPfThreads;
+    *reinterpret_cast<uint4*>(stage + k_off<D>(id / CPR, id % CPR)) = kreg[i];
+  }
+#pragma unroll
+  for (int i = 0; i < VLD; ++i) {
+    const int id = tid + i * kPfThreads;
+    *reinterpret_cast<uint4*>(vb + v_off(id >> 3, id & 7)) = vreg[i];
+  }
+}
+
 template <int D, int QT>
-__global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
+__global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
@@ -123,10 +199,15 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
   constexpr int DS = D / 32;             // 32-row slices of O^T
   constexpr int BMW = 32 * QT;           // queries per wave
   constexpr int BM = 4 * BMW;            // queries per workgroup
-  constexpr int KSTR = D * 2 + 16;       // bytes per K row in LDS
-  constexpr int VSTR = kBN * 2 + 16;     // bytes per V^T row in LDS
-  __shared__ __attribute__((aligned(16))) unsigned char lds_k[kBN * KSTR];
-  __shared__ __attribute__((aligned(16))) unsigned char lds_v[D * VSTR];
+  constexpr int CPR = D / 8;             // 16-byte chunks per K row
+  constexpr int KBYTES = kBN * D * 2;    // K tile
+  constexpr int VBYTES = D * kBN * 2;    // V^T tile
+  constexpr int KLD = kBN * CPR / kPfThreads;   // 16-byte loads per thread per K tile
+  constexpr int VLD = D * 8 / kPfThreads;       // ... per V^T tile
+  // Two stages of {K tile, V^T tile}.  Rows are not padded; the 16-byte chunk
+  // index is XOR-swizzled with the row so that the b128 reads of 16 consecutive
+  // rows at one chunk column fall into distinct banks.
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (KBYTES + VBYTES)];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int hh = lane >> 5, c = lane & 31;
@@ -145,6 +226,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
   bf16x8_t qf[QT][KK];
   const int64_t base = ph.offs[h];
   const int nr = n_rows[h];
+  const size_t vgt_tile0 = (size_t)ph.tile_off[h];
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     int64_t r = r0 + wv * BMW + t * 32 + c;
@@ -169,6 +251,13 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
   const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
   const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
 
+  // ---- staging: global -> registers -> LDS stage (tile after next is in flight in registers)
+  uint4 kreg[KLD], vreg[VLD];
+  TileWalk tw;
+  tw.n_gt = n_gt; tw.wt0 = wt0; tw.base = base; tw.nr = nr; tw.vgt_tile0 = vgt_tile0; tw.kvh = kvh;
+  tw.kv_stride = kv_stride; tw.last_pos = q_pos0 + last_row; tw.dense_tiles = dense_tiles;
+  tw.dense_tile0 = dense_tile0;
+
   f32x16_t o[QT][DS];
   float m[QT], l[QT];
 #pragma unroll
@@ -181,40 +270,22 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
       for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
   }
 
+  load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, kreg, vreg);
+  store_tile<D>(lds, tid, kreg, vreg);
+  if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, kreg, vreg);
+
   for (int it = 0; it < n_tiles; ++it) {
-    const bool is_glob = it < n_gt;
-    // ---- stage the K tile and the V^T tile
-    const uint16_t* ksrc;
-    const uint16_t* vsrc;
-    int64_t krow_max;            // last row that may be read, relative to ksrc
-    int64_t key0;                // global: first region row of the tile; dense: first absolute key
-    if (is_glob) {
-      key0 = (int64_t)it * kBN;
-      ksrc = Kg + (size_t)(base + key0) * D;
-      krow_max = (int64_t)nr - 1 - key0;
-      vsrc = Vgt + ((size_t)ph.tile_off[h] + it) * (size_t)(D * kBN);
-    } else {
-      const int64_t at = wt0 + (it - n_gt);
-      key0 = at * kBN;
-      ksrc = K + ((size_t)kvh * kv_stride + key0) * D;
-      krow_max = q_pos0 + last_row - key0;
-      vsrc = Vt + ((size_t)kvh * dense_tiles + (at - dense_tile0)) * (size_t)(D * kBN);
-    }
-    __syncthreads();             // previous tile fully consumed
-    constexpr int CPR = D / 8;
-    for (int ch = tid; ch < kBN * CPR; ch += kPfThreads) {
-      int r = ch / CPR;
-      const int part = ch - r * CPR;
-      const int rr = r > krow_max ? (int)krow_max : r;      // stay inside the buffer; such keys are masked
-      const uint4 v = *reinterpret_cast<const uint4*>(ksrc + (size_t)rr * D + part * 8);
-      *reinterpret_cast<uint4*>(lds_k + r * KSTR + part * 16) = v;
-    }
-    for (int ch = tid; ch < D * (kBN / 8); ch += kPfThreads) {
-      const int dd = ch / (kBN / 8), part = ch - dd * (kBN / 8);
-      const uint4 v = *reinterpret_cast<const uint4*>(vsrc + (size_t)dd * kBN + part * 8);
-      *reinterpret_cast<uint4*>(lds_v + dd * VSTR + part * 16) = v;
-    }
+    // stage it&1 holds tile `it` once every wave has passed this barrier; the other
+    // stage was last read while computing tile it-1, which every wave has finished.
     __syncthreads();
+    if (it + 1 < n_tiles) {
+      store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, kreg, vreg);
+      if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, kreg, vreg);
+    }
+    const bool is_glob = it < n_gt;
+    const int64_t key0 = tw.key0(it);
+    const unsigned char* kb = lds + (it & 1) * (KBYTES + VBYTES);
+    const unsigned char* vb = kb + KBYTES;
 
     // ---- does this wave have anything to do in the tile, and does it need a mask?
     bool active, masked;
@@ -237,7 +308,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
         for (int r = 0; r < 16; ++r) s[t][sub][r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(lds_k + (sub * 32 + c) * KSTR + (kk * 16 + hh * 8) * 2);
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>(sub * 32 + c, 2 * kk + hh));
 #pragma unroll
         for (int t = 0; t < QT; ++t)
           s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][kk], s[t][sub], 0, 0, 0);
@@ -263,7 +334,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[t][0][r]);
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][1][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = half_max(mx);
       const float m_new = fmaxf(m[t], mx);
       if (__any(m_new > m[t])) {
         const float alpha = (m_new > m[t]) ? __builtin_amdgcn_exp2f((m[t] - m_new) * sl2e) : 1.f;
@@ -299,7 +370,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
-          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(lds_v + (sl * 32 + c) * VSTR + (sub * 32 + g * 16 + hh * 8) * 2);
+          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(vb + v_off(sl * 32 + c, sub * 4 + g * 2 + hh));
 #pragma unroll
           for (int t = 0; t < QT; ++t)
             o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][sub][g], o[t][sl], 0, 0, 0);
@@ -310,7 +381,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(
 #pragma unroll
   for (int t = 0; t < QT; ++t) {
     const int64_t r = r0 + wv * BMW + t * 32 + c;
-    const float lt = l[t] + __shfl_xor(l[t], 32, 64);
+    const float lt = half_sum(l[t]);
     if (r > last_row) continue;
     const float inv = 1.f / lt;
     uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
