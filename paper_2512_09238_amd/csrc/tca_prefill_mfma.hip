@@ -31,9 +31,16 @@
 #include "tca_prefill.h"
 
 namespace tca {
+#if defined(EXP_NOSTAGE) || defined(EXP_BARRIERONLY)
+#define EXP_NOSTAGE 1
+#define EXP_STAGE_SKIP 1
+#else
+#define EXP_STAGE_SKIP 0
+#endif
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 
 constexpr int kBN = 64;              // keys per tile
 constexpr int kPfThreads = 256;
@@ -188,8 +195,36 @@ __device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const 
   }
 }
 
+// Pulls the 128-byte lines of a future tile into L2: each thread reads one dword
+// of one line (first half of the threads the K tile, second half the V^T tile).
+template <int D>
+__device__ __forceinline__ uint32_t touch_tile(const TileWalk& tw, int it, int tid, const uint16_t* __restrict__ Kg,
+                                               const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
+                                               const uint16_t* __restrict__ Vt) {
+  constexpr int LINES = kBN * D * 2 / 128;          // lines per tile (K and V^T tiles have the same size)
+  const int64_t key0 = tw.key0(it);
+  const int line = tid % LINES;
+  const uint16_t* p;
+  if (tid < LINES || kPfThreads < 2 * LINES) {
+    int64_t r = (int64_t)line * 64 / D;             // row holding this line (64 elements per line)
+    const int col = (line * 64) % D;
+    if (it < tw.n_gt) {
+      const int64_t mx = (int64_t)tw.nr - 1 - key0;
+      p = Kg + (size_t)(tw.base + key0 + (r > mx ? mx : r)) * D + col;
+    } else {
+      const int64_t mx = tw.last_pos - key0;
+      p = K + ((size_t)tw.kvh * tw.kv_stride + key0 + (r > mx ? mx : r)) * D + col;
+    }
+  } else {
+    const uint16_t* vsrc = it < tw.n_gt ? Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN)
+                                        : Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+    p = vsrc + (size_t)line * 64;
+  }
+  return *reinterpret_cast<const uint32_t*>(p);
+}
+
 template <int D, int QT>
-__global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
+__global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
@@ -209,7 +244,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
   // rows at one chunk column fall into distinct banks.
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (KBYTES + VBYTES)];
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index, scalar
   const int hh = lane >> 5, c = lane & 31;
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   const int bid = blockIdx.x;
@@ -243,9 +279,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
   const int64_t wave_last = q_pos0 + i64min(r0 + wv * BMW + BMW - 1, last_row);
   const int64_t wg_last = q_pos0 + i64min(r0 + BM - 1, last_row);
   const int64_t wg_first = q_pos0 + r0;
-  const int nv_wave_lo = count_le_i32(idx + base, nr, wave_first - w);   // visible to every query of the wave
-  const int nv_wave_hi = count_le_i32(idx + base, nr, wave_last - w);    // visible to at least one
-  const int nv_wg_hi = count_le_i32(idx + base, nr, wg_last - w);
+  // the searches below take wave-uniform arguments; readfirstlane keeps the results scalar
+  const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wave_first - w));  // visible to every query of the wave
+  const int nv_wave_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wave_last - w));   // visible to at least one
+  const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wg_last - w));
   const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
   const int64_t win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
   const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
@@ -270,6 +307,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
       for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
   }
 
+  uint32_t touch0 = 0, touch1 = 0;
+  constexpr int kAhead = 4;                        // tiles between the L2 touch and the compute
   load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, kreg, vreg);
   store_tile<D>(lds, tid, kreg, vreg);
   if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, kreg, vreg);
@@ -277,11 +316,30 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
   for (int it = 0; it < n_tiles; ++it) {
     // stage it&1 holds tile `it` once every wave has passed this barrier; the other
     // stage was last read while computing tile it-1, which every wave has finished.
+#if !defined(EXP_NOSTAGE) && !defined(EXP_NOBARRIER)
     __syncthreads();
-    if (it + 1 < n_tiles) {
+#endif
+#ifdef EXP_BARRIERONLY
+    __syncthreads();
+#endif
+    if (it + 1 < n_tiles && !(EXP_STAGE_SKIP && it > 0)) {
+#ifdef EXP_LOADSONLY
+#pragma unroll
+      for (int i = 0; i < KLD; ++i) asm volatile("" ::"v"(kreg[i]));
+#pragma unroll
+      for (int i = 0; i < VLD; ++i) asm volatile("" ::"v"(vreg[i]));
+#else
       store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, kreg, vreg);
+#endif
+#ifndef EXP_STORESONLY
       if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, kreg, vreg);
+#endif
     }
+#ifdef EXP_TOUCH
+    asm volatile("" ::"v"(touch0));                // retire the touch issued two tiles ago
+    touch0 = touch1;
+    if (it + kAhead < n_tiles) touch1 = touch_tile<D>(tw, it + kAhead, tid, Kg, K, Vgt, Vt);
+#endif
     const bool is_glob = it < n_gt;
     const int64_t key0 = tw.key0(it);
     const unsigned char* kb = lds + (it & 1) * (KBYTES + VBYTES);
@@ -311,7 +369,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
         const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>(sub * 32 + c, 2 * kk + hh));
 #pragma unroll
         for (int t = 0; t < QT; ++t)
+#ifdef EXP_NOS
+          s[t][sub][kk] += (float)kf[0] * (float)qf[t][kk][1];
+#else
           s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][kk], s[t][sub], 0, 0, 0);
+#endif
       }
     }
 
@@ -320,13 +382,24 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
       if (masked) {
+        // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
+        int lo, hi;
+        if (is_glob) {
+          lo = 0;
+          hi = (int)i64min((int64_t)nvis[t] - key0, kBN);
+        } else {
+          const int64_t l64 = qpos[t] - w + 1 - key0, h64 = qpos[t] + 1 - key0;
+          lo = (int)(l64 < 0 ? 0 : (l64 > kBN ? kBN : l64));
+          hi = (int)(h64 < 0 ? 0 : (h64 > kBN ? kBN : h64));
+        }
+        const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
+        const int rel0 = 4 * hh - lo;
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int64_t key = key0 + sub * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-            const bool vis = is_glob ? key < nvis[t] : (key <= qpos[t] && key > qpos[t] - w);
-            if (!vis) s[t][sub][r] = -INFINITY;
+            const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
+            s[t][sub][r] = kr < span ? s[t][sub][r] : -INFINITY;
           }
       }
       float mx = s[t][0][0];
@@ -354,7 +427,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
           bf16x8_t pk;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
+#ifdef EXP_NOEXP
+            const float p = fmaf(s[t][sub][8 * g + e], sl2e, -mb);
+#else
             const float p = __builtin_amdgcn_exp2f(fmaf(s[t][sub][8 * g + e], sl2e, -mb));
+#endif
             ls += p;
             pk[e] = (__bf16)p;
           }
@@ -363,6 +440,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
       l[t] += ls;
     }
 
+#ifndef EXP_NOPV
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int sl = 0; sl < DS; ++sl)
@@ -375,6 +453,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
           for (int t = 0; t < QT; ++t)
             o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][sub][g], o[t][sl], 0, 0, 0);
         }
+#else
+#pragma unroll
+    for (int t = 0; t < QT; ++t) { o[t][0][0] += (float)pf[t][0][0][0] + (float)pf[t][1][1][7] + (float)pf[t][0][1][3] + (float)pf[t][1][0][5]; }
+#endif
   }
 
   // ---- normalise and store
@@ -389,10 +471,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_mfma_kernel(
     for (int sl = 0; sl < DS; ++sl)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        uint2 pk;
-        pk.x = f32_to_bf16(o[t][sl][4 * q4] * inv) | ((uint32_t)f32_to_bf16(o[t][sl][4 * q4 + 1] * inv) << 16);
-        pk.y = f32_to_bf16(o[t][sl][4 * q4 + 2] * inv) | ((uint32_t)f32_to_bf16(o[t][sl][4 * q4 + 3] * inv) << 16);
-        *reinterpret_cast<uint2*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
+        bf16x4_t pk;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[t][sl][4 * q4 + j] * inv);
+        *reinterpret_cast<bf16x4_t*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
       }
     if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m[t] * scale + __logf(lt);
   }
@@ -453,7 +535,10 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
 
-  constexpr int QT = 1;
+#ifndef EXP_QT
+#define EXP_QT 1
+#endif
+  constexpr int QT = EXP_QT;
   constexpr int BM = 128 * QT;
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   hipLaunchKernelGGL((prefill_mfma_kernel<D, QT>), dim3((unsigned)n_qt * Hq), dim3(kPfThreads), 0, st, Q,
