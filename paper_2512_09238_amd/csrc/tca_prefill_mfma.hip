@@ -44,6 +44,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 
 constexpr int kBN = 64;              // keys per tile
 constexpr int kPfThreads = 256;
+constexpr int kFragAhead = 4;        // LDS fragment reads in flight ahead of the MFMA that uses them
 
 struct PrefillHeads {
   int64_t offs[TCA_MAX_HEADS + 1];      // row offsets of the heads' regions
@@ -148,11 +149,20 @@ template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
 }
 __device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + ((ch ^ ((dd >> 1) & 7)) << 4); }
 
-template <int D, int KLD, int VLD>
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// One tile in flight: up to four 16-byte chunks of K and of V^T per thread, in
+// named registers (arrays here end up in scratch or LDS instead of VGPRs).
+struct TileRegs {
+  u32x4_t k0, k1, k2, k3, v0, v1, v2, v3;
+};
+
+template <int D>
 __device__ __forceinline__ void load_tile(const TileWalk& tw, int it, int tid, const uint16_t* __restrict__ Kg,
                                           const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
-                                          const uint16_t* __restrict__ Vt, uint4 (&kreg)[KLD], uint4 (&vreg)[VLD]) {
+                                          const uint16_t* __restrict__ Vt, TileRegs& tr) {
   constexpr int CPR = D / 8;
+  constexpr int NLD = kBN * CPR / kPfThreads;   // chunks per thread per tile (K and V^T alike): 4 or 2
   const uint16_t* ksrc;
   const uint16_t* vsrc;
   int64_t krow_max;                       // last row that may be read, relative to ksrc
@@ -166,33 +176,38 @@ __device__ __forceinline__ void load_tile(const TileWalk& tw, int it, int tid, c
     krow_max = tw.last_pos - key0;
     vsrc = Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
   }
-#pragma unroll
-  for (int i = 0; i < KLD; ++i) {
+  auto kld = [&](int i) -> u32x4_t {
     const int id = tid + i * kPfThreads;
     const int r = id / CPR, ch = id % CPR;
     const int rr = r > krow_max ? (int)krow_max : r;    // stay inside the buffer; such keys are masked
-    kreg[i] = *reinterpret_cast<const uint4*>(ksrc + (size_t)rr * D + ch * 8);
-  }
-#pragma unroll
-  for (int i = 0; i < VLD; ++i)
-    vreg[i] = *reinterpret_cast<const uint4*>(vsrc + (size_t)(tid + i * kPfThreads) * 8);
+    return *reinterpret_cast<const u32x4_t*>(ksrc + (size_t)rr * D + ch * 8);
+  };
+  auto vld = [&](int i) -> u32x4_t {
+    return *reinterpret_cast<const u32x4_t*>(vsrc + (size_t)(tid + i * kPfThreads) * 8);
+  };
+  tr.k0 = kld(0); tr.k1 = kld(1);
+  if constexpr (NLD > 2) { tr.k2 = kld(2); tr.k3 = kld(3); }
+  tr.v0 = vld(0); tr.v1 = vld(1);
+  if constexpr (NLD > 2) { tr.v2 = vld(2); tr.v3 = vld(3); }
 }
 
-template <int D, int KLD, int VLD>
-__device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const uint4 (&kreg)[KLD],
-                                           const uint4 (&vreg)[VLD]) {
+template <int D>
+__device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const TileRegs& tr) {
   constexpr int CPR = D / 8;
+  constexpr int NLD = kBN * CPR / kPfThreads;
   unsigned char* vb = stage + kBN * D * 2;
-#pragma unroll
-  for (int i = 0; i < KLD; ++i) {
+  auto kst = [&](int i, u32x4_t x) {
     const int id = tid + i * kPfThreads;
-    *reinterpret_cast<uint4*>(stage + k_off<D>(id / CPR, id % CPR)) = kreg[i];
-  }
-#pragma unroll
-  for (int i = 0; i < VLD; ++i) {
+    *reinterpret_cast<u32x4_t*>(stage + k_off<D>(id / CPR, id % CPR)) = x;
+  };
+  auto vst = [&](int i, u32x4_t x) {
     const int id = tid + i * kPfThreads;
-    *reinterpret_cast<uint4*>(vb + v_off(id >> 3, id & 7)) = vreg[i];
-  }
+    *reinterpret_cast<u32x4_t*>(vb + v_off(id >> 3, id & 7)) = x;
+  };
+  kst(0, tr.k0); kst(1, tr.k1);
+  if constexpr (NLD > 2) { kst(2, tr.k2); kst(3, tr.k3); }
+  vst(0, tr.v0); vst(1, tr.v1);
+  if constexpr (NLD > 2) { vst(2, tr.v2); vst(3, tr.v3); }
 }
 
 // Pulls the 128-byte lines of a future tile into L2: each thread reads one dword
@@ -237,8 +252,6 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
   constexpr int CPR = D / 8;             // 16-byte chunks per K row
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
-  constexpr int KLD = kBN * CPR / kPfThreads;   // 16-byte loads per thread per K tile
-  constexpr int VLD = D * 8 / kPfThreads;       // ... per V^T tile
   // Two stages of {K tile, V^T tile}.  Rows are not padded; the 16-byte chunk
   // index is XOR-swizzled with the row so that the b128 reads of 16 consecutive
   // rows at one chunk column fall into distinct banks.
@@ -289,7 +302,7 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
   const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
 
   // ---- staging: global -> registers -> LDS stage (tile after next is in flight in registers)
-  uint4 kreg[KLD], vreg[VLD];
+  TileRegs tr;
   TileWalk tw;
   tw.n_gt = n_gt; tw.wt0 = wt0; tw.base = base; tw.nr = nr; tw.vgt_tile0 = vgt_tile0; tw.kvh = kvh;
   tw.kv_stride = kv_stride; tw.last_pos = q_pos0 + last_row; tw.dense_tiles = dense_tiles;
@@ -309,9 +322,9 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
 
   uint32_t touch0 = 0, touch1 = 0;
   constexpr int kAhead = 4;                        // tiles between the L2 touch and the compute
-  load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, kreg, vreg);
-  store_tile<D>(lds, tid, kreg, vreg);
-  if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, kreg, vreg);
+  load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, tr);
+  store_tile<D>(lds, tid, tr);
+  if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, tr);
 
   for (int it = 0; it < n_tiles; ++it) {
     // stage it&1 holds tile `it` once every wave has passed this barrier; the other
@@ -323,17 +336,8 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
     __syncthreads();
 #endif
     if (it + 1 < n_tiles && !(EXP_STAGE_SKIP && it > 0)) {
-#ifdef EXP_LOADSONLY
-#pragma unroll
-      for (int i = 0; i < KLD; ++i) asm volatile("" ::"v"(kreg[i]));
-#pragma unroll
-      for (int i = 0; i < VLD; ++i) asm volatile("" ::"v"(vreg[i]));
-#else
-      store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, kreg, vreg);
-#endif
-#ifndef EXP_STORESONLY
-      if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, kreg, vreg);
-#endif
+      store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, tr);
+      if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, tr);
     }
 #ifdef EXP_TOUCH
     asm volatile("" ::"v"(touch0));                // retire the touch issued two tiles ago
@@ -356,26 +360,41 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
     }
     if (!active) continue;
 
-    // ---- S^T = K Q^T for the 64 keys (two 32-key sub-tiles)
+    // ---- S^T = K Q^T for the 64 keys (two 32-key sub-tiles).  The two accumulation
+    // chains alternate and the K fragments are read four MFMAs ahead.
     f32x16_t s[QT][2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int t = 0; t < QT; ++t)
 #pragma unroll
-      for (int t = 0; t < QT; ++t)
+      for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[t][sub][r] = 0.f;
+    {
+      bf16x8_t fr[kFragAhead];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>(sub * 32 + c, 2 * kk + hh));
+      for (int i = 0; i < kFragAhead; ++i)
+        fr[i] = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>((i & 1) * 32 + c, 2 * (i >> 1) + hh));
+#pragma unroll
+      for (int i = 0; i < 2 * KK; ++i) {
+        const int sub = i & 1, kk = i >> 1;
 #pragma unroll
         for (int t = 0; t < QT; ++t)
 #ifdef EXP_NOS
-          s[t][sub][kk] += (float)kf[0] * (float)qf[t][kk][1];
+          s[t][sub][kk] += (float)fr[i % kFragAhead][0] * (float)qf[t][kk][1];
 #else
-          s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][kk], s[t][sub], 0, 0, 0);
+          s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[t][kk], s[t][sub], 0, 0, 0);
 #endif
+        if (i + kFragAhead < 2 * KK) {
+          const int j = i + kFragAhead;
+          fr[i % kFragAhead] = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>((j & 1) * 32 + c, 2 * (j >> 1) + hh));
+        }
       }
     }
+    // first V^T fragments: issued now, consumed after the softmax
+    bf16x8_t vfr[kFragAhead];
+#pragma unroll
+    for (int j = 0; j < kFragAhead; ++j)
+      vfr[j] = *reinterpret_cast<const bf16x8_t*>(vb + v_off((j % DS) * 32 + c, (j / DS) * 2 + hh));
 
     // ---- online softmax per query (lane column), P^T packed to bf16
     bf16x8_t pf[QT][2][2];
@@ -402,11 +421,13 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
             s[t][sub][r] = kr < span ? s[t][sub][r] : -INFINITY;
           }
       }
-      float mx = s[t][0][0];
+      float mx;
+      {
+        float m8[8];
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[t][0][r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][1][r]);
+        for (int r = 0; r < 8; ++r) m8[r] = fmaxf(fmaxf(s[t][0][r], s[t][0][r + 8]), fmaxf(s[t][1][r], s[t][1][r + 8]));
+        mx = fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7])));
+      }
       mx = half_max(mx);
       const float m_new = fmaxf(m[t], mx);
       if (__any(m_new > m[t])) {
@@ -419,7 +440,7 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
         m[t] = m_new;
       }
       const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
-      float ls = 0.f;
+      float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -432,27 +453,27 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
 #else
             const float p = __builtin_amdgcn_exp2f(fmaf(s[t][sub][8 * g + e], sl2e, -mb));
 #endif
-            ls += p;
+            ls[e & 3] += p;
             pk[e] = (__bf16)p;
           }
           pf[t][sub][g] = pk;
         }
-      l[t] += ls;
+      l[t] += (ls[0] + ls[1]) + (ls[2] + ls[3]);
     }
 
 #ifndef EXP_NOPV
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T: the DS accumulation chains alternate; V^T fragments are read ahead
 #pragma unroll
-    for (int sl = 0; sl < DS; ++sl)
+    for (int j = 0; j < 4 * DS; ++j) {
+      const int sl = j % DS, sg = j / DS;           // sg = sub*2 + g: 16 keys
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(vb + v_off(sl * 32 + c, sub * 4 + g * 2 + hh));
-#pragma unroll
-          for (int t = 0; t < QT; ++t)
-            o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][sub][g], o[t][sl], 0, 0, 0);
-        }
+      for (int t = 0; t < QT; ++t)
+        o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[t][sg >> 1][sg & 1], o[t][sl], 0, 0, 0);
+      if (j + kFragAhead < 4 * DS) {
+        const int n = j + kFragAhead;
+        vfr[j % kFragAhead] = *reinterpret_cast<const bf16x8_t*>(vb + v_off((n % DS) * 32 + c, (n / DS) * 2 + hh));
+      }
+    }
 #else
 #pragma unroll
     for (int t = 0; t < QT; ++t) { o[t][0][0] += (float)pf[t][0][0][0] + (float)pf[t][1][1][7] + (float)pf[t][0][1][3] + (float)pf[t][1][0][5]; }
