@@ -18,6 +18,7 @@
 
 #include "tca_common.h"
 #include "tca_device.h"
+#include "tca_select.h"
 
 namespace tca {
 
@@ -26,15 +27,7 @@ constexpr int kAssignThreads = 1024;
 constexpr int kGatherThreads = 256;
 constexpr int kHeadsPerLaunch = 32;
 
-struct SelectWs {
-  uint8_t* tokrank;   // [Hq][n_blocks*b]
-  double* stats;      // [Hq][nbt][3]
-  int32_t* blk_t;     // [Hq][n_blocks]
-  int32_t* blk_dst;   // [Hq][n_blocks] row inside the head's region
-  size_t bytes;
-};
-
-static SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
+SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
   int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
   size_t off = 0;
   SelectWs w;
@@ -304,13 +297,53 @@ static void launch_score(int G, dim3 grid, hipStream_t st, const T* K, const T* 
 #undef TCA_SCORE_CASE
 }
 
+// Stage 1 of selection for callers outside this file (calibration): logits, block
+// statistics and in-block ranks of tokens [0, n_tokens) of K scored by q_last.
+void select_score_stage(const tca_params* prm, const void* q_last, const void* K, int64_t kv_stride,
+                        int64_t n_tokens, const SelectWs& w, hipStream_t st) {
+  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
+  const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
+  const dim3 grid((unsigned)nbt, Hkv);
+  const double sc = logit_scale(prm);
+  if (prm->dtype == TCA_BF16) {
+    using T = bf16_t;
+    if (prm->head_dim == 128) launch_score<T, 128>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+    else launch_score<T, 64>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+  } else {
+    using T = float;
+    if (prm->head_dim == 128) launch_score<T, 128>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+    else launch_score<T, 64>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+  }
+}
+
+// Stage 2: block metric, ranking and budgets for one configuration per head.
+// blk_t / blk_dst: [Hq][nb]; n_rows: [Hq] fill counters (in/out); cap: per-head capacity.
+void select_assign_stage(const tca_params* prm, int64_t n_tokens, const double* p, const int64_t* cap,
+                         const double* stats, int32_t* n_rows, int32_t* blk_t, int32_t* blk_dst,
+                         hipStream_t st) {
+  const int Hq = prm->n_q_heads, b = prm->block, nk = block_log2(b) + 1;
+  const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
+  for (int h0 = 0; h0 < Hq; h0 += kHeadsPerLaunch) {
+    const int nh = Hq - h0 < kHeadsPerLaunch ? Hq - h0 : kHeadsPerLaunch;
+    AssignArgs aa;
+    for (int hl = 0; hl < nh; ++hl) {
+      int64_t c[TCA_MAX_COUNTS];
+      psi_counts(nk, nb, p + (size_t)(h0 + hl) * nk, c);
+      int64_t run = 0;
+      for (int e = 0; e < nk; ++e) { run += c[e]; aa.cum[hl][e] = (int32_t)run; }
+      aa.cap[hl] = cap[h0 + hl];
+    }
+    hipLaunchKernelGGL(assign_kernel, dim3(nh), dim3(kAssignThreads), 0, st, aa, h0, nk, (int)nb,
+                       (int)nbt, prm->alpha, stats, n_rows, blk_t, blk_dst);
+  }
+}
+
 template <typename T, int D>
 static int run_select(const tca_params* prm, const T* q_last, const T* K, const T* V,
                       int64_t kv_stride, int64_t pos0, int64_t n_tokens, const double* p,
                       const int64_t* offs, int32_t* n_rows, int32_t* idx, T* Kg, T* Vg, void* ws,
                       hipStream_t st) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
-  const int nk = block_log2(b) + 1;
   const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
   SelectWs w = carve_select_ws(ws, Hq, b, n_tokens);
   int64_t* offs_dev = (int64_t*)((char*)ws + w.bytes);
@@ -323,19 +356,9 @@ static int run_select(const tca_params* prm, const T* q_last, const T* K, const 
                      Hq, logit_scale(prm), w.tokrank, w.stats);
   if (nb == 0) return TCA_OK;
 
-  for (int h0 = 0; h0 < Hq; h0 += kHeadsPerLaunch) {
-    const int nh = Hq - h0 < kHeadsPerLaunch ? Hq - h0 : kHeadsPerLaunch;
-    AssignArgs aa;
-    for (int hl = 0; hl < nh; ++hl) {
-      int64_t c[TCA_MAX_COUNTS];
-      psi_counts(nk, nb, p + (size_t)(h0 + hl) * nk, c);
-      int64_t run = 0;
-      for (int e = 0; e < nk; ++e) { run += c[e]; aa.cum[hl][e] = (int32_t)run; }
-      aa.cap[hl] = offs[h0 + hl + 1] - offs[h0 + hl];
-    }
-    hipLaunchKernelGGL(assign_kernel, dim3(nh), dim3(kAssignThreads), 0, st, aa, h0, nk, (int)nb,
-                       (int)nbt, prm->alpha, w.stats, n_rows, w.blk_t, w.blk_dst);
-  }
+  int64_t cap[TCA_MAX_HEADS];
+  for (int h = 0; h < Hq; ++h) cap[h] = offs[h + 1] - offs[h];
+  select_assign_stage(prm, n_tokens, p, cap, w.stats, n_rows, w.blk_t, w.blk_dst, st);
   hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hq), dim3(kGatherThreads), 0, st, K, V,
                      kv_stride, pos0, b, nb, G, w.tokrank, w.blk_t, w.blk_dst, offs_dev, idx, Kg, Vg);
   return TCA_OK;

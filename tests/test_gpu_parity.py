@@ -249,3 +249,38 @@ def test_decode_from_empty_cache_batched(tb, bufs):
         for h in range(Hq):
             o, n = int(cache.offs[h]), int(cache.n_rows[sq, h].item())
             assert np.array_equal(cache.idx[sq, o:o + n].cpu().numpy(), oc.S[h])
+
+
+CALIB_CASES = [
+    # kind, Hq, Hkv, d, L, dtype, b, M, seed
+    ("lowrank", 4, 2, 64, 512, "f32", 16, 6, 71),
+    ("lowrank", 8, 2, 128, 640 + 13, "bf16", 32, 14, 72),
+    ("centroid", 2, 1, 128, 300, "bf16", 128, 5, 73),
+]
+
+
+@pytest.mark.parametrize("case", CALIB_CASES, ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}-M{c[7]}")
+def test_calibrate_budgets_matches_oracle(tb, bufs, case):
+    """Alg. 1: a_i (Eq. 4) and |S_i| of every candidate, and the chosen candidate."""
+    kind, Hq, Hkv, d, L, dtype, b, M, seed = case
+    print("case", case, flush=True)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    prm = H.params_for(tb, Hq, Hkv, d, b, b, dtype)
+    Qd, Kd = bufs.to_device(x["Q"]), bufs.to_device(x["K"])
+    ws = bufs.workspace(tb.tca_calibrate_workspace_bytes(prm, L, M))
+    Qf, Kf = wl.to_f64(x["Q"]), wl.to_f64(x["K"])
+    ref0 = orc.calibrate(Qf, Kf, b, M, 1.0, 0.0, 0.5)
+    a_ref = np.stack([c.a for c in ref0])
+    n_ref = np.stack([c.n for c in ref0])
+    taus = [0.0, 1e9, float(np.median(a_ref)), 0.9]
+    for tau in taus:
+        got = tb.tca_calibrate_budgets(prm, Qd, Kd, L, M, 1.0, tau, ws)
+        np.testing.assert_allclose(got["a"], a_ref, rtol=1e-9, atol=1e-12)
+        assert np.array_equal(got["n"], n_ref)
+        ref = orc.calibrate(Qf, Kf, b, M, 1.0, tau, 0.5)
+        for h in range(Hq):
+            if np.min(np.abs(a_ref[h] - tau)) > 1e-9 * max(1.0, abs(tau)):     # decision margin
+                assert got["cand_idx"][h] == ref[h].index, (tau, h)
+                assert bool(got["fallback"][h]) == ref[h].fallback
+                np.testing.assert_allclose(got["p_star"][h], ref[h].p, rtol=1e-12, atol=1e-15)
+    assert np.all(tb.tca_calibrate_budgets(prm, Qd, Kd, L, M, 1.0, 1e9, ws)["fallback"] == 1)
