@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM bytes per launch of prefill_mfma_kernel on the default workload, from the rocprofv3
+# --pmc runs summarised in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB)
+PROFILED_PREFILL_TRAFFIC_BYTES = (5.156e7 * 2.0 + 1.0486e6) * 1024
 
 
 def log(*a):
@@ -227,7 +230,9 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--calibrate", action="store_true", default=False)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--calibrate", action="store_true", default=True)
     ap.add_argument("--no-calibrate", dest="calibrate", action="store_false")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -242,6 +247,16 @@ def main():
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
     log(f"[bench] device {props.name}: {props.multi_processor_count} CUs")
+
+    if args.copy_probe:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        b_ = torch.empty_like(a)
+        a.fill_(1)
+        torch.cuda.synchronize()
+        b_.copy_(a)                      # the plain copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b_
+        torch.cuda.empty_cache()
 
     res, host = bench_prefill(args, tb, bufs, wl, torch)
     cpu = None
@@ -267,7 +282,8 @@ def main():
         },
         "roofline": {
             "kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": res["tflops"], "peak": PEAK_BF16_TFLOPS,
-            "unit": "TFLOP/s", "frac": res["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+            "unit": "TFLOP/s", "frac": res["tflops"] / PEAK_BF16_TFLOPS,
+            "traffic": PROFILED_PREFILL_TRAFFIC_BYTES if (res["L"] == 131072 and args.calibrate) else None,
             "flops_per_launch": res["flops"], "visible_pairs": res["pairs"],
         },
         "select_roofline": {
