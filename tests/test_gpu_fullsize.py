@@ -1,0 +1,169 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py
+times: index sets compared in full (selection is O(L d) for the oracle),
+attention outputs on sampled rows the oracle computes one by one."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import tca_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tb():
+    import paper_2512_09238_amd.binding as tb
+    return tb
+
+
+@pytest.fixture(scope="module")
+def bufs():
+    import paper_2512_09238_amd.buffers as bufs
+    return bufs
+
+
+def _sample_positions(L, w, b, n, seed):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, b - 1, b, w - 1, w, w + 1, L // 2, L - b, L - 2, L - 1]
+    return np.unique(np.concatenate([fixed, rng.integers(0, L, size=n)])).astype(np.int64)
+
+
+@pytest.mark.parametrize("cfg_id", [2, 3])
+def test_prefill_full_size_sampled_rows(tb, bufs, cfg_id):
+    c = wl.CONFIGS[cfg_id]
+    Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
+    print("config", cfg_id, "L", L, flush=True)
+    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(cfg_id))
+    fr = wl.budget_fractions(wl.budget_seed(cfg_id), Hq)
+    P_gpu = np.stack([tb.tca_config_from_budget(b, c["sigma"], f) for f in fr])
+    P_orc = np.stack([orc.config_from_budget(b, c["sigma"], f) for f in fr])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    O = torch.empty_like(Qd)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+
+    Kf, Vf = wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    sels = orc.select_all_heads(wl.to_f64(x["Q"][:, L - 1]), Kf, b, P_orc, c["alpha"])
+    S_used = []
+    for h in range(Hq):
+        got = H.head_indices(gb, h)
+        H.assert_selection(sels[h], got, b, P_orc[h], tag=f"cfg{cfg_id} head {h}")
+        S_used.append(got)
+        # the compacted rows are byte copies
+        if h % 7 == 0:
+            o = int(gb.offs[h])
+            pick = np.linspace(0, len(got) - 1, 64).astype(np.int64)
+            kg = gb.Kg[o + torch.from_numpy(pick).cuda()].cpu()
+            assert torch.equal(kg, bufs.to_device(x["K"][h // (Hq // Hkv)][got[pick]], "cpu"))
+    pos = _sample_positions(L, w, b, 12, 99)
+    Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
+    worst = 0.0
+    for h in range(Hq):
+        g = h // (Hq // Hkv)
+        qh = wl.to_f64(x["Q"][h][pos])
+        for n, i in enumerate(pos):
+            ref = orc.attention_row(qh[n], int(i), Kf[g], Vf[g], S_used[h], w)
+            worst = max(worst, float(np.abs(ref - Og[h, n]).max()))
+    print("max abs err on", len(pos) * Hq, "rows:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
+
+
+def test_calibration_full_length_two_heads(tb, bufs):
+    """Alg. 1 at the calibration length of config 3 (8192 tokens), on a two-head
+    slice (the oracle's dense L x L pass is what bounds the slice)."""
+    c = wl.CONFIGS[3]
+    Lc, b, M, d = c["L_cal"], c["b"], c["M"], c["d"]
+    x = wl.prefill_inputs(c["kind"], 2, 1, d, Lc, "bf16", wl.calib_seed(3))
+    prm = H.params_for(tb, 2, 1, d, b, c["w"], "bf16")
+    Qd, Kd = bufs.to_device(x["Q"]), bufs.to_device(x["K"])
+    ws = bufs.workspace(tb.tca_calibrate_workspace_bytes(prm, Lc, M))
+    got = tb.tca_calibrate_budgets(prm, Qd, Kd, Lc, M, c["sigma"], c["tau"], ws)
+    ref = orc.calibrate(wl.to_f64(x["Q"]), wl.to_f64(x["K"]), b, M, c["sigma"], c["tau"], c["alpha"])
+    for h in range(2):
+        np.testing.assert_allclose(got["a"][h], ref[h].a, rtol=1e-9)
+        assert np.array_equal(got["n"][h], ref[h].n)
+        if np.min(np.abs(ref[h].a - c["tau"])) > 1e-9:
+            assert got["cand_idx"][h] == ref[h].index and bool(got["fallback"][h]) == ref[h].fallback
+
+
+def test_decode_full_size_sampled_heads(tb, bufs):
+    """Config 4: batch 16 at 128K context.  Cache contents are drawn on the
+    device with a seeded torch generator; sampled (sequence, head) pairs are
+    copied to the host and checked against the oracle, including a sequence
+    whose block completes at the first step."""
+    c = wl.CONFIGS[4]
+    Hq, Hkv, d, T0, b, w, B = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"], c["batch"]
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    fr = wl.budget_fractions(wl.budget_seed(4), Hq)
+    P_gpu = np.stack([tb.tca_config_from_budget(b, c["sigma"], f) for f in fr])
+    P_orc = np.stack([orc.config_from_budget(b, c["sigma"], f) for f in fr])
+    n_glob = np.round(fr * (T0 - w)).astype(np.int64)
+    t_dec = np.array([tb.tca_decode_budget(b, p) for p in P_gpu])
+    cache = bufs.DecodeCache(prm, B, n_glob + 2 * t_dec)
+    g = torch.Generator(device="cuda").manual_seed(wl.data_seed(4))
+    rng = np.random.default_rng(wl.data_seed(4))
+    pend = rng.integers(0, b, size=B)
+    pend[3] = b - 1                                    # sequence 3 completes a block at step 0
+    lengths = T0 + pend
+    for s in range(B):
+        cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=g, device="cuda", dtype=torch.float32))
+        cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=g, device="cuda", dtype=torch.float32))
+        for h in range(Hq):
+            o = int(cache.offs[h])
+            pos = np.sort(rng.choice(T0 - w, size=int(n_glob[h]), replace=False)).astype(np.int32)
+            cache.idx[s, o:o + len(pos)] = torch.from_numpy(pos).cuda()
+    cache.n_rows.copy_(torch.from_numpy(np.tile(n_glob.astype(np.int32), (B, 1))))
+    cache.ringK.copy_(torch.randn(cache.ringK.shape, generator=g, device="cuda", dtype=torch.float32))
+    cache.ringV.copy_(torch.randn(cache.ringV.shape, generator=g, device="cuda", dtype=torch.float32))
+    cache.length.copy_(torch.from_numpy(lengths.astype(np.int64)))
+    q = torch.randn(B, Hq, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    kn = torch.randn(B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    vn = torch.randn(B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    O = torch.full((B, Hq, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    ws = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache.max_head_rows))
+    # host copies of what the sampled pairs need, taken before the step
+    pairs = [(0, 0), (3, 5), (3, 31), (7, 13), (15, 31), (9, 18)]
+    before = {}
+    for (s, h) in pairs:
+        o, n = int(cache.offs[h]), int(n_glob[h])
+        kvh = h // (Hq // Hkv)
+        before[(s, h)] = dict(idx=cache.idx[s, o:o + n].cpu().numpy().astype(np.int64),
+                              Kg=cache.Kg[s, o:o + n].double().cpu().numpy(), Vg=cache.Vg[s, o:o + n].double().cpu().numpy(),
+                              ringK=cache.ringK[s, kvh].double().cpu().numpy(), ringV=cache.ringV[s, kvh].double().cpu().numpy())
+    tb.tca_decode(prm, cache.view, cache.offs, q, kn, vn, P_gpu, O, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O.float()).any()
+    assert cache.length.cpu().tolist() == (lengths + 1).tolist()
+    worst = 0.0
+    for (s, h) in pairs:
+        kvh = h // (Hq // Hkv)
+        T = int(lengths[s])
+        bf = before[(s, h)]
+        # dense arrays holding only what the query can see: global rows and the window
+        Kfull = np.zeros((T + 1, d)); Vfull = np.zeros((T + 1, d))
+        Kfull[bf["idx"]] = bf["Kg"]; Vfull[bf["idx"]] = bf["Vg"]
+        for p in range(T - w + 1, T):
+            Kfull[p] = bf["ringK"][p % w]; Vfull[p] = bf["ringV"][p % w]
+        Kfull[T] = kn[s, kvh].double().cpu().numpy(); Vfull[T] = vn[s, kvh].double().cpu().numpy()
+        qv = q[s, h].double().cpu().numpy()
+        ref = orc.attention_row(qv, T, Kfull, Vfull, bf["idx"], w)
+        worst = max(worst, float(np.abs(ref - O[s, h].double().cpu().numpy()).max()))
+        o = int(cache.offs[h])
+        n_now = int(cache.n_rows[s, h].item())
+        if (T + 1) % b == 0:
+            blk = T // b
+            x = orc.last_query_logits(qv, Kfull[blk * b:(blk + 1) * b])
+            keep = blk * b + orc.top_t(x, orc.decode_budget(b, P_orc[h]))
+            assert n_now == n_glob[h] + len(keep)
+            assert np.array_equal(cache.idx[s, o + int(n_glob[h]):o + n_now].cpu().numpy(), keep)
+            kg_new = cache.Kg[s, o + int(n_glob[h]):o + n_now].double().cpu().numpy()
+            assert np.array_equal(kg_new, Kfull[keep])
+        else:
+            assert n_now == n_glob[h]
+    print("max abs err on sampled (sequence, head) pairs:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
