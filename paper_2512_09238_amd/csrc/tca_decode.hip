@@ -26,6 +26,7 @@ namespace tca {
 
 constexpr int kChunk = 1024;          // rows per split-K slot
 constexpr int kDecThreads = 256;
+constexpr int kMaxSlots = 4096;       // split-K slots per head the merge kernel can weigh (4M rows per head)
 
 struct DecodeHeads {
   int64_t offs[TCA_MAX_HEADS + 1];
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
 #pragma unroll
       for (int e = 0; e < EL; ++e) sc = fmaf(qv[e], kv[e], sc);
     }
-    sc = group_sum(sc, 16);
+    sc = row16_sum(sc);
     if (ok) {
       float vv[EL];
       load_slice<T, EL>(vbase + (size_t)r * D + sub * EL, vv);
@@ -205,20 +206,43 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   const int G = Hq / Hkv, kvh = h / G;
   const float* pp = part + ((size_t)s * Hq + h) * n_slots * (D + 2);
 
-  if (tid < D) {
+  // log-sum-exp merge of the head's partials: slot weights first (one thread per
+  // slot), then every thread sums one output column over a share of the slots
+  __shared__ float wgt[kMaxSlots];
+  __shared__ float colsum[kDecThreads];
+  __shared__ float lsum[kDecThreads / kWave];
+  {
     float M = -INFINITY;
-    for (int x = 0; x < n_slots; ++x)
+    for (int x = tid; x < n_slots; x += kDecThreads)
       if (pp[(size_t)x * (D + 2) + 1] > 0.f) M = fmaxf(M, pp[(size_t)x * (D + 2)]);
-    float L = 0.f, a = 0.f;
-    for (int x = 0; x < n_slots; ++x) {
+    M = group_max(M, kWave);
+    if (lane == 0) lsum[wv] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(lsum[0], lsum[1]), fmaxf(lsum[2], lsum[3]));
+    __syncthreads();
+    float lpart = 0.f;
+    for (int x = tid; x < n_slots; x += kDecThreads) {
       const float lx = pp[(size_t)x * (D + 2) + 1];
-      if (lx > 0.f) {
-        const float cf = __expf(pp[(size_t)x * (D + 2)] - M);
-        L += lx * cf;
-        a += pp[(size_t)x * (D + 2) + 2 + tid] * cf;
-      }
+      const float wx = lx > 0.f ? __expf(pp[(size_t)x * (D + 2)] - M) : 0.f;
+      wgt[x] = wx;
+      lpart += lx * wx;
     }
-    store_f32(O + ((size_t)s * Hq + h) * D + tid, a / L);
+    lpart = group_sum(lpart, kWave);
+    if (lane == 0) lsum[wv] = lpart;
+    __syncthreads();
+    const float L = (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
+    constexpr int SPLIT = kDecThreads / D;               // threads per output column
+    const int col = tid % D, part = tid / D;
+    float a = 0.f;
+    for (int x = part; x < n_slots; x += SPLIT) a += pp[(size_t)x * (D + 2) + 2 + col] * wgt[x];
+    colsum[tid] = a;
+    __syncthreads();
+    if (tid < D) {
+      float t = 0.f;
+#pragma unroll
+      for (int q2 = 0; q2 < SPLIT; ++q2) t += colsum[q2 * D + tid];
+      store_f32(O + ((size_t)s * Hq + h) * D + tid, t / L);
+    }
   }
 
   // block completed by this token?
@@ -389,6 +413,8 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
     dh.t_dec[h] = tca_decode_budget(b, p + (size_t)h * nk);
   }
   dh.offs[Hq] = offs[Hq];
+  if (global_slots(max_rows) + window_slots(prm->window) > kMaxSlots)
+    return fail(TCA_ERR_UNSUPPORTED, "tca_decode: more than %d split-K slots per head", kMaxSlots);
   const size_t need = tca_decode_workspace_bytes(prm, cache->batch, max_rows);
   if (ws_bytes < need || ((uintptr_t)ws & 255))
     return fail(TCA_ERR_WORKSPACE, "tca_decode: workspace needs %zu bytes, 256-byte aligned", need);

@@ -43,6 +43,25 @@ template <> struct Vec16<bf16_t> {
   }
 };
 
+// Raw 16-byte load and its later widening: lets many loads stay in flight at
+// 4 registers each.
+typedef unsigned int raw16_t __attribute__((ext_vector_type(4)));
+template <typename T> __device__ __forceinline__ raw16_t load_raw16(const T* p) {
+  return *reinterpret_cast<const raw16_t*>(p);
+}
+template <typename T> __device__ __forceinline__ void widen_raw16(raw16_t v, float (&out)[Vec16<T>::N]);
+template <> __device__ __forceinline__ void widen_raw16<float>(raw16_t v, float (&out)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
+}
+template <> __device__ __forceinline__ void widen_raw16<bf16_t>(raw16_t v, float (&out)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(v[i] << 16);
+    out[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+  }
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(p->bits); }
@@ -71,6 +90,37 @@ template <> __device__ __forceinline__ void load_slice<bf16_t, 4>(const bf16_t* 
   uint2 v = *reinterpret_cast<const uint2*>(p);
   out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
   out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+
+// Lane exchanges on the vector ALU (DPP), which are several times cheaper than
+// the LDS-crossbar shuffles.  Patterns (all within a row of 16 lanes):
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each group of 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside the row
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// sum over the 16 lanes of a row, result in every lane
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f32<kDppXor1>(v);
+  v += dpp_f32<kDppXor2>(v);
+  v += dpp_f32<kDppHalfMirror>(v);
+  v += dpp_f32<kDppMirror>(v);
+  return v;
+}
+__device__ __forceinline__ double row16_sum(double v) {
+  v += dpp_f64<kDppXor1>(v);
+  v += dpp_f64<kDppXor2>(v);
+  v += dpp_f64<kDppHalfMirror>(v);
+  v += dpp_f64<kDppMirror>(v);
+  return v;
 }
 
 // Butterfly reductions over the low `width` lanes groups of a wave (width a power of two <= 64).

@@ -210,34 +210,6 @@ __device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const 
   if constexpr (NLD > 2) { vst(2, tr.v2); vst(3, tr.v3); }
 }
 
-// Pulls the 128-byte lines of a future tile into L2: each thread reads one dword
-// of one line (first half of the threads the K tile, second half the V^T tile).
-template <int D>
-__device__ __forceinline__ uint32_t touch_tile(const TileWalk& tw, int it, int tid, const uint16_t* __restrict__ Kg,
-                                               const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
-                                               const uint16_t* __restrict__ Vt) {
-  constexpr int LINES = kBN * D * 2 / 128;          // lines per tile (K and V^T tiles have the same size)
-  const int64_t key0 = tw.key0(it);
-  const int line = tid % LINES;
-  const uint16_t* p;
-  if (tid < LINES || kPfThreads < 2 * LINES) {
-    int64_t r = (int64_t)line * 64 / D;             // row holding this line (64 elements per line)
-    const int col = (line * 64) % D;
-    if (it < tw.n_gt) {
-      const int64_t mx = (int64_t)tw.nr - 1 - key0;
-      p = Kg + (size_t)(tw.base + key0 + (r > mx ? mx : r)) * D + col;
-    } else {
-      const int64_t mx = tw.last_pos - key0;
-      p = K + ((size_t)tw.kvh * tw.kv_stride + key0 + (r > mx ? mx : r)) * D + col;
-    }
-  } else {
-    const uint16_t* vsrc = it < tw.n_gt ? Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN)
-                                        : Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
-    p = vsrc + (size_t)line * 64;
-  }
-  return *reinterpret_cast<const uint32_t*>(p);
-}
-
 template <int D, int QT>
 __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
@@ -249,7 +221,6 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
   constexpr int DS = D / 32;             // 32-row slices of O^T
   constexpr int BMW = 32 * QT;           // queries per wave
   constexpr int BM = 4 * BMW;            // queries per workgroup
-  constexpr int CPR = D / 8;             // 16-byte chunks per K row
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
   // Two stages of {K tile, V^T tile}.  Rows are not padded; the 16-byte chunk
@@ -320,8 +291,6 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
   }
 
-  uint32_t touch0 = 0, touch1 = 0;
-  constexpr int kAhead = 4;                        // tiles between the L2 touch and the compute
   load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, tr);
   store_tile<D>(lds, tid, tr);
   if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, tr);
@@ -339,11 +308,6 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, tr);
       if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, tr);
     }
-#ifdef EXP_TOUCH
-    asm volatile("" ::"v"(touch0));                // retire the touch issued two tiles ago
-    touch0 = touch1;
-    if (it + kAhead < n_tiles) touch1 = touch_tile<D>(tw, it + kAhead, tid, Kg, K, Vgt, Vt);
-#endif
     const bool is_glob = it < n_gt;
     const int64_t key0 = tw.key0(it);
     const unsigned char* kb = lds + (it & 1) * (KBYTES + VBYTES);

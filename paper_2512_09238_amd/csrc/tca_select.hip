@@ -41,6 +41,62 @@ SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
 }
 
 // ---------------------------------------------------------------- scoring --
+// Monotone map of a double to an unsigned 64-bit key (larger value -> larger key).
+__device__ __forceinline__ uint64_t ordered_key(double x) {
+  const uint64_t u = (uint64_t)__double_as_longlong(x);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+
+// Sum of G per-lane partials over the LPR lanes that share a row (LPR = 8, 16 or 32
+// consecutive lanes).  Exchange steps pair lane i with its mirror image inside
+// groups of 32 (LDS shuffle), 16, 8 (DPP mirrors), then xor 2 and xor 1 (DPP quad
+// permutes).  While a lane still carries more than one head, a step halves the
+// heads it carries: the lower lane of a pair keeps the lower half.  The total of
+// head g ends up in every lane whose position bits spell g.
+template <int G, int LPR>
+struct GroupReduce {
+  static constexpr int GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));   // heads padded to a power of two
+  template <int W> __device__ static __forceinline__ double exchange(double v) {
+    if constexpr (W == 32) return __shfl_xor(v, 31, kWave) ;   // i <-> 31-i inside 32 lanes
+    else if constexpr (W == 16) return dpp_f64<kDppMirror>(v);
+    else if constexpr (W == 8) return dpp_f64<kDppHalfMirror>(v);
+    else if constexpr (W == 4) return dpp_f64<kDppXor2>(v);
+    else return dpp_f64<kDppXor1>(v);
+  }
+  // is this lane the upper one of its pair at width W?
+  template <int W> __device__ static __forceinline__ bool upper(int sub) {
+    if constexpr (W >= 8) return (sub & (W - 1)) >= W / 2;
+    else return (sub & (W / 2)) != 0;
+  }
+  template <int W, int N> __device__ static __forceinline__ void step(double (&acc)[GP], int sub) {
+    if constexpr (W >= 2) {
+      if constexpr (N > 1) {
+        const bool hi = upper<W>(sub);
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) {
+          const double send = hi ? acc[i] : acc[i + N / 2];
+          const double keep = hi ? acc[i + N / 2] : acc[i];
+          acc[i] = keep + exchange<W>(send);
+        }
+        step<W / 2, N / 2>(acc, sub);
+      } else {
+        acc[0] += exchange<W>(acc[0]);
+        step<W / 2, 1>(acc, sub);
+      }
+    }
+  }
+  __device__ static __forceinline__ double run(double (&acc)[GP], int sub) {
+    step<LPR, GP>(acc, sub);
+    return acc[0];
+  }
+  template <int W, int N> __device__ static __forceinline__ int head_bits(int sub, int g) {
+    if constexpr (W >= 2 && N > 1) return head_bits<W / 2, N / 2>(sub, (g << 1) | (upper<W>(sub) ? 1 : 0));
+    else return g;
+  }
+  // head whose total this lane holds after run()
+  __device__ static __forceinline__ int head_of(int sub) { return head_bits<LPR, GP>(sub, 0); }
+};
+
 // grid (nbt, Hkv); block 256.  T storage type, D head dim, G query heads per KV head.
 template <typename T, int D, int G>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(
@@ -51,45 +107,59 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int RPW = kWave / LPR;            // rows per wave per load
   constexpr int RPI = RPW * (kScoreThreads / kWave);   // rows per workgroup iteration
+  constexpr int UNR = 2;                      // 16-byte row loads in flight per lane (more costs occupancy: measured best)
+  using GR = GroupReduce<G, LPR>;
+  constexpr int GP = GR::GP;
+  static_assert(GP <= LPR, "more heads than lanes per row");
   __shared__ double xs[G][256];
+  __shared__ __attribute__((aligned(16))) uint64_t keys[G][256];
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int64_t j = blockIdx.x;
   const int kvh = blockIdx.y;
   const int sub = lane % LPR, rsub = lane / LPR;
 
-  double qv[G][EPL];
+  double qv[GP][EPL];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int g = 0; g < GP; ++g) {
     float tmp[EPL];
-    Vec16<T>::load(q_last + (size_t)(kvh * G + g) * D + sub * EPL, tmp);
+    if (g < G) Vec16<T>::load(q_last + (size_t)(kvh * G + g) * D + sub * EPL, tmp);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qv[g][e] = (double)tmp[e];
+    for (int e = 0; e < EPL; ++e) qv[g][e] = g < G ? (double)tmp[e] : 0.0;
   }
 
   const T* Kb = K + ((size_t)kvh * kv_stride + pos0 + j * b) * D;
   const int64_t left = n_tokens - j * b;                  // tokens from the block start to the end
   const int rows_here = left < b ? (int)left : b;
-  for (int r0 = 0; r0 < b; r0 += RPI) {
-    const int r = r0 + wv * RPW + rsub;
-    const bool ok = r < rows_here;
-    double acc[G];
+  const int my_head = GR::head_of(sub);
+  const bool writer = my_head < G && (sub & (LPR / GP - 1)) == 0;   // one lane per head holds the row's total
+  for (int r0 = 0; r0 < b; r0 += RPI * UNR) {
+    raw16_t raw[UNR];
 #pragma unroll
-    for (int g = 0; g < G; ++g) acc[g] = 0.0;
-    if (ok) {
-      float kv[EPL];
-      Vec16<T>::load(Kb + (size_t)r * D + sub * EPL, kv);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const double kd = (double)kv[e];
-#pragma unroll
-        for (int g = 0; g < G; ++g) acc[g] = fma(kd, qv[g][e], acc[g]);
-      }
+    for (int u = 0; u < UNR; ++u) {
+      const int r = r0 + u * RPI + wv * RPW + rsub;
+      if (r < rows_here) raw[u] = load_raw16(Kb + (size_t)r * D + sub * EPL);
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      double v = group_sum(acc[g], LPR);
-      if (sub == 0 && r < b) xs[g][r] = ok ? v * scale : -INFINITY;
+    for (int u = 0; u < UNR; ++u) {
+      const int r = r0 + u * RPI + wv * RPW + rsub;
+      const bool ok = r < rows_here;
+      double acc[GP];
+#pragma unroll
+      for (int g = 0; g < GP; ++g) acc[g] = 0.0;
+      if (ok) {
+        float kv[EPL];
+        widen_raw16<T>(raw[u], kv);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const double kd = (double)kv[e];
+#pragma unroll
+          for (int g = 0; g < GP; ++g)
+            if (g < G) acc[g] = fma(kd, qv[g][e], acc[g]);
+        }
+      }
+      const double v = GR::run(acc, sub);
+      if (writer && r < b) xs[my_head][r] = ok ? v * scale : -INFINITY;
     }
   }
   __syncthreads();
@@ -112,20 +182,28 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
       st[0] = mx; st[1] = e1; st[2] = e2;
     }
   }
+  if (j >= n_blocks) return;             // the tail block only feeds the normaliser
 
-  // rank inside the block: number of tokens that beat token i (higher logit, or
-  // the same logit at a lower position).  Full blocks only.
-  if (j < n_blocks) {
-    for (int pi = tid; pi < G * b; pi += kScoreThreads) {
-      const int g = pi / b, i = pi - g * b;
-      const double xi = xs[g][i];
-      int cnt = 0;
-      for (int o = 0; o < b; ++o) {
-        const double xo = xs[g][o];
-        cnt += (xo > xi) || (xo == xi && o < i);
-      }
-      tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)cnt;
+  // Rank inside the block = number of tokens that beat token i (higher logit, or
+  // the same logit at a lower position).  Both conditions are folded into one
+  // 64-bit key: the ordered image of the logit with its 8 lowest mantissa bits
+  // replaced by 255 - position, so one unsigned compare decides a pair.  Logits
+  // that agree in all but those bits (relative distance below 2^-44) count as tied.
+  for (int pi = tid; pi < G * b; pi += kScoreThreads) {
+    const int g = pi / b, i = pi - g * b;
+    keys[g][i] = (ordered_key(xs[g][i]) & ~0xFFull) | (uint64_t)(255 - i);
+  }
+  __syncthreads();
+  for (int pi = tid; pi < G * b; pi += kScoreThreads) {
+    const int g = pi / b, i = pi - g * b;
+    const uint64_t ki = keys[g][i];
+    int cnt = 0;
+    for (int o = 0; o < b; o += 2) {
+      const ulonglong2 ko = *reinterpret_cast<const ulonglong2*>(&keys[g][o]);
+      cnt += (ko.x > ki);
+      cnt += (ko.y > ki);
     }
+    tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)cnt;
   }
 }
 
@@ -162,7 +240,8 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
     const double* __restrict__ stats, int32_t* __restrict__ n_rows,
     int32_t* __restrict__ blk_t, int32_t* __restrict__ blk_dst) {
   __shared__ double hs[TCA_MAX_BLOCKS];
-  __shared__ int32_t ts[TCA_MAX_BLOCKS];
+  __shared__ uint16_t ts[TCA_MAX_BLOCKS];
+  __shared__ uint16_t js[TCA_MAX_BLOCKS];
   __shared__ double red[kAssignThreads / kWave];
   __shared__ int32_t scan[kAssignThreads];
   const int tid = threadIdx.x;
@@ -186,17 +265,45 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
   }
   __syncthreads();
 
-  // rank of each block in ascending h (ties: lower block first), then Eq. 7
-  for (int j = tid; j < m; j += kAssignThreads) {
-    const double hj = hs[j];
-    int rank = 0;
-    for (int o = 0; o < m; ++o) {
-      const double ho = hs[o];
-      rank += (ho < hj) || (ho == hj && o < j);
+  // order the blocks by ascending h (ties: lower block first) with a bitonic sort
+  // of (h, block) pairs in LDS, then Eq. 7: the block at sorted position r gets Psi[r]
+  int P = 1;
+  while (P < m) P <<= 1;
+  for (int e = tid; e < P; e += kAssignThreads) {
+    js[e] = (uint16_t)e;
+    if (e >= m) hs[e] = INFINITY;                      // padding sorts last
+  }
+  __syncthreads();
+  for (int k = 2; k <= P; k <<= 1) {
+    for (int jj = k >> 1; jj > 0; jj >>= 1) {
+      for (int e = tid; e < P; e += kAssignThreads) {
+        const int pr = e ^ jj;
+        if (pr > e) {
+          const double ha = hs[e], hb = hs[pr];
+          const uint16_t ja = js[e], jb = js[pr];
+          const bool a_after_b = (ha > hb) || (ha == hb && ja > jb);
+          const bool ascending = (e & k) == 0;
+          if (a_after_b == ascending) {
+            hs[e] = hb; hs[pr] = ha;
+            js[e] = jb; js[pr] = ja;
+          }
+        }
+      }
+      // Element e is always handled by the wave that owns its aligned group of 64,
+      // so a stage with partner distance < 64 touches only the wave's own
+      // elements.  A workgroup barrier is needed only when this stage or the next
+      // one pairs elements of different waves; otherwise the wave's own LDS
+      // accesses are already ordered.
+      const int next_jj = jj > 1 ? (jj >> 1) : k;        // distance of the following stage
+      if (jj >= kWave || next_jj >= kWave) __syncthreads();
+      else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
+  }
+  __syncthreads();
+  for (int r = tid; r < m; r += kAssignThreads) {
     int e = 0;
-    while (e < nk - 1 && rank >= args.cum[hl][e]) ++e;
-    ts[j] = 1 << e;
+    while (e < nk - 1 && r >= args.cum[hl][e]) ++e;
+    ts[js[r]] = (uint16_t)(1 << e);
   }
   __syncthreads();
 
