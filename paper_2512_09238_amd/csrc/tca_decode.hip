@@ -128,31 +128,42 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
 #pragma unroll
   for (int e = 0; e < EL; ++e) acc[e] = 0.f;
 
-  for (int r0 = r_begin; r0 < r_end; r0 += 16) {
-    const int r = r0 + grp;
-    bool ok = r < r_end;
-    if (ok && is_window) {
-      // slot r of the ring holds position Tpos - ((Tpos - r) mod w); empty while Tpos < w
-      const int64_t back = ((Tpos - r) % w + w) % w;
-      ok = Tpos - back >= 0;
-    }
-    float sc = 0.f;
-    float kv[EL];
-    if (ok) {
-      load_slice<T, EL>(kbase + (size_t)r * D + sub * EL, kv);
+  // kUnr rows per group are loaded (K and V) before any of them is used, so that
+  // each lane keeps 2*kUnr 16-byte loads in flight
+  constexpr int kUnr = 2;
+  for (int r0 = r_begin; r0 < r_end; r0 += 16 * kUnr) {
+    float kv[kUnr][EL], vv[kUnr][EL];
+    bool ok[kUnr];
 #pragma unroll
-      for (int e = 0; e < EL; ++e) sc = fmaf(qv[e], kv[e], sc);
+    for (int u = 0; u < kUnr; ++u) {
+      const int r = r0 + u * 16 + grp;
+      ok[u] = r < r_end;
+      if (ok[u] && is_window) {
+        // slot r of the ring holds position Tpos - ((Tpos - r) mod w); empty while Tpos < w
+        const int64_t back = ((Tpos - r) % w + w) % w;
+        ok[u] = Tpos - back >= 0;
+      }
+      if (ok[u]) {
+        load_slice<T, EL>(kbase + (size_t)r * D + sub * EL, kv[u]);
+        load_slice<T, EL>(vbase + (size_t)r * D + sub * EL, vv[u]);
+      }
     }
-    sc = row16_sum(sc);
-    if (ok) {
-      float vv[EL];
-      load_slice<T, EL>(vbase + (size_t)r * D + sub * EL, vv);
-      const float mn = fmaxf(m, sc);
-      const float corr = __expf(m - mn), pr = __expf(sc - mn);
-      l = l * corr + pr;
 #pragma unroll
-      for (int e = 0; e < EL; ++e) acc[e] = acc[e] * corr + pr * vv[e];
-      m = mn;
+    for (int u = 0; u < kUnr; ++u) {
+      float sc = 0.f;
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < EL; ++e) sc = fmaf(qv[e], kv[u][e], sc);
+      }
+      sc = row16_sum(sc);
+      if (ok[u]) {
+        const float mn = fmaxf(m, sc);
+        const float corr = __expf(m - mn), pr = __expf(sc - mn);
+        l = l * corr + pr;
+#pragma unroll
+        for (int e = 0; e < EL; ++e) acc[e] = acc[e] * corr + pr * vv[u][e];
+        m = mn;
+      }
     }
   }
   // merge the 4 groups of a wave, then the 4 waves through LDS
