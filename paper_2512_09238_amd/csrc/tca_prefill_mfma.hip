@@ -210,6 +210,59 @@ __device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const 
   if constexpr (NLD > 2) { vst(2, tr.v2); vst(3, tr.v3); }
 }
 
+// Direct global->LDS copies of one tile (no staging registers, no ds_write): every
+// lane of a wave-load deposits 16 bytes at consecutive LDS addresses, so the lane
+// that fills LDS chunk position p of a row fetches the global chunk the XOR
+// swizzle assigns to p.
+template <int D>
+__device__ __forceinline__ void dma_k_tile(const TileWalk& tw, int it, int wv, int lane,
+                                           const uint16_t* __restrict__ Kg, const uint16_t* __restrict__ K,
+                                           unsigned char* kstage) {
+  constexpr int CPR = D / 8;
+  constexpr int PER_WAVE = CPR / 4;                 // 1 KB wave-loads per wave (the tile has CPR of them)
+  const int64_t key0 = tw.key0(it);
+  const uint16_t* ksrc;
+  int64_t krow_max;
+  if (it < tw.n_gt) {
+    ksrc = Kg + (size_t)(tw.base + key0) * D;
+    krow_max = (int64_t)tw.nr - 1 - key0;
+  } else {
+    ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
+    krow_max = tw.last_pos - key0;
+  }
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; ++i) {
+    const int q = wv * PER_WAVE + i;                // wave-uniform: which KB of the tile
+    const int cid = q * 64 + lane;                  // 16-byte chunk of the LDS tile this lane fills
+    const int r = cid / CPR, pch = cid % CPR;
+    const int swz = (CPR == 16) ? (r & 15) : ((r >> 1) & 7);
+    const int ch = pch ^ swz;                       // global chunk that belongs at this LDS position
+    const int rr = r > krow_max ? (int)krow_max : r;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + (size_t)rr * D + ch * 8),
+                                     (__attribute__((address_space(3))) void*)(kstage + q * 1024), 16, 0, 0);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void dma_v_tile(const TileWalk& tw, int it, int wv, int lane,
+                                           const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
+                                           unsigned char* vstage) {
+  constexpr int PER_WAVE = D / 32;                  // the tile has D/8 wave-loads
+  const int64_t key0 = tw.key0(it);
+  const uint16_t* vsrc = it < tw.n_gt
+      ? Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN)
+      : Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+#pragma unroll
+  for (int i = 0; i < PER_WAVE; ++i) {
+    const int q = wv * PER_WAVE + i;
+    const int cid = q * 64 + lane;
+    const int dd = cid >> 3, pch = cid & 7;
+    const int ch = pch ^ ((dd >> 1) & 7);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + (size_t)dd * kBN + ch * 8),
+                                     (__attribute__((address_space(3))) void*)(vstage + q * 1024), 16, 0, 0);
+  }
+}
+
 template <int D, int QT>
 __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
@@ -272,8 +325,7 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
   const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
   const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
 
-  // ---- staging: global -> registers -> LDS stage (tile after next is in flight in registers)
-  TileRegs tr;
+  // ---- staging: direct global -> LDS loads, the next tile in flight while this one is computed
   TileWalk tw;
   tw.n_gt = n_gt; tw.wt0 = wt0; tw.base = base; tw.nr = nr; tw.vgt_tile0 = vgt_tile0; tw.kvh = kvh;
   tw.kv_stride = kv_stride; tw.last_pos = q_pos0 + last_row; tw.dense_tiles = dense_tiles;
@@ -291,22 +343,20 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
   }
 
-  load_tile<D>(tw, 0, tid, Kg, K, Vgt, Vt, tr);
-  store_tile<D>(lds, tid, tr);
-  if (n_tiles > 1) load_tile<D>(tw, 1, tid, Kg, K, Vgt, Vt, tr);
+  dma_k_tile<D>(tw, 0, wv, lane, Kg, K, lds);
+  dma_v_tile<D>(tw, 0, wv, lane, Vgt, Vt, lds + KBYTES);
 
   for (int it = 0; it < n_tiles; ++it) {
-    // stage it&1 holds tile `it` once every wave has passed this barrier; the other
-    // stage was last read while computing tile it-1, which every wave has finished.
+    // this wave's direct loads of tile `it` have landed; after the barrier everyone's
+    // have, and everyone has finished reading the other stage (tile it-1)
+    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
 #if !defined(EXP_NOSTAGE) && !defined(EXP_NOBARRIER)
     __syncthreads();
 #endif
-#ifdef EXP_BARRIERONLY
-    __syncthreads();
-#endif
     if (it + 1 < n_tiles && !(EXP_STAGE_SKIP && it > 0)) {
-      store_tile<D>(lds + ((it + 1) & 1) * (KBYTES + VBYTES), tid, tr);
-      if (it + 2 < n_tiles) load_tile<D>(tw, it + 2, tid, Kg, K, Vgt, Vt, tr);
+      unsigned char* st = lds + ((it + 1) & 1) * (KBYTES + VBYTES);
+      dma_k_tile<D>(tw, it + 1, wv, lane, Kg, K, st);
+      dma_v_tile<D>(tw, it + 1, wv, lane, Vgt, Vt, st + KBYTES);
     }
     const bool is_glob = it < n_gt;
     const int64_t key0 = tw.key0(it);
