@@ -33,6 +33,8 @@ here and the only behaviour the GPU path implements):
     positions; a block is scored, with the query of the step that completes
     it, over its b rows, and its top t = floor(sum_k k p_k) rows join the
     global subset; they become visible once they leave the window.
+  * chunked prefill is not in the paper; `tca_prefill_chunked` states the rule
+    used (each chunk scored by its own last query over its own keys).
 
 Functions pinned by tests/test_oracle_pins.py; none is "parity unpinned"
 except the readings listed above, which are choices rather than facts.
@@ -307,6 +309,38 @@ def tca_prefill(Q, K, V, b: int, w: int, p, alpha: float, scale: float | None = 
         for h in range(Hq)
     ])
     return O, sels
+
+
+def tca_prefill_chunked(Q, K, V, b: int, w: int, p, alpha: float, chunk: int, scale: float | None = None):
+    """Chunked prefill.  NOT in the paper: a serving extension, defined here as
+    follows.  The sequence arrives in chunks of `chunk` tokens (a multiple of b).
+    For the chunk covering positions [c0, c1): the chunk's last query scores the
+    chunk's own keys only (Eq. 5 restricted to [c0, c1)), Eq. 6-8 run over the
+    chunk's full blocks with the head's configuration, and the kept positions
+    are appended to the head's global subset; then every query of the chunk
+    attends (Eq. 2) to the global subset as it stands - rows kept from earlier
+    chunks and from this one, visible once they have left the query's window -
+    plus its window.  With one chunk covering the sequence this is Alg. 2.
+
+    Q [Hq,L,d], K,V [Hkv,L,d], p [Hq,nk].  Returns (O [Hq,L,d], list of index sets).
+    """
+    Q, K, V = (np.asarray(a, F64) for a in (Q, K, V))
+    Hq, L, _ = Q.shape
+    Hkv = K.shape[0]
+    if chunk % b != 0:
+        raise ValueError("chunk must be a multiple of the block size")
+    S = [np.zeros(0, np.int64) for _ in range(Hq)]
+    O = np.empty((Hq, L, V.shape[2]), F64)
+    for c0 in range(0, L, chunk):
+        c1 = min(L, c0 + chunk)
+        for h in range(Hq):
+            g = kv_head_of(h, Hq, Hkv)
+            sel = select(Q[h, c1 - 1], K[g, c0:c1], b, p[h], alpha, scale)
+            S[h] = np.concatenate([S[h], c0 + sel.S]).astype(np.int64)
+        for h in range(Hq):
+            g = kv_head_of(h, Hq, Hkv)
+            O[h, c0:c1] = tca_attention(Q[h, c0:c1], K[g, :c1], V[g, :c1], S[h], w, scale, q_pos0=c0)
+    return O, S
 
 
 # --------------------------------------------------------------------------

@@ -424,3 +424,38 @@ def test_pins_would_catch_a_swapped_rank_direction(monkeypatch):
     monkeypatch.setattr(orc, "block_ranks", lambda h: len(h) - 1 - real(h))
     t = orc.block_budgets(4, np.array([0.1, 0.9, 0.5, 0.3]), np.array([0.5, 0.25, 0.25]))
     assert list(t) != [1, 4, 2, 1]
+
+
+# ------------------------------------------------------- chunked prefill --
+def test_chunked_prefill_reduces_to_alg2_and_follows_its_definition():
+    rng = np.random.default_rng(14)
+    Hq, Hkv, L, d, b, w = 2, 1, 70, 8, 4, 8
+    Q = rng.standard_normal((Hq, L, d))
+    K = rng.standard_normal((Hkv, L, d))
+    V = rng.standard_normal((Hkv, L, d))
+    p = rng.dirichlet(np.ones(3), size=Hq)
+    O1, sels = orc.tca_prefill(Q, K, V, b, w, p, 0.5)
+    # one chunk covering the sequence is Alg. 2
+    O2, S2 = orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=72)
+    np.testing.assert_allclose(O2, O1, rtol=1e-13)
+    for h in range(Hq):
+        assert list(S2[h]) == list(sels[h].S)
+    # three chunks: index sets are the per-chunk selections put end to end; a row
+    # of chunk 1 sees rows kept from chunks 0 and 1 only, and only outside its window
+    chunk = 24
+    O3, S3 = orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=chunk)
+    for h in range(Hq):
+        parts = []
+        for c0 in range(0, L, chunk):
+            c1 = min(L, c0 + chunk)
+            parts.append(c0 + orc.select(Q[h, c1 - 1], K[0, c0:c1], b, p[h], 0.5).S)
+        assert list(S3[h]) == list(np.concatenate(parts))
+        assert len(S3[h]) == sum(orc.selected_rows(b, (min(L, c0 + chunk) - c0) // b, p[h]) for c0 in range(0, L, chunk))
+        i = 40                                                     # in chunk 1 = [24, 48)
+        upto = np.concatenate(parts[:2])
+        keys = [int(j) for j in upto if j <= i - w] + list(range(i - w + 1, i + 1))
+        ref = scipy_softmax(K[0][keys] @ Q[h, i] / math.sqrt(d)) @ V[0][keys]
+        np.testing.assert_allclose(O3[h, i], ref, rtol=1e-12)
+    # chunk not a multiple of b is rejected
+    with pytest.raises(ValueError):
+        orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=10)
