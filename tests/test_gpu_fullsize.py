@@ -167,3 +167,86 @@ def test_decode_full_size_sampled_heads(tb, bufs):
             assert n_now == n_glob[h]
     print("max abs err on sampled (sequence, head) pairs:", worst, flush=True)
     assert worst <= H.TOL["bf16"]
+
+
+def test_config5_ragged_mixed_batch_sampled(tb, bufs):
+    """Config 5: 70B-shaped layer (Hq=64, Hkv=8), 8 sequences with log-uniform
+    lengths, 8192-token chunks interleaved with decode steps, budgets from
+    calibration.  Inputs are drawn on the device; sampled (sequence, head) pairs
+    are copied to the host and replayed by the oracle alone."""
+    import paper_2512_09238_amd.schedule as sched
+    c = wl.CONFIGS[5]
+    Hq, Hkv, d, b, w, chunk = c["Hq"], c["Hkv"], c["d"], c["b"], c["w"], c["chunk"]
+    G = Hq // Hkv
+    lengths = wl.config5_lengths()
+    print("lengths", lengths, flush=True)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    # budgets: calibration on a separate 8192-token sample
+    xc = wl.device_lowrank_inputs(Hq, Hkv, d, c["L_cal"], wl.calib_seed(5))
+    wsc = bufs.workspace(tb.tca_calibrate_workspace_bytes(prm, c["L_cal"], c["M"]))
+    cal = tb.tca_calibrate_budgets(prm, xc["Q"], xc["K"], c["L_cal"], c["M"], c["sigma"], c["tau"], wsc)
+    P_gpu = cal["p_star"]
+    # the oracle calibrates the heads it is going to replay by itself (Alg. 1 on the same sample)
+    sample_heads = [0, 17, 40, Hq - 1]
+    P_orc = {}
+    for h in sample_heads:
+        kv = h // G
+        ch = orc.calibrate_head(xc["Q"][h].double().cpu().numpy(), xc["K"][kv].double().cpu().numpy(), b,
+                                orc.candidates(b, c["M"], c["sigma"]), c["tau"], c["alpha"])
+        assert ch.index == cal["cand_idx"][h], f"calibration of head {h}"
+        np.testing.assert_allclose(P_gpu[h], ch.p, rtol=1e-12, atol=1e-15)
+        P_orc[h] = ch.p
+    del xc, wsc
+    seqs = []
+    for i, L in enumerate(lengths):
+        x = wl.device_lowrank_inputs(Hq, Hkv, d, L, wl.data_seed(5) + 10 * i)
+        seqs.append(dict(Q=x["Q"], K=x["K"], V=x["V"], O=torch.empty_like(x["Q"])))
+    mb = sched.MixedBatch(prm, lengths, chunk, P_gpu)
+    n_calls = len(mb.events)
+    g = torch.Generator(device="cuda").manual_seed(77)
+    dq = torch.randn(n_calls, len(lengths), Hq, d, generator=g, device="cuda").to(torch.bfloat16)
+    dk = torch.randn(n_calls, len(lengths), Hkv, d, generator=g, device="cuda").to(torch.bfloat16)
+    dv = torch.randn(n_calls, len(lengths), Hkv, d, generator=g, device="cuda").to(torch.bfloat16)
+    outs = {}
+    mb.run(seqs, lambda step, slots: (dq[step, :len(slots)].contiguous(), dk[step, :len(slots)].contiguous(),
+                                      dv[step, :len(slots)].contiguous()),
+           lambda step, slots, Od: outs.__setitem__(step, (len(slots), Od.clone())))
+    torch.cuda.synchronize()
+    print("gpu done:", n_calls, "chunk events,", mb.decode_calls, "decode steps", flush=True)
+    longest = int(np.argmax(lengths))
+    pairs = [(longest, 0), (longest, Hq - 1), (int(np.argmin(lengths)), 17), (2, 40)]   # heads in sample_heads
+    worst_p = worst_d = 0.0
+    for (i, h) in pairs:
+        L, kv = lengths[i], h // G
+        Kf = seqs[i]["K"][kv].double().cpu().numpy()[None]
+        Vf = seqs[i]["V"][kv].double().cpu().numpy()[None]
+        p1 = P_orc[h][None]
+        # selection replay: every chunk scored by its own last query
+        S = np.zeros(0, np.int64)
+        for c0, c1 in sched.chunk_bounds(L, chunk):
+            ql = seqs[i]["Q"][h, c1 - 1].double().cpu().numpy()
+            S = np.concatenate([S, c0 + orc.select(ql, Kf[0, c0:c1], b, p1[0], c["alpha"]).S])
+        rows = np.unique(np.concatenate([[0, w, L - 1, min(L - 1, chunk), min(L - 1, chunk - 1)],
+                                         np.random.default_rng(i * 100 + h).integers(0, L, 6)]))
+        for r in rows:
+            r = int(r)
+            # the global subset as it stood when row r's chunk was processed
+            c1 = min(L, (r // chunk + 1) * chunk)
+            S_then = S[S < c1]
+            ref = orc.attention_row(seqs[i]["Q"][h, r].double().cpu().numpy(), r, Kf[0], Vf[0], S_then, w)
+            worst_p = max(worst_p, float(np.abs(ref - seqs[i]["O"][h, r].double().cpu().numpy()).max()))
+        # decode replay for this (sequence, head)
+        slot = mb.slot_of[i]
+        oc = orc.HeadCache(S=[S.copy()], K=Kf.copy(), V=Vf.copy())
+        for step in sorted(outs):
+            n, Od = outs[step]
+            if slot >= n:
+                continue
+            ref = orc.decode_step(oc, dq[step, slot, h:h + 1].double().cpu().numpy(),
+                                  dk[step, slot, kv:kv + 1].double().cpu().numpy(),
+                                  dv[step, slot, kv:kv + 1].double().cpu().numpy(), b, w, p1)
+            worst_d = max(worst_d, float(np.abs(ref[0] - Od[slot, h].double().cpu().numpy()).max()))
+        o, n = int(mb.cache.offs[h]), int(mb.cache.n_rows[slot, h].item())
+        assert np.array_equal(mb.cache.idx[slot, o:o + n].cpu().numpy(), oc.S[0]), (i, h)
+    print("max abs err prefill rows", worst_p, "decode", worst_d, flush=True)
+    assert worst_p <= H.TOL["bf16"] and worst_d <= H.TOL["bf16"]

@@ -166,3 +166,41 @@ def budget_seed(cfg_id: int) -> int:
 
 def calib_seed(cfg_id: int) -> int:
     return 3000 + cfg_id
+
+
+# ------------------------------------------- device-side generation (large) --
+def device_lowrank_inputs(Hq: int, Hkv: int, d: int, L: int, seed: int, device="cuda:0", rank: int = 32,
+                          noise_std: float = 0.1, dup_frac: float = 0.3, dup_noise_std: float = 0.01):
+    """The "lowrank" recipe of `prefill_inputs`, drawn on the GPU with a seeded torch
+    generator (for workloads too large to build on the host in reasonable time).
+    Returns bf16 torch tensors Q [Hq,L,d], K,V [Hkv,L,d] and the per-head gains."""
+    import torch
+    g = torch.Generator(device=device).manual_seed(seed)
+    rn = lambda *shape: torch.randn(*shape, generator=g, device=device, dtype=torch.float32)
+    K = torch.empty(Hkv, L, d, device=device, dtype=torch.bfloat16)
+    for kv in range(Hkv):
+        U, W = rn(L, rank), rn(d, rank)
+        base = (U @ W.T) / rank ** 0.5 + noise_std * rn(L, d)
+        n_dup = int(round(dup_frac * L))
+        rows = torch.randperm(L - 1, generator=g, device=device)[:n_dup] + 1
+        src = (torch.rand(n_dup, generator=g, device=device) * rows).long()
+        out = base.clone()
+        out[rows] = base[src] + dup_noise_std * rn(n_dup, d)
+        K[kv] = out.to(torch.bfloat16)
+    V = rn(Hkv, L, d).to(torch.bfloat16)
+    gains = torch.exp(torch.rand(Hq, generator=g, device=device) * float(np.log(8.0)))
+    Q = torch.empty(Hq, L, d, device=device, dtype=torch.bfloat16)
+    for h in range(Hq):
+        Q[h] = (gains[h] * rn(L, d)).to(torch.bfloat16)
+    return {"Q": Q, "K": K, "V": V, "gains": gains}
+
+
+CONFIGS[5] = dict(kind="lowrank", Hq=64, Hkv=8, d=128, dtype="bf16", b=128, w=4096, alpha=0.5, sigma=1.0,
+                  n_seqs=8, len_lo=4096, len_hi=131072, chunk=8192, L_cal=8192, M=14, tau=0.9)
+
+
+def config5_lengths(seed: int = 1005) -> list:
+    """8 sequence lengths, log-uniform in [4096, 131072]."""
+    c = CONFIGS[5]
+    rng = np.random.default_rng(seed)
+    return [int(x) for x in np.exp(rng.uniform(np.log(c["len_lo"]), np.log(c["len_hi"]), size=c["n_seqs"]))]
