@@ -24,20 +24,14 @@
 //                  a lane belongs to the same query, so rescaling is a per-lane scalar.
 //
 // Pipeline: two LDS stages of {K tile [64][D], V^T tile [D][64]} with XOR-swizzled
-// 16-byte chunks (conflict-free b128 reads without padding); the tile after next
-// is in flight in registers while the current one is computed; one barrier per tile.
+// 16-byte chunks (conflict-free b128 reads without padding); the next tile is
+// copied global -> LDS directly (no staging registers) while the current one is
+// computed; one barrier per tile.
 #include <hip/hip_runtime.h>
 
 #include "tca_prefill.h"
 
 namespace tca {
-#if defined(EXP_NOSTAGE) || defined(EXP_BARRIERONLY)
-#define EXP_NOSTAGE 1
-#define EXP_STAGE_SKIP 1
-#else
-#define EXP_STAGE_SKIP 0
-#endif
-
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
@@ -148,67 +142,6 @@ template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
   return r * (D * 2) + ((ch ^ swz) << 4);
 }
 __device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + ((ch ^ ((dd >> 1) & 7)) << 4); }
-
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-
-// One tile in flight: up to four 16-byte chunks of K and of V^T per thread, in
-// named registers (arrays here end up in scratch or LDS instead of VGPRs).
-struct TileRegs {
-  u32x4_t k0, k1, k2, k3, v0, v1, v2, v3;
-};
-
-template <int D>
-__device__ __forceinline__ void load_tile(const TileWalk& tw, int it, int tid, const uint16_t* __restrict__ Kg,
-                                          const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
-                                          const uint16_t* __restrict__ Vt, TileRegs& tr) {
-  constexpr int CPR = D / 8;
-  constexpr int NLD = kBN * CPR / kPfThreads;   // chunks per thread per tile (K and V^T alike): 4 or 2
-  const uint16_t* ksrc;
-  const uint16_t* vsrc;
-  int64_t krow_max;                       // last row that may be read, relative to ksrc
-  const int64_t key0 = tw.key0(it);
-  if (it < tw.n_gt) {
-    ksrc = Kg + (size_t)(tw.base + key0) * D;
-    krow_max = (int64_t)tw.nr - 1 - key0;
-    vsrc = Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN);
-  } else {
-    ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
-    krow_max = tw.last_pos - key0;
-    vsrc = Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
-  }
-  auto kld = [&](int i) -> u32x4_t {
-    const int id = tid + i * kPfThreads;
-    const int r = id / CPR, ch = id % CPR;
-    const int rr = r > krow_max ? (int)krow_max : r;    // stay inside the buffer; such keys are masked
-    return *reinterpret_cast<const u32x4_t*>(ksrc + (size_t)rr * D + ch * 8);
-  };
-  auto vld = [&](int i) -> u32x4_t {
-    return *reinterpret_cast<const u32x4_t*>(vsrc + (size_t)(tid + i * kPfThreads) * 8);
-  };
-  tr.k0 = kld(0); tr.k1 = kld(1);
-  if constexpr (NLD > 2) { tr.k2 = kld(2); tr.k3 = kld(3); }
-  tr.v0 = vld(0); tr.v1 = vld(1);
-  if constexpr (NLD > 2) { tr.v2 = vld(2); tr.v3 = vld(3); }
-}
-
-template <int D>
-__device__ __forceinline__ void store_tile(unsigned char* stage, int tid, const TileRegs& tr) {
-  constexpr int CPR = D / 8;
-  constexpr int NLD = kBN * CPR / kPfThreads;
-  unsigned char* vb = stage + kBN * D * 2;
-  auto kst = [&](int i, u32x4_t x) {
-    const int id = tid + i * kPfThreads;
-    *reinterpret_cast<u32x4_t*>(stage + k_off<D>(id / CPR, id % CPR)) = x;
-  };
-  auto vst = [&](int i, u32x4_t x) {
-    const int id = tid + i * kPfThreads;
-    *reinterpret_cast<u32x4_t*>(vb + v_off(id >> 3, id & 7)) = x;
-  };
-  kst(0, tr.k0); kst(1, tr.k1);
-  if constexpr (NLD > 2) { kst(2, tr.k2); kst(3, tr.k3); }
-  vst(0, tr.v0); vst(1, tr.v1);
-  if constexpr (NLD > 2) { vst(2, tr.v2); vst(3, tr.v3); }
-}
 
 // Direct global->LDS copies of one tile (no staging registers, no ds_write): every
 // lane of a wave-load deposits 16 bytes at consecutive LDS addresses, so the lane
@@ -343,6 +276,13 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
   }
 
+  // per-lane LDS byte offsets of the MFMA fragments inside a stage (the rest is compile-time constant)
+  int kfa[KK], vfa[4];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) kfa[kk] = k_off<D>(c, 2 * kk + hh);
+#pragma unroll
+  for (int sg = 0; sg < 4; ++sg) vfa[sg] = v_off(c, 2 * sg + hh);
+
   dma_k_tile<D>(tw, 0, wv, lane, Kg, K, lds);
   dma_v_tile<D>(tw, 0, wv, lane, Vgt, Vt, lds + KBYTES);
 
@@ -350,10 +290,8 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
     // this wave's direct loads of tile `it` have landed; after the barrier everyone's
     // have, and everyone has finished reading the other stage (tile it-1)
     __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
-#if !defined(EXP_NOSTAGE) && !defined(EXP_NOBARRIER)
     __syncthreads();
-#endif
-    if (it + 1 < n_tiles && !(EXP_STAGE_SKIP && it > 0)) {
+    if (it + 1 < n_tiles) {
       unsigned char* st = lds + ((it + 1) & 1) * (KBYTES + VBYTES);
       dma_k_tile<D>(tw, it + 1, wv, lane, Kg, K, st);
       dma_v_tile<D>(tw, it + 1, wv, lane, Vgt, Vt, st + KBYTES);
@@ -384,31 +322,31 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[t][sub][r] = 0.f;
     {
+      // fragment (sub, kk) sits at kfa[kk] + sub * 32 rows: the swizzle depends on the row only through c
+      auto kfrag = [&](int i) {
+        return *reinterpret_cast<const bf16x8_t*>(kb + kfa[i >> 1] + (i & 1) * (32 * D * 2));
+      };
       bf16x8_t fr[kFragAhead];
 #pragma unroll
-      for (int i = 0; i < kFragAhead; ++i)
-        fr[i] = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>((i & 1) * 32 + c, 2 * (i >> 1) + hh));
+      for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
 #pragma unroll
       for (int i = 0; i < 2 * KK; ++i) {
         const int sub = i & 1, kk = i >> 1;
 #pragma unroll
         for (int t = 0; t < QT; ++t)
-#ifdef EXP_NOS
-          s[t][sub][kk] += (float)fr[i % kFragAhead][0] * (float)qf[t][kk][1];
-#else
           s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[t][kk], s[t][sub], 0, 0, 0);
-#endif
-        if (i + kFragAhead < 2 * KK) {
-          const int j = i + kFragAhead;
-          fr[i % kFragAhead] = *reinterpret_cast<const bf16x8_t*>(kb + k_off<D>((j & 1) * 32 + c, 2 * (j >> 1) + hh));
-        }
+        if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
       }
     }
     // first V^T fragments: issued now, consumed after the softmax
+    // fragment (sl, sg) sits at vfa[sg] + sl * 32 rows
+    auto vfrag = [&](int j) {
+      return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
+    };
     bf16x8_t vfr[kFragAhead];
 #pragma unroll
     for (int j = 0; j < kFragAhead; ++j)
-      vfr[j] = *reinterpret_cast<const bf16x8_t*>(vb + v_off((j % DS) * 32 + c, (j / DS) * 2 + hh));
+      vfr[j] = vfrag(j);
 
     // ---- online softmax per query (lane column), P^T packed to bf16
     bf16x8_t pf[QT][2][2];
@@ -462,11 +400,7 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
           bf16x8_t pk;
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-#ifdef EXP_NOEXP
-            const float p = fmaf(s[t][sub][8 * g + e], sl2e, -mb);
-#else
             const float p = __builtin_amdgcn_exp2f(fmaf(s[t][sub][8 * g + e], sl2e, -mb));
-#endif
             ls[e & 3] += p;
             pk[e] = (__bf16)p;
           }
@@ -475,7 +409,6 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       l[t] += (ls[0] + ls[1]) + (ls[2] + ls[3]);
     }
 
-#ifndef EXP_NOPV
     // ---- O^T += V^T P^T: the DS accumulation chains alternate; V^T fragments are read ahead
 #pragma unroll
     for (int j = 0; j < 4 * DS; ++j) {
@@ -483,15 +416,8 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
 #pragma unroll
       for (int t = 0; t < QT; ++t)
         o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[t][sg >> 1][sg & 1], o[t][sl], 0, 0, 0);
-      if (j + kFragAhead < 4 * DS) {
-        const int n = j + kFragAhead;
-        vfr[j % kFragAhead] = *reinterpret_cast<const bf16x8_t*>(vb + v_off((n % DS) * 32 + c, (n / DS) * 2 + hh));
-      }
+      if (j + kFragAhead < 4 * DS) vfr[j % kFragAhead] = vfrag(j + kFragAhead);
     }
-#else
-#pragma unroll
-    for (int t = 0; t < QT; ++t) { o[t][0][0] += (float)pf[t][0][0][0] + (float)pf[t][1][1][7] + (float)pf[t][0][1][3] + (float)pf[t][1][0][5]; }
-#endif
   }
 
   // ---- normalise and store
@@ -570,10 +496,7 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
 
-#ifndef EXP_QT
-#define EXP_QT 1
-#endif
-  constexpr int QT = EXP_QT;
+  constexpr int QT = 1;                  // 32 queries per wave (QT = 2 needs more than 256 registers per lane)
   constexpr int BM = 128 * QT;
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   hipLaunchKernelGGL((prefill_mfma_kernel<D, QT>), dim3((unsigned)n_qt * Hq), dim3(kPfThreads), 0, st, Q,
