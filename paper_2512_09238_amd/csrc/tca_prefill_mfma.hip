@@ -29,6 +29,8 @@
 // computed; one barrier per tile.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tca_prefill.h"
 
 namespace tca {
@@ -37,7 +39,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 
 constexpr int kBN = 64;              // keys per tile
-constexpr int kPfThreads = 256;
 constexpr int kFragAhead = 4;        // LDS fragment reads in flight ahead of the MFMA that uses them
 
 struct PrefillHeads {
@@ -146,58 +147,67 @@ __device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + (
 // Direct global->LDS copies of one tile (no staging registers, no ds_write): every
 // lane of a wave-load deposits 16 bytes at consecutive LDS addresses, so the lane
 // that fills LDS chunk position p of a row fetches the global chunk the XOR
-// swizzle assigns to p.
-template <int D>
-__device__ __forceinline__ void dma_k_tile(const TileWalk& tw, int it, int wv, int lane,
-                                           const uint16_t* __restrict__ Kg, const uint16_t* __restrict__ K,
-                                           unsigned char* kstage) {
-  constexpr int CPR = D / 8;
-  constexpr int PER_WAVE = CPR / 4;                 // 1 KB wave-loads per wave (the tile has CPR of them)
-  const int64_t key0 = tw.key0(it);
+// swizzle assigns to p.  A tile is CPR wave-loads of K plus D/8 of V^T; each wave
+// issues its share one at a time (`issue(j)`), so that the loads can be spread
+// between the MFMAs instead of queueing up behind the barrier.
+template <int D, int NW>
+struct TileDma {
+  static constexpr int CPR = D / 8;
+  static constexpr int NK = CPR / NW;               // K wave-loads per wave
+  static constexpr int NV = D / 8 / NW;             // V^T wave-loads per wave
+  static constexpr int N = NK + NV;
+  static_assert(NK >= 1 && NV >= 1 && N <= D / 16, "too many or too few waves for this tile");
   const uint16_t* ksrc;
-  int64_t krow_max;
-  if (it < tw.n_gt) {
-    ksrc = Kg + (size_t)(tw.base + key0) * D;
-    krow_max = (int64_t)tw.nr - 1 - key0;
-  } else {
-    ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
-    krow_max = tw.last_pos - key0;
-  }
-#pragma unroll
-  for (int i = 0; i < PER_WAVE; ++i) {
-    const int q = wv * PER_WAVE + i;                // wave-uniform: which KB of the tile
-    const int cid = q * 64 + lane;                  // 16-byte chunk of the LDS tile this lane fills
-    const int r = cid / CPR, pch = cid % CPR;
-    const int swz = (CPR == 16) ? (r & 15) : ((r >> 1) & 7);
-    const int ch = pch ^ swz;                       // global chunk that belongs at this LDS position
-    const int rr = r > krow_max ? (int)krow_max : r;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + (size_t)rr * D + ch * 8),
-                                     (__attribute__((address_space(3))) void*)(kstage + q * 1024), 16, 0, 0);
-  }
-}
+  const uint16_t* vsrc;
+  int krow_max;                                     // last row of ksrc that may be read (later rows are masked keys)
+  unsigned char* stage;
 
-template <int D>
-__device__ __forceinline__ void dma_v_tile(const TileWalk& tw, int it, int wv, int lane,
-                                           const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
-                                           unsigned char* vstage) {
-  constexpr int PER_WAVE = D / 32;                  // the tile has D/8 wave-loads
-  const int64_t key0 = tw.key0(it);
-  const uint16_t* vsrc = it < tw.n_gt
-      ? Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN)
-      : Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
-#pragma unroll
-  for (int i = 0; i < PER_WAVE; ++i) {
-    const int q = wv * PER_WAVE + i;
-    const int cid = q * 64 + lane;
-    const int dd = cid >> 3, pch = cid & 7;
-    const int ch = pch ^ ((dd >> 1) & 7);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + (size_t)dd * kBN + ch * 8),
-                                     (__attribute__((address_space(3))) void*)(vstage + q * 1024), 16, 0, 0);
+  __device__ __forceinline__ TileDma(const TileWalk& tw, int it, const uint16_t* __restrict__ Kg,
+                                     const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
+                                     const uint16_t* __restrict__ Vt, unsigned char* stage_)
+      : stage(stage_) {
+    const int64_t key0 = tw.key0(it);
+    int64_t kmax;
+    if (it < tw.n_gt) {
+      ksrc = Kg + (size_t)(tw.base + key0) * D;
+      kmax = (int64_t)tw.nr - 1 - key0;
+      vsrc = Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN);
+    } else {
+      ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
+      kmax = tw.last_pos - key0;
+      vsrc = Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+    }
+    krow_max = (int)(kmax < kBN - 1 ? kmax : kBN - 1);
   }
-}
 
-template <int D, int QT>
-__global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_kernel(
+  __device__ __forceinline__ void issue(int j, int wv, int lane) const {
+    if (j < NK) {
+      const int q = wv * NK + j;                    // wave-uniform: which KB of the K tile
+      const int cid = q * 64 + lane;                // 16-byte chunk of the LDS tile this lane fills
+      const int r = cid / CPR, pch = cid % CPR;
+      const int swz = (CPR == 16) ? (r & 15) : ((r >> 1) & 7);
+      const int ch = pch ^ swz;                     // global chunk that belongs at this LDS position
+      const int rr = r > krow_max ? krow_max : r;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + rr * D + ch * 8),
+                                       (__attribute__((address_space(3))) void*)(stage + q * 1024), 16, 0, 0);
+    } else {
+      const int q = wv * NV + (j - NK);
+      const int cid = q * 64 + lane;
+      const int dd = cid >> 3, pch = cid & 7;
+      const int ch = pch ^ ((dd >> 1) & 7);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + dd * kBN + ch * 8),
+                                       (__attribute__((address_space(3))) void*)(stage + kBN * D * 2 + q * 1024), 16, 0,
+                                       0);
+    }
+  }
+  __device__ __forceinline__ void issue_all(int wv, int lane) const {
+#pragma unroll
+    for (int j = 0; j < N; ++j) issue(j, wv, lane);
+  }
+};
+
+template <int D, int QT, int NW>
+__global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
   constexpr int BMW = 32 * QT;           // queries per wave
-  constexpr int BM = 4 * BMW;            // queries per workgroup
+  constexpr int BM = NW * BMW;           // queries per workgroup
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
   // Two stages of {K tile, V^T tile}.  Rows are not padded; the 16-byte chunk
@@ -283,19 +293,17 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
 #pragma unroll
   for (int sg = 0; sg < 4; ++sg) vfa[sg] = v_off(c, 2 * sg + hh);
 
-  dma_k_tile<D>(tw, 0, wv, lane, Kg, K, lds);
-  dma_v_tile<D>(tw, 0, wv, lane, Vgt, Vt, lds + KBYTES);
+  using Dma = TileDma<D, NW>;
+  Dma(tw, 0, Kg, K, Vgt, Vt, lds).issue_all(wv, lane);
 
   for (int it = 0; it < n_tiles; ++it) {
     // this wave's direct loads of tile `it` have landed; after the barrier everyone's
     // have, and everyone has finished reading the other stage (tile it-1)
     __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
     __syncthreads();
-    if (it + 1 < n_tiles) {
-      unsigned char* st = lds + ((it + 1) & 1) * (KBYTES + VBYTES);
-      dma_k_tile<D>(tw, it + 1, wv, lane, Kg, K, st);
-      dma_v_tile<D>(tw, it + 1, wv, lane, Vgt, Vt, st + KBYTES);
-    }
+    // the next tile's loads are issued one per MFMA pair inside the S^T loop below
+    const bool has_next = it + 1 < n_tiles;
+    const Dma dma(tw, has_next ? it + 1 : it, Kg, K, Vgt, Vt, lds + ((it + 1) & 1) * (KBYTES + VBYTES));
     const bool is_glob = it < n_gt;
     const int64_t key0 = tw.key0(it);
     const unsigned char* kb = lds + (it & 1) * (KBYTES + VBYTES);
@@ -310,7 +318,10 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       active = key0 <= wave_last && key0 + kBN - 1 > wave_first - w;
       masked = !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
     }
-    if (!active) continue;
+    if (!active) {
+      if (has_next) dma.issue_all(wv, lane);
+      continue;
+    }
 
     // ---- S^T = K Q^T for the 64 keys (two 32-key sub-tiles).  The two accumulation
     // chains alternate and the K fragments are read four MFMAs ahead.
@@ -326,19 +337,25 @@ __global__ __launch_bounds__(kPfThreads, (QT == 1 ? 2 : 1)) void prefill_mfma_ke
       auto kfrag = [&](int i) {
         return *reinterpret_cast<const bf16x8_t*>(kb + kfa[i >> 1] + (i & 1) * (32 * D * 2));
       };
-      bf16x8_t fr[kFragAhead];
+      auto s_phase = [&](auto with_dma) {
+        bf16x8_t fr[kFragAhead];
 #pragma unroll
-      for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
+        for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
 #pragma unroll
-      for (int i = 0; i < 2 * KK; ++i) {
-        const int sub = i & 1, kk = i >> 1;
+        for (int i = 0; i < 2 * KK; ++i) {
+          const int sub = i & 1, kk = i >> 1;
 #pragma unroll
-        for (int t = 0; t < QT; ++t)
-          s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[t][kk], s[t][sub], 0, 0, 0);
-        if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
-      }
+          for (int t = 0; t < QT; ++t)
+            s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[t][kk], s[t][sub], 0, 0, 0);
+          if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
+          if constexpr (decltype(with_dma)::value) {
+            // loads spread as evenly as the counts allow: load j after MFMA pair j * KK / N
+            if (sub == 1 && (kk * Dma::N) % KK == 0 && kk * Dma::N / KK < Dma::N) dma.issue(kk * Dma::N / KK, wv, lane);
+          }
+        }
+      };
+      if (has_next) s_phase(std::true_type{}); else s_phase(std::false_type{});
     }
-    // first V^T fragments: issued now, consumed after the softmax
     // fragment (sl, sg) sits at vfa[sg] + sl * 32 rows
     auto vfrag = [&](int j) {
       return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
@@ -497,9 +514,13 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
 
   constexpr int QT = 1;                  // 32 queries per wave (QT = 2 needs more than 256 registers per lane)
-  constexpr int BM = 128 * QT;
+#ifndef TCA_PF_WAVES
+#define TCA_PF_WAVES 4
+#endif
+  constexpr int NW = TCA_PF_WAVES;       // wavefronts per workgroup
+  constexpr int BM = NW * 32 * QT;
   const int n_qt = (int)((n_queries + BM - 1) / BM);
-  hipLaunchKernelGGL((prefill_mfma_kernel<D, QT>), dim3((unsigned)n_qt * Hq), dim3(kPfThreads), 0, st, Q,
+  hipLaunchKernelGGL((prefill_mfma_kernel<D, QT, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                      q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
                      Hq / Hkv, w, (float)logit_scale(prm), O, lse);
 }
