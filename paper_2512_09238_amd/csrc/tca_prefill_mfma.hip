@@ -144,12 +144,14 @@ template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
 }
 __device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + ((ch ^ ((dd >> 1) & 7)) << 4); }
 
-// Direct global->LDS copies of one tile (no staging registers, no ds_write): every
+// Direct global->LDS copies of tiles (no staging registers, no ds_write): every
 // lane of a wave-load deposits 16 bytes at consecutive LDS addresses, so the lane
 // that fills LDS chunk position p of a row fetches the global chunk the XOR
-// swizzle assigns to p.  A tile is CPR wave-loads of K plus D/8 of V^T; each wave
-// issues its share one at a time (`issue(j)`), so that the loads can be spread
-// between the MFMAs instead of queueing up behind the barrier.
+// swizzle assigns to p.  A K tile is CPR wave-loads, a V^T tile D/8; each wave
+// issues its share one load at a time (`issue(j)`), so that the loads can be
+// spread between the MFMAs instead of queueing up behind the barrier.  One
+// object describes the K tile `itk` and the V^T tile `itv` (the two rings run
+// one tile apart).
 template <int D, int NW>
 struct TileDma {
   static constexpr int CPR = D / 8;
@@ -160,24 +162,26 @@ struct TileDma {
   const uint16_t* ksrc;
   const uint16_t* vsrc;
   int krow_max;                                     // last row of ksrc that may be read (later rows are masked keys)
-  unsigned char* stage;
+  unsigned char* kstage;
+  unsigned char* vstage;
 
-  __device__ __forceinline__ TileDma(const TileWalk& tw, int it, const uint16_t* __restrict__ Kg,
+  __device__ __forceinline__ TileDma(const TileWalk& tw, int itk, int itv, const uint16_t* __restrict__ Kg,
                                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
-                                     const uint16_t* __restrict__ Vt, unsigned char* stage_)
-      : stage(stage_) {
-    const int64_t key0 = tw.key0(it);
+                                     const uint16_t* __restrict__ Vt, unsigned char* kstage_, unsigned char* vstage_)
+      : kstage(kstage_), vstage(vstage_) {
+    const int64_t kkey0 = tw.key0(itk);
     int64_t kmax;
-    if (it < tw.n_gt) {
-      ksrc = Kg + (size_t)(tw.base + key0) * D;
-      kmax = (int64_t)tw.nr - 1 - key0;
-      vsrc = Vgt + (size_t)(tw.vgt_tile0 + it) * (size_t)(D * kBN);
+    if (itk < tw.n_gt) {
+      ksrc = Kg + (size_t)(tw.base + kkey0) * D;
+      kmax = (int64_t)tw.nr - 1 - kkey0;
     } else {
-      ksrc = K + ((size_t)tw.kvh * tw.kv_stride + key0) * D;
-      kmax = tw.last_pos - key0;
-      vsrc = Vt + ((size_t)tw.kvh * tw.dense_tiles + (key0 / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+      ksrc = K + ((size_t)tw.kvh * tw.kv_stride + kkey0) * D;
+      kmax = tw.last_pos - kkey0;
     }
     krow_max = (int)(kmax < kBN - 1 ? kmax : kBN - 1);
+    vsrc = itv < tw.n_gt
+        ? Vgt + (size_t)(tw.vgt_tile0 + itv) * (size_t)(D * kBN)
+        : Vt + ((size_t)tw.kvh * tw.dense_tiles + (tw.key0(itv) / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
   }
 
   __device__ __forceinline__ void issue(int j, int wv, int lane) const {
@@ -189,15 +193,14 @@ struct TileDma {
       const int ch = pch ^ swz;                     // global chunk that belongs at this LDS position
       const int rr = r > krow_max ? krow_max : r;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + rr * D + ch * 8),
-                                       (__attribute__((address_space(3))) void*)(stage + q * 1024), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(kstage + q * 1024), 16, 0, 0);
     } else {
       const int q = wv * NV + (j - NK);
       const int cid = q * 64 + lane;
       const int dd = cid >> 3, pch = cid & 7;
       const int ch = pch ^ ((dd >> 1) & 7);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + dd * kBN + ch * 8),
-                                       (__attribute__((address_space(3))) void*)(stage + kBN * D * 2 + q * 1024), 16, 0,
-                                       0);
+                                       (__attribute__((address_space(3))) void*)(vstage + q * 1024), 16, 0, 0);
     }
   }
   __device__ __forceinline__ void issue_all(int wv, int lane) const {
@@ -206,7 +209,13 @@ struct TileDma {
   }
 };
 
-template <int D, int QT, int NW>
+// Software pipeline over the tiles of a workgroup (tile t = 0 .. n_tiles-1):
+//   iteration t :  S(t+1) = K(t+1) Q^T      (MFMA)     }  one basic block: the MFMAs of the
+//                  P(t)   = softmax step on S(t) (VALU) }  next tile run under this tile's exps
+//                  O     += V(t)^T P(t)     (MFMA)
+// K(t+2) and V^T(t+1) are copied global -> LDS during iteration t.  The K ring and
+// the V^T ring hold two tiles each; one barrier per iteration.
+template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
@@ -215,14 +224,14 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     uint16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
-  constexpr int BMW = 32 * QT;           // queries per wave
-  constexpr int BM = NW * BMW;           // queries per workgroup
+  constexpr int BM = NW * 32;            // queries per workgroup, 32 per wave
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
-  // Two stages of {K tile, V^T tile}.  Rows are not padded; the 16-byte chunk
-  // index is XOR-swizzled with the row so that the b128 reads of 16 consecutive
-  // rows at one chunk column fall into distinct banks.
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * (KBYTES + VBYTES)];
+  // Rows are not padded; the 16-byte chunk index is XOR-swizzled with the row so that
+  // the b128 reads of 16 consecutive rows at one chunk column fall into distinct banks.
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * KBYTES + 2 * VBYTES];
+  unsigned char* const kring = lds;
+  unsigned char* const vring = lds + 2 * KBYTES;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index, scalar
@@ -236,225 +245,211 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const int64_t last_row = n_queries - 1;
   const float sl2e = scale * 1.4426950408889634f;
 
-  // ---- per-lane query state
-  int64_t qpos[QT];
-  int nvis[QT];
-  bf16x8_t qf[QT][KK];
+  // ---- per-lane query state (lane column c = one query)
   const int64_t base = ph.offs[h];
   const int nr = n_rows[h];
   const size_t vgt_tile0 = (size_t)ph.tile_off[h];
+  int64_t qrow_i = r0 + wv * 32 + c;
+  if (qrow_i > last_row) qrow_i = last_row;         // clamped rows compute a duplicate; never stored
+  const int64_t qpos = q_pos0 + qrow_i;
+  const int nvis = count_le_i32(idx + base, nr, qpos - w);
+  bf16x8_t qf[KK];
+  {
+    const uint16_t* qrow = Q + ((size_t)h * n_queries + qrow_i) * D;
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    int64_t r = r0 + wv * BMW + t * 32 + c;
-    if (r > last_row) r = last_row;                 // clamped rows compute a duplicate; never stored
-    qpos[t] = q_pos0 + r;
-    nvis[t] = count_le_i32(idx + base, nr, qpos[t] - w);
-    const uint16_t* qrow = Q + ((size_t)h * n_queries + r) * D;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qf[t][kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
   }
   // wave-level visibility bounds (queries ascend with the lane index c; clamped rows repeat the last)
-  const int64_t wave_first = q_pos0 + i64min(r0 + wv * BMW, last_row);
-  const int64_t wave_last = q_pos0 + i64min(r0 + wv * BMW + BMW - 1, last_row);
+  const int64_t wave_first = q_pos0 + i64min(r0 + wv * 32, last_row);
+  const int64_t wave_last = q_pos0 + i64min(r0 + wv * 32 + 31, last_row);
   const int64_t wg_last = q_pos0 + i64min(r0 + BM - 1, last_row);
   const int64_t wg_first = q_pos0 + r0;
   // the searches below take wave-uniform arguments; readfirstlane keeps the results scalar
   const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wave_first - w));  // visible to every query of the wave
-  const int nv_wave_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wave_last - w));   // visible to at least one
   const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wg_last - w));
   const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
   const int64_t win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
   const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
   const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
 
-  // ---- staging: direct global -> LDS loads, the next tile in flight while this one is computed
   TileWalk tw;
   tw.n_gt = n_gt; tw.wt0 = wt0; tw.base = base; tw.nr = nr; tw.vgt_tile0 = vgt_tile0; tw.kvh = kvh;
   tw.kv_stride = kv_stride; tw.last_pos = q_pos0 + last_row; tw.dense_tiles = dense_tiles;
   tw.dense_tile0 = dense_tile0;
+  using Dma = TileDma<D, NW>;
 
-  f32x16_t o[QT][DS];
-  float m[QT], l[QT];
+  f32x16_t o[DS];
+  float m = -INFINITY, l = 0.f;
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    m[t] = -INFINITY;
-    l[t] = 0.f;
+  for (int sl = 0; sl < DS; ++sl)
 #pragma unroll
-    for (int s = 0; s < DS; ++s)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[t][s][r] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) o[sl][r] = 0.f;
 
-  // per-lane LDS byte offsets of the MFMA fragments inside a stage (the rest is compile-time constant)
+  // per-lane LDS byte offsets of the MFMA fragments inside a tile (the rest is compile-time constant):
+  // K fragment (sub, kk) sits at kfa[kk] + sub * 32 rows, V^T fragment (sl, sg) at vfa[sg] + sl * 32 rows;
+  // the swizzles depend on the row only through c
   int kfa[KK], vfa[4];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) kfa[kk] = k_off<D>(c, 2 * kk + hh);
 #pragma unroll
   for (int sg = 0; sg < 4; ++sg) vfa[sg] = v_off(c, 2 * sg + hh);
 
-  using Dma = TileDma<D, NW>;
-  Dma(tw, 0, Kg, K, Vgt, Vt, lds).issue_all(wv, lane);
+  // S^T = K Q^T for the 64 keys of the tile at kb (two 32-key sub-tiles = two accumulation
+  // chains that alternate; fragments read kFragAhead MFMAs ahead); between_pairs(kk) runs after
+  // the kk-th pair of MFMAs (the place where the tile copies are issued)
+  auto s_tile = [&](const unsigned char* kb, f32x16_t (&s)[2], auto between_pairs) {
+    auto kfrag = [&](int i) {
+      return *reinterpret_cast<const bf16x8_t*>(kb + kfa[i >> 1] + (i & 1) * (32 * D * 2));
+    };
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+    bf16x8_t fr[kFragAhead];
+#pragma unroll
+    for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
+#pragma unroll
+    for (int i = 0; i < 2 * KK; ++i) {
+      const int sub = i & 1, kk = i >> 1;
+      s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[kk], s[sub], 0, 0, 0);
+      if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
+      if (sub == 1) between_pairs(kk);
+    }
+  };
 
-  for (int it = 0; it < n_tiles; ++it) {
-    // this wave's direct loads of tile `it` have landed; after the barrier everyone's
-    // have, and everyone has finished reading the other stage (tile it-1)
+  // One pipeline step: tile `it` (scores in sc) goes through softmax and P V; the scores of tile it+1 go to sn.
+  auto step = [&](int it, f32x16_t (&sc)[2], f32x16_t (&sn)[2]) {
+    // the loads issued during the previous step (K(it+1), V^T(it)) have landed for this wave; after the
+    // barrier for every wave, and every wave is done reading K(it) and V^T(it-1)
     __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
     __syncthreads();
-    // the next tile's loads are issued one per MFMA pair inside the S^T loop below
-    const bool has_next = it + 1 < n_tiles;
-    const Dma dma(tw, has_next ? it + 1 : it, Kg, K, Vgt, Vt, lds + ((it + 1) & 1) * (KBYTES + VBYTES));
+    const int last = n_tiles - 1;
+    const Dma dma(tw, it + 2 < last ? it + 2 : last, it + 1 < last ? it + 1 : last, Kg, K, Vgt, Vt,
+                  kring + (it & 1) * KBYTES, vring + ((it + 1) & 1) * VBYTES);   // past the end: a harmless reload
+    const unsigned char* kb = kring + ((it + 1) & 1) * KBYTES;
+    const unsigned char* vb = vring + (it & 1) * VBYTES;
     const bool is_glob = it < n_gt;
     const int64_t key0 = tw.key0(it);
-    const unsigned char* kb = lds + (it & 1) * (KBYTES + VBYTES);
-    const unsigned char* vb = kb + KBYTES;
 
-    // ---- does this wave have anything to do in the tile, and does it need a mask?
-    bool active, masked;
-    if (is_glob) {
-      active = key0 < nv_wave_hi;
-      masked = key0 + kBN > nv_wave_lo;
-    } else {
-      active = key0 <= wave_last && key0 + kBN - 1 > wave_first - w;
-      masked = !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
-    }
-    if (!active) {
-      if (has_next) dma.issue_all(wv, lane);
-      continue;
-    }
-
-    // ---- S^T = K Q^T for the 64 keys (two 32-key sub-tiles).  The two accumulation
-    // chains alternate and the K fragments are read four MFMAs ahead.
-    f32x16_t s[QT][2];
-#pragma unroll
-    for (int t = 0; t < QT; ++t)
+    // ---- mask of tile `it` (boundary tiles only; a tile this wave sees nothing of is fully masked)
+    const bool masked = is_glob ? (key0 + kBN > nv_wave_lo)
+                                : !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
+    if (masked) {
+      // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
+      int lo, hi;
+      if (is_glob) {
+        lo = 0;
+        hi = (int)i64min((int64_t)nvis - key0, kBN);
+      } else {
+        const int64_t l64 = qpos - w + 1 - key0, h64 = qpos + 1 - key0;
+        lo = (int)(l64 < 0 ? 0 : (l64 > kBN ? kBN : l64));
+        hi = (int)(h64 < 0 ? 0 : (h64 > kBN ? kBN : h64));
+      }
+      const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
+      const int rel0 = 4 * hh - lo;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[t][sub][r] = 0.f;
-    {
-      // fragment (sub, kk) sits at kfa[kk] + sub * 32 rows: the swizzle depends on the row only through c
-      auto kfrag = [&](int i) {
-        return *reinterpret_cast<const bf16x8_t*>(kb + kfa[i >> 1] + (i & 1) * (32 * D * 2));
-      };
-      auto s_phase = [&](auto with_dma) {
-        bf16x8_t fr[kFragAhead];
-#pragma unroll
-        for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
-#pragma unroll
-        for (int i = 0; i < 2 * KK; ++i) {
-          const int sub = i & 1, kk = i >> 1;
-#pragma unroll
-          for (int t = 0; t < QT; ++t)
-            s[t][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[t][kk], s[t][sub], 0, 0, 0);
-          if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
-          if constexpr (decltype(with_dma)::value) {
-            // loads spread as evenly as the counts allow: load j after MFMA pair j * KK / N
-            if (sub == 1 && (kk * Dma::N) % KK == 0 && kk * Dma::N / KK < Dma::N) dma.issue(kk * Dma::N / KK, wv, lane);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
+          sc[sub][r] = kr < span ? sc[sub][r] : -INFINITY;
         }
-      };
-      if (has_next) s_phase(std::true_type{}); else s_phase(std::false_type{});
     }
-    // fragment (sl, sg) sits at vfa[sg] + sl * 32 rows
+
+    // ---- running maximum of the query (lane column); rescale only when some lane's maximum moved
+    float mx;
+    {
+      float m8[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) m8[r] = fmaxf(fmaxf(sc[0][r], sc[0][r + 8]), fmaxf(sc[1][r], sc[1][r + 8]));
+      mx = fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7])));
+    }
+    mx = half_max(mx);
+    const float m_new = fmaxf(m, mx);
+    if (__any(m_new > m)) {
+      const float alpha = (m_new > m) ? __builtin_amdgcn_exp2f((m - m_new) * sl2e) : 1.f;
+      l *= alpha;
+#pragma unroll
+      for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[sl][r] *= alpha;
+      m = m_new;
+    }
+    const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
+
+    // ---- scores of the next tile (MFMA) under the exponentials of this one (VALU)
+    s_tile(kb, sn, [&](int kk) {       // loads spread as evenly as the counts allow: load j after pair j * KK / N
+      if ((kk * Dma::N) % KK == 0 && kk * Dma::N / KK < Dma::N) dma.issue(kk * Dma::N / KK, wv, lane);
+    });
+    bf16x8_t pf[2][2];
+    float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        bf16x8_t pk;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(sc[sub][8 * g + e], sl2e, -mb));
+          ls[e & 3] += p;
+          pk[e] = (__bf16)p;
+        }
+        pf[sub][g] = pk;
+      }
+    l += (ls[0] + ls[1]) + (ls[2] + ls[3]);
+
+    // ---- O^T += V^T P^T: the DS accumulation chains alternate; V^T fragments are read ahead
     auto vfrag = [&](int j) {
       return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
     };
     bf16x8_t vfr[kFragAhead];
 #pragma unroll
-    for (int j = 0; j < kFragAhead; ++j)
-      vfr[j] = vfrag(j);
-
-    // ---- online softmax per query (lane column), P^T packed to bf16
-    bf16x8_t pf[QT][2][2];
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      if (masked) {
-        // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
-        int lo, hi;
-        if (is_glob) {
-          lo = 0;
-          hi = (int)i64min((int64_t)nvis[t] - key0, kBN);
-        } else {
-          const int64_t l64 = qpos[t] - w + 1 - key0, h64 = qpos[t] + 1 - key0;
-          lo = (int)(l64 < 0 ? 0 : (l64 > kBN ? kBN : l64));
-          hi = (int)(h64 < 0 ? 0 : (h64 > kBN ? kBN : h64));
-        }
-        const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
-        const int rel0 = 4 * hh - lo;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
-            s[t][sub][r] = kr < span ? s[t][sub][r] : -INFINITY;
-          }
-      }
-      float mx;
-      {
-        float m8[8];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) m8[r] = fmaxf(fmaxf(s[t][0][r], s[t][0][r + 8]), fmaxf(s[t][1][r], s[t][1][r + 8]));
-        mx = fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7])));
-      }
-      mx = half_max(mx);
-      const float m_new = fmaxf(m[t], mx);
-      if (__any(m_new > m[t])) {
-        const float alpha = (m_new > m[t]) ? __builtin_amdgcn_exp2f((m[t] - m_new) * sl2e) : 1.f;
-        l[t] *= alpha;
-#pragma unroll
-        for (int sl = 0; sl < DS; ++sl)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[t][sl][r] *= alpha;
-        m[t] = m_new;
-      }
-      const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
-      float ls[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          bf16x8_t pk;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[t][sub][8 * g + e], sl2e, -mb));
-            ls[e & 3] += p;
-            pk[e] = (__bf16)p;
-          }
-          pf[t][sub][g] = pk;
-        }
-      l[t] += (ls[0] + ls[1]) + (ls[2] + ls[3]);
-    }
-
-    // ---- O^T += V^T P^T: the DS accumulation chains alternate; V^T fragments are read ahead
+    for (int j = 0; j < kFragAhead; ++j) vfr[j] = vfrag(j);
 #pragma unroll
     for (int j = 0; j < 4 * DS; ++j) {
       const int sl = j % DS, sg = j / DS;           // sg = sub*2 + g: 16 keys
-#pragma unroll
-      for (int t = 0; t < QT; ++t)
-        o[t][sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[t][sg >> 1][sg & 1], o[t][sl], 0, 0, 0);
+      o[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[sg >> 1][sg & 1], o[sl], 0, 0, 0);
       if (j + kFragAhead < 4 * DS) vfr[j % kFragAhead] = vfrag(j + kFragAhead);
     }
+  };
+
+  // ---- prologue: K(0), V^T(0) in; S(0) computed while K(1) comes in
+  f32x16_t sa[2], sb[2];
+  {
+    const Dma first(tw, 0, 0, Kg, K, Vgt, Vt, kring, vring);
+    first.issue_all(wv, lane);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    const int t1 = n_tiles > 1 ? 1 : 0;
+    const Dma second(tw, t1, t1, Kg, K, Vgt, Vt, kring + KBYTES, vring + VBYTES);
+    s_tile(kring, sa, [&](int kk) {     // K(1) only; V^T(1) is step 0's load
+      if (kk < Dma::NK) second.issue(kk, wv, lane);
+    });
   }
+  for (int it = 0; it < n_tiles; it += 2) {
+    step(it, sa, sb);
+    if (it + 1 < n_tiles) step(it + 1, sb, sa);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);             // no copy into this workgroup's LDS may outlive it
 
   // ---- normalise and store
+  {
+    const int64_t r = r0 + wv * 32 + c;
+    const float lt = half_sum(l);
+    if (r <= last_row) {
+      const float inv = 1.f / lt;
+      uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
 #pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    const int64_t r = r0 + wv * BMW + t * 32 + c;
-    const float lt = half_sum(l[t]);
-    if (r > last_row) continue;
-    const float inv = 1.f / lt;
-    uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
+      for (int sl = 0; sl < DS; ++sl)
 #pragma unroll
-    for (int sl = 0; sl < DS; ++sl)
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4_t pk;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4_t pk;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[t][sl][4 * q4 + j] * inv);
-        *reinterpret_cast<bf16x4_t*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
-      }
-    if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m[t] * scale + __logf(lt);
+          for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[sl][4 * q4 + j] * inv);
+          *reinterpret_cast<bf16x4_t*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
+        }
+      if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m * scale + __logf(lt);
+    }
   }
 }
 
@@ -513,14 +508,13 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
 
-  constexpr int QT = 1;                  // 32 queries per wave (QT = 2 needs more than 256 registers per lane)
 #ifndef TCA_PF_WAVES
 #define TCA_PF_WAVES 4
 #endif
   constexpr int NW = TCA_PF_WAVES;       // wavefronts per workgroup
-  constexpr int BM = NW * 32 * QT;
+  constexpr int BM = NW * 32;            // 32 queries per wave
   const int n_qt = (int)((n_queries + BM - 1) / BM);
-  hipLaunchKernelGGL((prefill_mfma_kernel<D, QT, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
+  hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                      q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
                      Hq / Hkv, w, (float)logit_scale(prm), O, lse);
 }
