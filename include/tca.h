@@ -154,6 +154,8 @@ int tca_select(const tca_params* prm, const void* q_last, const void* K, const v
  *   idx, Kg, Vg, offs, n_rows : as written by tca_select (n_rows: device int32 [Hq])
  *   lse    : device float [Hq, n_queries] or NULL: natural-log sum of exp of the scaled logits
  * TCA_BF16: bf16 MFMA products, fp32 softmax and accumulation.  TCA_F32: fp32 throughout.
+ * TCA_BF16 limit: (q_pos0 + n_queries + w + 128) * d * 2 bytes and every head's region must stay
+ * below 2 GiB (8M positions at d = 128); beyond that the call returns TCA_ERR_UNSUPPORTED.
  * Does not synchronise. */
 int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_queries,
                 const void* K, const void* V, int64_t kv_stride,

@@ -245,7 +245,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
     constexpr int SPLIT = kDecThreads / D;               // threads per output column
     const int col = tid % D, part = tid / D;
     float a = 0.f;
-    for (int x = part; x < n_slots; x += SPLIT) a += pp[(size_t)x * (D + 2) + 2 + col] * wgt[x];
+    for (int x = part; x < n_slots; x += SPLIT) {
+      const float wx = wgt[x];                           // an empty slot's columns were never written
+      if (wx != 0.f) a += pp[(size_t)x * (D + 2) + 2 + col] * wx;
+    }
     colsum[tid] = a;
     __syncthreads();
     if (tid < D) {

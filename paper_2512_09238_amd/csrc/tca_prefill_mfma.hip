@@ -1,8 +1,8 @@
 // bf16 MFMA flash-attention prefill over the global and local subsets (Eq. 2;
 // Alg. 2 line 7) for gfx950.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = one tile of BM = 128*QT
-// consecutive queries of one query head; wave v owns 32*QT of them.  The
+// Work decomposition.  One workgroup = 4 wavefronts = one tile of BM = 128
+// consecutive queries of one query head; wave v owns 32 of them.  The
 // workgroup walks 64-key tiles: first the head's compacted global rows (tiles
 // of the head's region of Kg), then the dense keys of the sliding window
 // (absolute 64-key tiles of K).  Visibility is a prefix test in both parts:
@@ -23,10 +23,10 @@
 //   O^T accumulators: C[d = 32*s + 8*(r/4)+4*hh+r%4][query = c]: every register of
 //                  a lane belongs to the same query, so rescaling is a per-lane scalar.
 //
-// Pipeline: two LDS stages of {K tile [64][D], V^T tile [D][64]} with XOR-swizzled
-// 16-byte chunks (conflict-free b128 reads without padding); the next tile is
-// copied global -> LDS directly (no staging registers) while the current one is
-// computed; one barrier per tile.
+// LDS holds a ring of two K tiles [64][D] and a ring of two V^T tiles [D][64] with
+// XOR-swizzled 16-byte chunks (conflict-free b128 reads without padding), filled by
+// direct global -> LDS loads.  The loop is software-pipelined by one tile (see the
+// kernel); one barrier per tile.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -126,17 +126,6 @@ __device__ __forceinline__ float half_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Where the 64-key tiles of one workgroup come from: first n_gt tiles of the
-// head's compacted region, then absolute dense tiles wt0, wt0+1, ...
-struct TileWalk {
-  int n_gt;
-  int64_t wt0, base, vgt_tile0, kv_stride, last_pos, dense_tile0;
-  int nr, kvh, dense_tiles;
-  __device__ __forceinline__ int64_t key0(int it) const {
-    return it < n_gt ? (int64_t)it * kBN : (wt0 + (it - n_gt)) * kBN;
-  }
-};
-
 // LDS byte offset of 16-byte chunk `ch` of K row r / V^T row dd (XOR swizzle, no padding)
 template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
   const int swz = (D / 8 == 16) ? (r & 15) : ((r >> 1) & 7);
@@ -144,77 +133,50 @@ template <int D> __device__ __forceinline__ int k_off(int r, int ch) {
 }
 __device__ __forceinline__ int v_off(int dd, int ch) { return dd * (kBN * 2) + ((ch ^ ((dd >> 1) & 7)) << 4); }
 
-// Direct global->LDS copies of tiles (no staging registers, no ds_write): every
-// lane of a wave-load deposits 16 bytes at consecutive LDS addresses, so the lane
-// that fills LDS chunk position p of a row fetches the global chunk the XOR
-// swizzle assigns to p.  A K tile is CPR wave-loads, a V^T tile D/8; each wave
-// issues its share one load at a time (`issue(j)`), so that the loads can be
-// spread between the MFMAs instead of queueing up behind the barrier.  One
-// object describes the K tile `itk` and the V^T tile `itv` (the two rings run
-// one tile apart).
+// Tile copies go global -> LDS directly (buffer loads with the LDS modifier: no
+// staging registers, no ds_write).  Every lane of a wave-load deposits 16 bytes at
+// consecutive LDS addresses, so the lane that fills LDS chunk position p of a row
+// fetches the global chunk the XOR swizzle assigns to p: a per-lane byte offset
+// inside the tile that never changes.  The tile itself is selected by the scalar
+// offset of the load, and rows past the end of a buffer read as zero (range check of
+// the buffer descriptor), so a copy costs no vector ALU work at all.  A K tile is CPR
+// wave-loads, a V^T tile D/8; each wave issues its share one load at a time, spread
+// between the MFMAs instead of queueing up behind the barrier.
 template <int D, int NW>
-struct TileDma {
+struct TileCopy {
   static constexpr int CPR = D / 8;
   static constexpr int NK = CPR / NW;               // K wave-loads per wave
   static constexpr int NV = D / 8 / NW;             // V^T wave-loads per wave
   static constexpr int N = NK + NV;
   static_assert(NK >= 1 && NV >= 1 && N <= D / 16, "too many or too few waves for this tile");
-  const uint16_t* ksrc;
-  const uint16_t* vsrc;
-  int krow_max;                                     // last row of ksrc that may be read (later rows are masked keys)
-  unsigned char* kstage;
-  unsigned char* vstage;
-
-  __device__ __forceinline__ TileDma(const TileWalk& tw, int itk, int itv, const uint16_t* __restrict__ Kg,
-                                     const uint16_t* __restrict__ K, const uint16_t* __restrict__ Vgt,
-                                     const uint16_t* __restrict__ Vt, unsigned char* kstage_, unsigned char* vstage_)
-      : kstage(kstage_), vstage(vstage_) {
-    const int64_t kkey0 = tw.key0(itk);
-    int64_t kmax;
-    if (itk < tw.n_gt) {
-      ksrc = Kg + (size_t)(tw.base + kkey0) * D;
-      kmax = (int64_t)tw.nr - 1 - kkey0;
-    } else {
-      ksrc = K + ((size_t)tw.kvh * tw.kv_stride + kkey0) * D;
-      kmax = tw.last_pos - kkey0;
-    }
-    krow_max = (int)(kmax < kBN - 1 ? kmax : kBN - 1);
-    vsrc = itv < tw.n_gt
-        ? Vgt + (size_t)(tw.vgt_tile0 + itv) * (size_t)(D * kBN)
-        : Vt + ((size_t)tw.kvh * tw.dense_tiles + (tw.key0(itv) / kBN - tw.dense_tile0)) * (size_t)(D * kBN);
+  // byte offset inside a K tile of the chunk this lane fetches in wave-load q
+  static __device__ __forceinline__ int k_lane_offset(int q, int lane) {
+    const int cid = q * 64 + lane;                  // 16-byte chunk of the LDS tile this lane fills
+    const int r = cid / CPR, pch = cid % CPR;
+    const int swz = (CPR == 16) ? (r & 15) : ((r >> 1) & 7);
+    return (r * D + (pch ^ swz) * 8) * 2;
   }
-
-  __device__ __forceinline__ void issue(int j, int wv, int lane) const {
-    if (j < NK) {
-      const int q = wv * NK + j;                    // wave-uniform: which KB of the K tile
-      const int cid = q * 64 + lane;                // 16-byte chunk of the LDS tile this lane fills
-      const int r = cid / CPR, pch = cid % CPR;
-      const int swz = (CPR == 16) ? (r & 15) : ((r >> 1) & 7);
-      const int ch = pch ^ swz;                     // global chunk that belongs at this LDS position
-      const int rr = r > krow_max ? krow_max : r;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ksrc + rr * D + ch * 8),
-                                       (__attribute__((address_space(3))) void*)(kstage + q * 1024), 16, 0, 0);
-    } else {
-      const int q = wv * NV + (j - NK);
-      const int cid = q * 64 + lane;
-      const int dd = cid >> 3, pch = cid & 7;
-      const int ch = pch ^ ((dd >> 1) & 7);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vsrc + dd * kBN + ch * 8),
-                                       (__attribute__((address_space(3))) void*)(vstage + q * 1024), 16, 0, 0);
-    }
-  }
-  __device__ __forceinline__ void issue_all(int wv, int lane) const {
-#pragma unroll
-    for (int j = 0; j < N; ++j) issue(j, wv, lane);
+  static __device__ __forceinline__ int v_lane_offset(int q, int lane) {
+    const int cid = q * 64 + lane;
+    const int dd = cid >> 3, pch = cid & 7;
+    return (dd * kBN + (pch ^ ((dd >> 1) & 7)) * 8) * 2;
   }
 };
 
-// Software pipeline over the tiles of a workgroup (tile t = 0 .. n_tiles-1):
+__device__ __forceinline__ void copy16_to_lds(__amdgpu_buffer_rsrc_t rsrc, int lane_off, int tile_off,
+                                              unsigned char* lds_dst) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds_dst, 16, lane_off,
+                                           tile_off, 0, 0);
+}
+
+// Software pipeline over the tiles of a workgroup (tile t = 0 .. n_tiles-1: first the
+// n_gt tiles of the head's compacted region, then the dense tiles of the window):
 //   iteration t :  S(t+1) = K(t+1) Q^T      (MFMA)     }  one basic block: the MFMAs of the
 //                  P(t)   = softmax step on S(t) (VALU) }  next tile run under this tile's exps
 //                  O     += V(t)^T P(t)     (MFMA)
 // K(t+2) and V^T(t+1) are copied global -> LDS during iteration t.  The K ring and
 // the V^T ring hold two tiles each; one barrier per iteration.
+// Positions and byte offsets are 32-bit here: the host checks (q_pos0 + n_queries) * D * 2 < 2^31.
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
@@ -248,11 +210,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   // ---- per-lane query state (lane column c = one query)
   const int64_t base = ph.offs[h];
   const int nr = n_rows[h];
-  const size_t vgt_tile0 = (size_t)ph.tile_off[h];
   int64_t qrow_i = r0 + wv * 32 + c;
   if (qrow_i > last_row) qrow_i = last_row;         // clamped rows compute a duplicate; never stored
-  const int64_t qpos = q_pos0 + qrow_i;
-  const int nvis = count_le_i32(idx + base, nr, qpos - w);
+  const int qpos = (int)(q_pos0 + qrow_i);
+  const int nvis = count_le_i32(idx + base, nr, (int64_t)qpos - w);
   bf16x8_t qf[KK];
   {
     const uint16_t* qrow = Q + ((size_t)h * n_queries + qrow_i) * D;
@@ -260,23 +221,61 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
   }
   // wave-level visibility bounds (queries ascend with the lane index c; clamped rows repeat the last)
-  const int64_t wave_first = q_pos0 + i64min(r0 + wv * 32, last_row);
-  const int64_t wave_last = q_pos0 + i64min(r0 + wv * 32 + 31, last_row);
-  const int64_t wg_last = q_pos0 + i64min(r0 + BM - 1, last_row);
-  const int64_t wg_first = q_pos0 + r0;
+  const int wave_first = (int)(q_pos0 + i64min(r0 + wv * 32, last_row));
+  const int wave_last = (int)(q_pos0 + i64min(r0 + wv * 32 + 31, last_row));
+  const int wg_last = (int)(q_pos0 + i64min(r0 + BM - 1, last_row));
+  const int wg_first = (int)(q_pos0 + r0);
+  const int last_pos = (int)(q_pos0 + last_row);
   // the searches below take wave-uniform arguments; readfirstlane keeps the results scalar
-  const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wave_first - w));  // visible to every query of the wave
-  const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, wg_last - w));
+  const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, (int64_t)wave_first - w));  // visible to every query of the wave
+  const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, (int64_t)wg_last - w));
   const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
-  const int64_t win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
-  const int64_t wt0 = win_lo / kBN, wt1 = wg_last / kBN;                 // absolute dense tiles [wt0, wt1]
-  const int n_tiles = n_gt + (int)(wt1 - wt0 + 1);
+  const int win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
+  const int wt0 = win_lo / kBN, wt1 = wg_last / kBN;                      // absolute dense tiles [wt0, wt1]
+  const int n_tiles = n_gt + (wt1 - wt0 + 1);
+  const int last = n_tiles - 1;
+  const int dshift = wt0 - n_gt;                   // tile t >= n_gt is the dense tile t + dshift
 
-  TileWalk tw;
-  tw.n_gt = n_gt; tw.wt0 = wt0; tw.base = base; tw.nr = nr; tw.vgt_tile0 = vgt_tile0; tw.kvh = kvh;
-  tw.kv_stride = kv_stride; tw.last_pos = q_pos0 + last_row; tw.dense_tiles = dense_tiles;
-  tw.dense_tile0 = dense_tile0;
-  using Dma = TileDma<D, NW>;
+  // ---- sources of the tile copies: one descriptor per buffer, the tile chosen by a scalar byte offset
+  using Copy = TileCopy<D, NW>;
+  constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
+  const __amdgpu_buffer_rsrc_t krs_g = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(Kg + (size_t)base * D), 0, nr * (D * 2), kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t krs_d = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(K + (size_t)kvh * kv_stride * D), 0, (last_pos + 1) * (D * 2), kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t vrs_g = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(Vgt + (size_t)ph.tile_off[h] * (D * kBN)), 0, n_gt * VBYTES, kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t vrs_d = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(Vt + (size_t)kvh * dense_tiles * (D * kBN)), 0, dense_tiles * VBYTES, kRsrcFlags);
+  const int vdshift = dshift - (int)dense_tile0;   // tile t >= n_gt is tile t + vdshift of the dense V^T buffer
+  int klo[Copy::NK], vlo[Copy::NV];                // this lane's byte offsets inside a tile, per wave-load
+#pragma unroll
+  for (int j = 0; j < Copy::NK; ++j) klo[j] = Copy::k_lane_offset(wv * Copy::NK + j, lane);
+#pragma unroll
+  for (int j = 0; j < Copy::NV; ++j) vlo[j] = Copy::v_lane_offset(wv * Copy::NV + j, lane);
+  // One K tile and one V^T tile to copy: descriptors and scalar offsets chosen once, then
+  // load(j) issues wave-load j of the K tile (j < NK) or of the V^T tile (j >= NK)
+  struct CopyJob {
+    __amdgpu_buffer_rsrc_t krs, vrs;
+    int koff, voff;
+    unsigned char* kdst;
+    unsigned char* vdst;
+  };
+  auto copy_job = [&](int tk, int tv, unsigned char* kstage, unsigned char* vstage) {
+    CopyJob j;
+    const bool kg = tk < n_gt, vg = tv < n_gt;
+    j.krs = kg ? krs_g : krs_d;
+    j.vrs = vg ? vrs_g : vrs_d;
+    j.koff = (tk + (kg ? 0 : dshift)) * KBYTES;
+    j.voff = (tv + (vg ? 0 : vdshift)) * VBYTES;
+    j.kdst = kstage + wv * (Copy::NK * 1024);
+    j.vdst = vstage + wv * (Copy::NV * 1024);
+    return j;
+  };
+  auto copy_load = [&](const CopyJob& job, int j) {
+    if (j < Copy::NK) copy16_to_lds(job.krs, klo[j], job.koff, job.kdst + j * 1024);
+    else copy16_to_lds(job.vrs, vlo[j - Copy::NK], job.voff, job.vdst + (j - Copy::NK) * 1024);
+  };
 
   f32x16_t o[DS];
   float m = -INFINITY, l = 0.f;
@@ -317,33 +316,42 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     }
   };
 
-  // One pipeline step: tile `it` (scores in sc) goes through softmax and P V; the scores of tile it+1 go to sn.
-  auto step = [&](int it, f32x16_t (&sc)[2], f32x16_t (&sn)[2]) {
+  // maximum over the 32 scores a lane holds of its query, then over the two lanes of the query
+  auto lane_max = [&](const f32x16_t (&s)[2]) {
+    float m8[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) m8[r] = fmaxf(fmaxf(s[0][r], s[0][r + 8]), fmaxf(s[1][r], s[1][r + 8]));
+    return half_max(fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7]))));
+  };
+
+  // One pipeline step: tile `it` (scores in sc, their unmasked maximum in mx_pre) goes through softmax
+  // and P V; the scores of tile it+1 go to sn, and their maximum is taken under the P V MFMAs.
+  auto step = [&](int it, f32x16_t (&sc)[2], f32x16_t (&sn)[2], float& mx_pre) {
     // the loads issued during the previous step (K(it+1), V^T(it)) have landed for this wave; after the
     // barrier for every wave, and every wave is done reading K(it) and V^T(it-1)
     __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
     __syncthreads();
-    const int last = n_tiles - 1;
-    const Dma dma(tw, it + 2 < last ? it + 2 : last, it + 1 < last ? it + 1 : last, Kg, K, Vgt, Vt,
-                  kring + (it & 1) * KBYTES, vring + ((it + 1) & 1) * VBYTES);   // past the end: a harmless reload
+    const int tk = it + 2 < last ? it + 2 : last, tv = it + 1 < last ? it + 1 : last;   // past the end: a harmless reload
+    const CopyJob job = copy_job(tk, tv, kring + (it & 1) * KBYTES, vring + ((it + 1) & 1) * VBYTES);
     const unsigned char* kb = kring + ((it + 1) & 1) * KBYTES;
     const unsigned char* vb = vring + (it & 1) * VBYTES;
     const bool is_glob = it < n_gt;
-    const int64_t key0 = tw.key0(it);
+    const int key0 = (it + (is_glob ? 0 : dshift)) * kBN;
 
     // ---- mask of tile `it` (boundary tiles only; a tile this wave sees nothing of is fully masked)
     const bool masked = is_glob ? (key0 + kBN > nv_wave_lo)
                                 : !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
+    float mx = mx_pre;
     if (masked) {
       // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
       int lo, hi;
       if (is_glob) {
         lo = 0;
-        hi = (int)i64min((int64_t)nvis - key0, kBN);
+        hi = nvis - key0 < kBN ? nvis - key0 : kBN;
       } else {
-        const int64_t l64 = qpos - w + 1 - key0, h64 = qpos + 1 - key0;
-        lo = (int)(l64 < 0 ? 0 : (l64 > kBN ? kBN : l64));
-        hi = (int)(h64 < 0 ? 0 : (h64 > kBN ? kBN : h64));
+        const int l32 = qpos - w + 1 - key0, h32 = qpos + 1 - key0;
+        lo = l32 < 0 ? 0 : (l32 > kBN ? kBN : l32);
+        hi = h32 < 0 ? 0 : (h32 > kBN ? kBN : h32);
       }
       const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
       const int rel0 = 4 * hh - lo;
@@ -354,17 +362,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
           const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
           sc[sub][r] = kr < span ? sc[sub][r] : -INFINITY;
         }
+      mx = lane_max(sc);
     }
 
     // ---- running maximum of the query (lane column); rescale only when some lane's maximum moved
-    float mx;
-    {
-      float m8[8];
-#pragma unroll
-      for (int r = 0; r < 8; ++r) m8[r] = fmaxf(fmaxf(sc[0][r], sc[0][r + 8]), fmaxf(sc[1][r], sc[1][r + 8]));
-      mx = fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7])));
-    }
-    mx = half_max(mx);
     const float m_new = fmaxf(m, mx);
     if (__any(m_new > m)) {
       const float alpha = (m_new > m) ? __builtin_amdgcn_exp2f((m - m_new) * sl2e) : 1.f;
@@ -378,8 +379,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
 
     // ---- scores of the next tile (MFMA) under the exponentials of this one (VALU)
-    s_tile(kb, sn, [&](int kk) {       // loads spread as evenly as the counts allow: load j after pair j * KK / N
-      if ((kk * Dma::N) % KK == 0 && kk * Dma::N / KK < Dma::N) dma.issue(kk * Dma::N / KK, wv, lane);
+    s_tile(kb, sn, [&](int kk) {       // copies spread as evenly as the counts allow: load j after pair j * KK / N
+      if ((kk * Copy::N) % KK == 0 && kk * Copy::N / KK < Copy::N) copy_load(job, kk * Copy::N / KK);
     });
     bf16x8_t pf[2][2];
     float ls[4] = {0.f, 0.f, 0.f, 0.f};
@@ -411,24 +412,27 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
       o[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[sg >> 1][sg & 1], o[sl], 0, 0, 0);
       if (j + kFragAhead < 4 * DS) vfr[j % kFragAhead] = vfrag(j + kFragAhead);
     }
+    mx_pre = lane_max(sn);              // vector ALU work for the shadow of the MFMAs above
   };
 
   // ---- prologue: K(0), V^T(0) in; S(0) computed while K(1) comes in
   f32x16_t sa[2], sb[2];
   {
-    const Dma first(tw, 0, 0, Kg, K, Vgt, Vt, kring, vring);
-    first.issue_all(wv, lane);
+    const CopyJob first = copy_job(0, 0, kring, vring);
+#pragma unroll
+    for (int j = 0; j < Copy::N; ++j) copy_load(first, j);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    const int t1 = n_tiles > 1 ? 1 : 0;
-    const Dma second(tw, t1, t1, Kg, K, Vgt, Vt, kring + KBYTES, vring + VBYTES);
+    const int t1 = last < 1 ? last : 1;
+    const CopyJob second = copy_job(t1, t1, kring + KBYTES, vring + VBYTES);
     s_tile(kring, sa, [&](int kk) {     // K(1) only; V^T(1) is step 0's load
-      if (kk < Dma::NK) second.issue(kk, wv, lane);
+      if (kk < Copy::NK) copy_load(second, kk);
     });
   }
+  float mx_pre = lane_max(sa);
   for (int it = 0; it < n_tiles; it += 2) {
-    step(it, sa, sb);
-    if (it + 1 < n_tiles) step(it + 1, sb, sa);
+    step(it, sa, sb, mx_pre);
+    if (it + 1 < n_tiles) step(it + 1, sb, sa, mx_pre);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);             // no copy into this workgroup's LDS may outlive it
 
@@ -508,10 +512,9 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
 
-#ifndef TCA_PF_WAVES
-#define TCA_PF_WAVES 4
-#endif
-  constexpr int NW = TCA_PF_WAVES;       // wavefronts per workgroup
+  // wavefronts per workgroup: 4 (two workgroups per CU) and 8 (one) run within 2 % of each other
+  // on a 128K prefill; 4 keeps twice as many workgroups in flight for short query ranges
+  constexpr int NW = 4;
   constexpr int BM = NW * 32;            // 32 queries per wave
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
@@ -523,6 +526,14 @@ int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, 
                         const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
                         const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,
                         bf16_t* O, float* lse, void* ws, hipStream_t st) {
+  // the kernel addresses tiles with 32-bit byte offsets inside each buffer
+  const int64_t row_bytes = (int64_t)prm->head_dim * 2;
+  int64_t max_rows = q_pos0 + n_queries + prm->window + 2 * kBN;
+  for (int h = 0; h < prm->n_q_heads; ++h)
+    if (offs[h + 1] - offs[h] + kBN > max_rows) max_rows = offs[h + 1] - offs[h] + kBN;
+  if (max_rows * row_bytes > (int64_t)INT32_MAX)
+    return fail(TCA_ERR_UNSUPPORTED, "tca_prefill (bf16): %lld rows of %lld bytes exceed 2 GiB per head buffer",
+                (long long)max_rows, (long long)row_bytes);
   auto u = [](const bf16_t* p) { return reinterpret_cast<const uint16_t*>(p); };
   if (prm->head_dim == 128)
     run_mfma<128>(prm, u(Q), q_pos0, n_queries, u(K), u(V), kv_stride, idx, u(Kg), u(Vg), offs, n_rows,
