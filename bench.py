@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of prefill_mfma_kernel on the default workload, from the rocprofv3
 # --pmc runs summarised in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB)
-PROFILED_PREFILL_TRAFFIC_BYTES = (5.156e7 * 2.0 + 1.0486e6) * 1024
+PROFILED_PREFILL_TRAFFIC_BYTES = (2.3440e7 * 2.0 + 1.0496e6) * 1024
 
 
 def log(*a):
@@ -101,6 +101,14 @@ def bench_prefill(args, tb, bufs, wl, torch):
     pf_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     ms_per_step = 1e3 * wall / args.steps
     log(f"[bench] step {ms_per_step:.3f} ms (select {sel_ms:.3f} ms, prefill {pf_ms:.3f} ms)")
+    # what the attention kernel's clock was, and what the matrix pipe sustains on this board with
+    # constant and with random operands (register-only loop, no memory traffic)
+    clock_ghz = tb.prefill_shader_clock_ghz(ws_pf)
+    wsp = bufs.workspace(tb.tca_probe_workspace_bytes())
+    probe_c = tb.tca_probe_mfma(False, 20000, wsp)
+    probe_r = tb.tca_probe_mfma(True, 20000, wsp)
+    log(f"[bench] shader clock during prefill_mfma_kernel {clock_ghz:.3f} GHz; MFMA probe: constants "
+        f"{probe_c[0]:.0f} TFLOP/s at {probe_c[1]:.2f} GHz, random operands {probe_r[0]:.0f} TFLOP/s at {probe_r[1]:.2f} GHz")
 
     idx_host = gb.idx.cpu().numpy()
     n_rows = gb.n_rows.cpu().numpy()
@@ -114,6 +122,7 @@ def bench_prefill(args, tb, bufs, wl, torch):
         "tokens_per_s": L / (ms_per_step * 1e-3), "pairs": pairs, "flops": flops, "tflops": tflops,
         "select_gbs": sel_bytes / (sel_ms * 1e-3) / 1e9, "select_bytes": sel_bytes,
         "budget_src": budget_src, "mean_budget": total / (Hq * L), "cfg": cfg,
+        "clock_ghz": clock_ghz, "probe_const": probe_c, "probe_random": probe_r,
     }
     host = {"x": x, "P": P, "idx": idx_host, "offs": gb.offs, "n_rows": n_rows, "O": O, "prm": prm, "budget": budget}
     return res, host
@@ -285,6 +294,13 @@ def main():
             "unit": "TFLOP/s", "frac": res["tflops"] / PEAK_BF16_TFLOPS,
             "traffic": PROFILED_PREFILL_TRAFFIC_BYTES if (res["L"] == 131072 and args.calibrate) else None,
             "flops_per_launch": res["flops"], "visible_pairs": res["pairs"],
+            "shader_clock_ghz": res["clock_ghz"],
+            "mfma_probe": {
+                "what": "register-only bf16 32x32x16 MFMA loop on every SIMD (tca_probe_mfma): TFLOP/s and shader clock",
+                "constant_operands": {"tflops": res["probe_const"][0], "ghz": res["probe_const"][1]},
+                "random_operands": {"tflops": res["probe_random"][0], "ghz": res["probe_random"][1]},
+            },
+            "frac_of_random_operand_probe": res["tflops"] / res["probe_random"][0] if res["probe_random"][0] else None,
         },
         "select_roofline": {
             "bound": "hbm", "achieved": res["select_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",

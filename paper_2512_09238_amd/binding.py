@@ -57,6 +57,8 @@ EXPORTS = {
     "tca_prefill_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64, C.c_int64]),
     "tca_decode_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int, C.c_int64]),
     "tca_calibrate_workspace_bytes": (C.c_size_t, [_P(tca_params), C.c_int64, C.c_int]),
+    "tca_probe_workspace_bytes": (C.c_size_t, []),
+    "tca_probe_mfma": (C.c_int, [C.c_int, C.c_int, _dbl_p, _dbl_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_select": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                              C.c_int64, _dbl_p, _i64_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -222,3 +224,26 @@ def tca_calibrate_budgets(prm, Qcal, Kcal, L_cal, M, sigma, tau, ws, stream=None
                                      a.ctypes.data_as(_dbl_p), n.ctypes.data_as(_i64_p),
                                      fb.ctypes.data_as(_i32_p), wsp, wsb, _stream(stream)))
     return {"p_star": p_star, "cand_idx": cand, "a": a, "n": n, "fallback": fb}
+
+
+# --------------------------------------------------------- diagnostics --
+def tca_probe_workspace_bytes() -> int:
+    return int(lib.tca_probe_workspace_bytes())
+
+
+def tca_probe_mfma(random_operands: bool, iters: int, ws, stream=None):
+    """Returns (TFLOP/s reached by a register-only bf16 MFMA loop, shader clock in GHz)."""
+    tf, ghz = C.c_double(0.0), C.c_double(0.0)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_probe_mfma(int(bool(random_operands)), int(iters), C.byref(tf), C.byref(ghz), wsp, wsb,
+                              _stream(stream)))
+    return tf.value, ghz.value
+
+
+def prefill_shader_clock_ghz(ws) -> float:
+    """Average shader clock during the last completed bf16 tca_prefill that used `ws`
+    (a torch uint8 tensor): its first two uint64 are cycle and 100 MHz tick sums."""
+    import torch
+    torch.cuda.synchronize()
+    c = ws[:16].view(torch.int64).cpu().numpy()
+    return float(c[0]) / (float(c[1]) * 10.0) if c[1] else 0.0

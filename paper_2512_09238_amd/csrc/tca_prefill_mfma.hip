@@ -61,11 +61,12 @@ template <int D>
 __global__ __launch_bounds__(256) void transpose_tiles_kernel(
     const uint16_t* __restrict__ src, int64_t group_stride_rows, const int32_t* group_valid,
     int64_t valid_all, int64_t first_row, uint16_t* __restrict__ dst, int tiles_per_group,
-    PrefillHeads ph, int mode) {
+    PrefillHeads ph, int mode, unsigned long long* clk) {
   // mode 0: global regions (group = query head; rows from ph.offs, valid rows from group_valid)
   // mode 1: dense K/V (group = KV head; absolute rows first_row + 64*tile, valid while < valid_all)
   __shared__ uint16_t tile[kBN][D + 8];
   const int g = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
+  if (clk && g == 0 && t == 0 && tid < 2) clk[tid] = 0;      // the attention kernel that follows accumulates here
   int64_t row0;
   int64_t n_valid;
   size_t out_tile;
@@ -183,10 +184,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
     int64_t dense_tile0, int dense_tiles, PrefillHeads ph, int Hq, int G, int w, float scale,
-    uint16_t* __restrict__ O, float* __restrict__ lse) {
+    uint16_t* __restrict__ O, float* __restrict__ lse, unsigned long long* __restrict__ clk) {
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
   constexpr int BM = NW * 32;            // queries per workgroup, 32 per wave
+  const unsigned long long clk_c0 = __builtin_readcyclecounter(), clk_r0 = __builtin_amdgcn_s_memrealtime();
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
   // Rows are not padded; the 16-byte chunk index is XOR-swizzled with the row so that
@@ -435,6 +437,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     if (it + 1 < n_tiles) step(it + 1, sb, sa, mx_pre);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);             // no copy into this workgroup's LDS may outlive it
+  if (tid == 0) {                                 // elapsed shader-clock cycles and 100 MHz ticks of this workgroup
+    atomicAdd(clk, (unsigned long long)__builtin_readcyclecounter() - clk_c0);
+    atomicAdd(clk + 1, (unsigned long long)__builtin_amdgcn_s_memrealtime() - clk_r0);
+  }
 
   // ---- normalise and store
   {
@@ -459,6 +465,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
 
 // ------------------------------------------------------------------ host side --
 struct MfmaWs {
+  unsigned long long* clk;   // {sum of workgroup shader-clock cycles, sum of workgroup 100 MHz ticks} of the last call
   uint16_t* Vgt;       // [g_tiles][D][64]
   uint16_t* Vt;        // [Hkv][dense_tiles][D][64]
   size_t bytes;
@@ -472,6 +479,7 @@ static MfmaWs carve_mfma_ws(void* ws, const tca_params* prm, int64_t g_tiles, in
   char* b = (char*)ws;
   size_t off = 0;
   const size_t tile_bytes = (size_t)prm->head_dim * kBN * 2;
+  m.clk = (unsigned long long*)(b + off); off = align_up(off + 2 * sizeof(unsigned long long), 256);
   m.Vgt = (uint16_t*)(b + off); off = align_up(off + (size_t)g_tiles * tile_bytes, 256);
   m.Vt = (uint16_t*)(b + off);  off = align_up(off + (size_t)prm->n_kv_heads * d_tiles * tile_bytes, 256);
   m.bytes = off;
@@ -508,18 +516,23 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
 
   if (max_tiles > 0)
     hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hq), dim3(256), 0, st, Vg, (int64_t)0,
-                       n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0);
+                       n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr);
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
-                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1);
+                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, mw.clk);
 
-  // wavefronts per workgroup: 4 (two workgroups per CU) and 8 (one) run within 2 % of each other
-  // on a 128K prefill; 4 keeps twice as many workgroups in flight for short query ranges
-  constexpr int NW = 4;
-  constexpr int BM = NW * 32;            // 32 queries per wave
-  const int n_qt = (int)((n_queries + BM - 1) / BM);
-  hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
-                     q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
-                     Hq / Hkv, w, (float)logit_scale(prm), O, lse);
+  // Wavefronts per workgroup.  Eight (256 queries, one workgroup per CU) halve the tile copies per
+  // query; the board is power-limited under this kernel and the lighter L2 -> LDS traffic lets it
+  // clock about 10 % higher.  Four (128 queries, two workgroups per CU) keep the chip full when
+  // there are few query tiles.
+  auto launch = [&](auto nw_tag) {
+    constexpr int NW = decltype(nw_tag)::value;
+    const int n_qt = (int)((n_queries + NW * 32 - 1) / (NW * 32));
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
+                       q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
+                       Hq / Hkv, w, (float)logit_scale(prm), O, lse, mw.clk);
+  };
+  if (((n_queries + 255) / 256) * Hq >= 1024) launch(std::integral_constant<int, 8>{});
+  else launch(std::integral_constant<int, 4>{});
 }
 
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
