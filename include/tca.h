@@ -135,8 +135,10 @@ size_t tca_calibrate_workspace_bytes(const tca_params* prm, int64_t L_cal, int M
  *   offs   : host [Hq+1]
  *   n_rows : device int32 [Hq], in/out (zero it before the first call)
  *   idx    : device int32 [offs[Hq]]; Kg, Vg: device [offs[Hq], d]
- * All scoring arithmetic is fp64, so the selected sets agree with an fp64
- * reference except at exact ties.  Does not synchronise. */
+ * All scoring arithmetic is fp64.  Inside a block, tokens whose scores agree to within
+ * 2^-44 relative are ordered by position, like exact ties (the ranking key drops the last
+ * 8 mantissa bits), so the selected sets agree with an fp64 reference except at such
+ * near-ties.  Does not synchronise. */
 int tca_select(const tca_params* prm, const void* q_last, const void* K, const void* V,
                int64_t kv_stride, int64_t pos0, int64_t n_tokens,
                const double* p, const int64_t* offs, int32_t* n_rows,
