@@ -80,3 +80,17 @@ def test_argument_errors_are_codes_not_crashes():
     assert rc == tb.TCA_ERR_INVALID and b"NULL" in tb.lib.tca_last_error()
     assert tb.lib.tca_strerror(-3) == b"workspace too small or misaligned"
     assert tb.tca_select_workspace_bytes(ok, 131072) > 4 * 131072
+
+
+def test_probe_rejects_bad_arguments_without_a_gpu():
+    import paper_2512_09238_amd.binding as tb
+    assert tb.tca_probe_workspace_bytes() >= 1024 * 24
+    tf, ghz = ctypes.c_double(0), ctypes.c_double(0)
+    rc = tb.lib.tca_probe_mfma(1, 100, ctypes.byref(tf), ctypes.byref(ghz), None, 0, None)
+    assert rc == tb.TCA_ERR_INVALID
+    rc = tb.lib.tca_probe_mfma(1, 100, None, None, ctypes.c_void_p(256), 1 << 20, None)
+    assert rc == tb.TCA_ERR_INVALID
+    rc = tb.lib.tca_probe_mfma(1, 0, ctypes.byref(tf), ctypes.byref(ghz), ctypes.c_void_p(256), 1 << 20, None)
+    assert rc == tb.TCA_ERR_INVALID
+    rc = tb.lib.tca_probe_mfma(1, 100, ctypes.byref(tf), ctypes.byref(ghz), ctypes.c_void_p(256), 16, None)
+    assert rc == tb.TCA_ERR_WORKSPACE

@@ -30,13 +30,18 @@ def _sample_positions(L, w, b, n, seed):
     return np.unique(np.concatenate([fixed, rng.integers(0, L, size=n)])).astype(np.int64)
 
 
-@pytest.mark.parametrize("cfg_id", [2, 3])
+# d = 64 with enough query tiles for the 8-wave workgroups of the MFMA kernel, ragged last tile
+WIDE_D64 = dict(kind="lowrank", Hq=32, Hkv=8, d=64, L=8192 + 77, b=64, w=512, alpha=0.5, sigma=1.0)
+
+
+@pytest.mark.parametrize("cfg_id", [2, 3, "d64"])
 def test_prefill_full_size_sampled_rows(tb, bufs, cfg_id):
-    c = wl.CONFIGS[cfg_id]
+    c = WIDE_D64 if cfg_id == "d64" else wl.CONFIGS[cfg_id]
     Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
     print("config", cfg_id, "L", L, flush=True)
-    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(cfg_id))
-    fr = wl.budget_fractions(wl.budget_seed(cfg_id), Hq)
+    seed_id = 6 if cfg_id == "d64" else cfg_id
+    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(seed_id))
+    fr = wl.budget_fractions(wl.budget_seed(seed_id), Hq)
     P_gpu = np.stack([tb.tca_config_from_budget(b, c["sigma"], f) for f in fr])
     P_orc = np.stack([orc.config_from_budget(b, c["sigma"], f) for f in fr])
     prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
@@ -61,6 +66,8 @@ def test_prefill_full_size_sampled_rows(tb, bufs, cfg_id):
             kg = gb.Kg[o + torch.from_numpy(pick).cuda()].cpu()
             assert torch.equal(kg, bufs.to_device(x["K"][h // (Hq // Hkv)][got[pick]], "cpu"))
     pos = _sample_positions(L, w, b, 12, 99)
+    if cfg_id == "d64":
+        pos = np.unique(np.concatenate([pos, np.arange(L - 80, L)]))   # the ragged last query tile in full
     Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
     worst = 0.0
     for h in range(Hq):
@@ -250,3 +257,29 @@ def test_config5_ragged_mixed_batch_sampled(tb, bufs):
         assert np.array_equal(mb.cache.idx[slot, o:o + n].cpu().numpy(), oc.S[0]), (i, h)
     print("max abs err prefill rows", worst_p, "decode", worst_d, flush=True)
     assert worst_p <= H.TOL["bf16"] and worst_d <= H.TOL["bf16"]
+
+
+def test_diagnostics_clock_and_mfma_probe(tb, bufs):
+    """The MFMA probe returns plausible figures, and a bf16 prefill leaves the cycle / tick
+    sums of its attention kernel at the head of its workspace."""
+    wsp = bufs.workspace(tb.tca_probe_workspace_bytes())
+    tf_c, ghz_c = tb.tca_probe_mfma(False, 2000, wsp)
+    tf_r, ghz_r = tb.tca_probe_mfma(True, 2000, wsp)
+    print("probe: constants %.0f TFLOP/s at %.2f GHz, random %.0f TFLOP/s at %.2f GHz" % (tf_c, ghz_c, tf_r, ghz_r), flush=True)
+    for tf, ghz in ((tf_c, ghz_c), (tf_r, ghz_r)):
+        assert 300.0 < tf < 2600.0 and 0.5 < ghz < 2.6
+        # 1024 SIMDs x 1024 flop per cycle at the measured clock bounds the rate
+        assert tf <= 1024 * 1024 * ghz * 1e9 / 1e12 * 1.05
+    with pytest.raises(tb.TcaError):
+        tb.tca_probe_mfma(True, 0, wsp)
+    Hq, Hkv, d, L, b, w = 8, 2, 128, 2048, 64, 256
+    x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "bf16", 77)
+    P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.3) for _ in range(Hq)])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P)
+    O = torch.empty_like(Qd)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+    ghz = tb.prefill_shader_clock_ghz(ws)
+    print("prefill shader clock %.3f GHz" % ghz, flush=True)
+    assert 0.3 < ghz < 2.6
