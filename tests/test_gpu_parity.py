@@ -40,6 +40,8 @@ SELECT_CASES = [
     ("centroid", 7, 1, 128, 2048 + 5, "f32", 256, 256, 13),       # G=7, largest block
     ("lowrank", 2, 2, 128, 300, "bf16", 2, 16, 14),               # smallest block, G=1
     ("lowrank", 8, 1, 64, 640, "f32", 64, 128, 15),               # G=8
+    ("lowrank", 2, 1, 64, 8192 + 1, "bf16", 2, 16, 16),           # 4096 blocks: the most one call ranks
+    ("lowrank", 128, 16, 64, 512, "bf16", 32, 64, 17),            # 128 query heads, G=8: the most heads
 ]
 
 
@@ -66,6 +68,17 @@ def test_select_matches_oracle(tb, bufs, case):
         kref = bufs.to_device(Kh[g][got], "cpu")
         vref = bufs.to_device(Vh[g][got], "cpu")
         assert torch.equal(kg, kref) and torch.equal(vg, vref)
+
+
+def test_select_rejects_more_blocks_than_it_can_rank(tb, bufs):
+    Hq, Hkv, d, b, w = 2, 1, 64, 2, 16
+    L = 2 * (4096 + 1)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "bf16", 18)
+    P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.5) for _ in range(Hq)])
+    with pytest.raises(tb.TcaError) as e:
+        H.gpu_select(tb, bufs, prm, x, P)
+    assert e.value.code == tb.TCA_ERR_UNSUPPORTED
 
 
 def test_select_degenerate_inputs(tb, bufs):
@@ -101,6 +114,7 @@ PREFILL_CASES = [
     ("lowrank", 8, 2, 128, 4096 + 100, "bf16", 128, 1024, 34),    # many key tiles, ragged query tile
     ("lowrank", 2, 1, 64, 2048 + 31, "bf16", 32, 512, 35),
     ("lowrank", 3, 1, 128, 100, "bf16", 16, 32, 36),              # shorter than one query tile
+    ("lowrank", 128, 16, 64, 300, "bf16", 32, 64, 37),            # 128 query heads, G=8
 ]
 
 
@@ -169,6 +183,7 @@ DECODE_CASES = [
     (4, 1, 64, 1024, "f32", 32, 128, 40, 1001),      # config 1 + decode across a block completion
     (8, 2, 128, 1500 + 100, "bf16", 128, 256, 140, 51),
     (4, 4, 64, 90, "bf16", 8, 32, 30, 52),           # shorter than... several completions, L < 3w
+    (128, 16, 64, 200, "bf16", 16, 64, 20, 53),      # 128 query heads, G=8
 ]
 
 
