@@ -259,6 +259,50 @@ def test_config5_ragged_mixed_batch_sampled(tb, bufs):
     assert worst_p <= H.TOL["bf16"] and worst_d <= H.TOL["bf16"]
 
 
+def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
+    """Config 3 exactly as bench.py times it: budgets from tca_calibrate_budgets on the separate
+    8192-token sample, then select + prefill at 131072 tokens.  The oracle calibrates the heads it
+    replays by itself, selects for them over the full sequence and attends on sampled rows."""
+    c = wl.CONFIGS[3]
+    Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
+    G = Hq // Hkv
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    xc = wl.prefill_inputs(c["kind"], Hq, Hkv, d, c["L_cal"], "bf16", wl.calib_seed(3))
+    wsc = bufs.workspace(tb.tca_calibrate_workspace_bytes(prm, c["L_cal"], c["M"]))
+    cal = tb.tca_calibrate_budgets(prm, bufs.to_device(xc["Q"]), bufs.to_device(xc["K"]), c["L_cal"], c["M"],
+                                   c["sigma"], c["tau"], wsc)
+    print("candidates", cal["cand_idx"].tolist(), flush=True)
+    heads = [0, 13, Hq - 1]
+    P_orc = {}
+    for h in heads:
+        ch = orc.calibrate_head(wl.to_f64(xc["Q"][h]), wl.to_f64(xc["K"][h // G]), b,
+                                orc.candidates(b, c["M"], c["sigma"]), c["tau"], c["alpha"])
+        assert ch.index == cal["cand_idx"][h], f"calibration of head {h}"
+        P_orc[h] = ch.p
+    del xc, wsc
+    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, cal["p_star"])
+    O = torch.empty_like(Qd)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+    pos = _sample_positions(L, w, b, 10, 7)
+    Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
+    worst = 0.0
+    for h in heads:
+        Kf, Vf = wl.to_f64(x["K"][h // G]), wl.to_f64(x["V"][h // G])
+        sel = orc.select(wl.to_f64(x["Q"][h, L - 1]), Kf, b, P_orc[h], c["alpha"])
+        got = H.head_indices(gb, h)
+        H.assert_selection(sel, got, b, P_orc[h], tag=f"cfg3 calibrated head {h}")
+        qh = wl.to_f64(x["Q"][h][pos])
+        for n, i in enumerate(pos):
+            ref = orc.attention_row(qh[n], int(i), Kf, Vf, got, w)
+            worst = max(worst, float(np.abs(ref - Og[h, n]).max()))
+    print("max abs err on", len(pos) * len(heads), "rows:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
+
+
 def test_diagnostics_clock_and_mfma_probe(tb, bufs):
     """The MFMA probe returns plausible figures, and a bf16 prefill leaves the cycle / tick
     sums of its attention kernel at the head of its workspace."""
