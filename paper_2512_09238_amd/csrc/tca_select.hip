@@ -5,15 +5,20 @@
 //                   block's K rows with 16-byte loads, forms the logits of all G
 //                   query heads of the group in fp64 (Eq. 5 numerator), reduces
 //                   them to the block statistics max / sum e^x / sum e^2x that
-//                   Eq. 6 needs, and ranks the b tokens inside the block (the
-//                   in-block rank does not depend on the budget, so Eq. 8 becomes
-//                   "rank < t_j" later).  Writes 1 byte per (head, token).
+//                   Eq. 6 needs, and emits one 64-bit ranking key per (head,
+//                   token).  The rank of a token inside its block does not depend
+//                   on the budget, so Eq. 8 becomes "rank < t_j" later.  For
+//                   calibration (ranks reused by every candidate) the kernel also
+//                   ranks and writes 1 byte per (head, token); for selection the
+//                   ranking is left to gather_kernel, which is bound by HBM and
+//                   has the vector ALU to spare.
 //   assign_kernel : one workgroup per query head.  Global softmax normaliser,
 //                   h_j (Eq. 6), rank of every block, t_j = Psi[rank] (Eq. 7),
 //                   exclusive scan of t_j -> destination row of every block.
-//   gather_kernel : one workgroup per (head, block).  Keeps tokens with
-//                   rank < t_j in position order and copies their K/V rows and
-//                   positions into the head's flat region (App. C).
+//   gather_kernel : one workgroup per (head, block).  Ranks the block's tokens by
+//                   counting over their keys (skipped when t_j = b), keeps those
+//                   with rank < t_j in position order and copies their K/V rows
+//                   and positions into the head's flat region (App. C).
 #include <hip/hip_runtime.h>
 
 #include "tca_common.h"
@@ -25,6 +30,7 @@ namespace tca {
 constexpr int kScoreThreads = 256;
 constexpr int kAssignThreads = 1024;
 constexpr int kGatherThreads = 256;
+constexpr int kGatherRows = 2;        // rows per thread in flight in the copy loop (4 measured the same)
 constexpr int kHeadsPerLaunch = 32;
 
 SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
@@ -33,6 +39,7 @@ SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
   SelectWs w;
   char* base = (char*)ws;
   w.tokrank = (uint8_t*)(base + off); off = align_up(off + (size_t)Hq * nb * b, 256);
+  w.keys = (uint64_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * b * sizeof(uint64_t), 256);
   w.stats = (double*)(base + off);    off = align_up(off + (size_t)Hq * nbt * 3 * sizeof(double), 256);
   w.blk_t = (int32_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
   w.blk_dst = (int32_t*)(base + off); off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
@@ -97,12 +104,25 @@ struct GroupReduce {
   __device__ static __forceinline__ int head_of(int sub) { return head_bits<LPR, GP>(sub, 0); }
 };
 
+// Number of keys of a block that beat key ki (higher logit, or the same logit at a lower
+// position): the rank of its token.  keys: b 64-bit keys in LDS, 16-byte aligned.
+__device__ __forceinline__ int count_greater(const uint64_t* keys, int o_begin, int o_end, uint64_t ki) {
+  int cnt = 0;
+  for (int o = o_begin; o < o_end; o += 2) {
+    const ulonglong2 ko = *reinterpret_cast<const ulonglong2*>(&keys[o]);
+    cnt += (ko.x > ki);
+    cnt += (ko.y > ki);
+  }
+  return cnt;
+}
+
 // grid (nbt, Hkv); block 256.  T storage type, D head dim, G query heads per KV head.
-template <typename T, int D, int G>
+// RANK: also rank inside the block and write tokrank (calibration); otherwise only keys_out is written.
+template <typename T, int D, int G, bool RANK>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     const T* __restrict__ K, const T* __restrict__ q_last, int64_t kv_stride, int64_t pos0,
     int64_t n_tokens, int b, int64_t n_blocks, int64_t nbt, int Hq, double scale,
-    uint8_t* __restrict__ tokrank, double* __restrict__ stats) {
+    uint8_t* __restrict__ tokrank, uint64_t* __restrict__ keys_out, double* __restrict__ stats) {
   constexpr int EPL = Vec16<T>::N;            // elements per lane per load
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int RPW = kWave / LPR;            // rows per wave per load
@@ -191,19 +211,16 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
   // that agree in all but those bits (relative distance below 2^-44) count as tied.
   for (int pi = tid; pi < G * b; pi += kScoreThreads) {
     const int g = pi / b, i = pi - g * b;
-    keys[g][i] = (ordered_key(xs[g][i]) & ~0xFFull) | (uint64_t)(255 - i);
+    const uint64_t key = (ordered_key(xs[g][i]) & ~0xFFull) | (uint64_t)(255 - i);
+    if constexpr (RANK) keys[g][i] = key;
+    else keys_out[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = key;
   }
-  __syncthreads();
-  for (int pi = tid; pi < G * b; pi += kScoreThreads) {
-    const int g = pi / b, i = pi - g * b;
-    const uint64_t ki = keys[g][i];
-    int cnt = 0;
-    for (int o = 0; o < b; o += 2) {
-      const ulonglong2 ko = *reinterpret_cast<const ulonglong2*>(&keys[g][o]);
-      cnt += (ko.x > ki);
-      cnt += (ko.y > ki);
+  if constexpr (RANK) {
+    __syncthreads();
+    for (int pi = tid; pi < G * b; pi += kScoreThreads) {
+      const int g = pi / b, i = pi - g * b;
+      tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)count_greater(keys[g], 0, b, keys[g][i]);
     }
-    tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)cnt;
   }
 }
 
@@ -248,20 +265,39 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
   const int hl = blockIdx.x, h = head0 + hl;
   const double* st = stats + (size_t)h * nbt * 3;
 
+  // the statistics of this thread's blocks (block j = tid + k * 1024, tail block included), read once
+  constexpr int KMAX = TCA_MAX_BLOCKS / kAssignThreads + 1;
+  double bM[KMAX], bE1[KMAX], bE2[KMAX];
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const int j = tid + k * kAssignThreads;
+    const bool in = j < nbt;
+    bM[k] = in ? st[j * 3] : -INFINITY;
+    bE1[k] = in ? st[j * 3 + 1] : 0.0;
+    bE2[k] = in ? st[j * 3 + 2] : 0.0;
+  }
   // global normaliser of Eq. 5 over every scored token, tail included
   double mx = -INFINITY;
-  for (int j = tid; j < nbt; j += kAssignThreads) mx = fmax(mx, st[j * 3]);
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) mx = fmax(mx, bM[k]);
   mx = block_reduce_max(mx, red);
   double z = 0.0;
-  for (int j = tid; j < nbt; j += kAssignThreads) z += st[j * 3 + 1] * exp(st[j * 3] - mx);
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    bM[k] = tid + k * kAssignThreads < nbt ? bE1[k] * exp(bM[k] - mx) : 0.0;   // block mass before normalisation
+    z += bM[k];
+  }
   z = block_reduce_sum(z, red);
 
   // Eq. 6
-  for (int j = tid; j < m; j += kAssignThreads) {
-    const double e1 = st[j * 3 + 1], e2 = st[j * 3 + 2];
-    const double mass = e1 * exp(st[j * 3] - mx) / z;
-    const double hhi = e2 / (e1 * e1);
-    hs[j] = (1.0 - alpha) * mass + alpha * (1.0 - hhi);
+#pragma unroll
+  for (int k = 0; k < KMAX; ++k) {
+    const int j = tid + k * kAssignThreads;
+    if (j < m) {
+      const double mass = bM[k] / z;
+      const double hhi = bE2[k] / (bE1[k] * bE1[k]);
+      hs[j] = (1.0 - alpha) * mass + alpha * (1.0 - hhi);
+    }
   }
   __syncthreads();
 
@@ -336,29 +372,51 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
 }
 
 // ----------------------------------------------------------------- gather --
+// offsets of the heads' regions travel in the kernel's argument block: no copy, no extra launch
+struct OffsArgs { int64_t offs[TCA_MAX_HEADS + 1]; };
+
 // grid (n_blocks, Hq); block 256.
 template <typename T, int D>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const T* __restrict__ K, const T* __restrict__ V, int64_t kv_stride, int64_t pos0, int b,
-    int64_t n_blocks, int G, const uint8_t* __restrict__ tokrank,
+    int64_t n_blocks, int G, const uint64_t* __restrict__ keys,
     const int32_t* __restrict__ blk_t, const int32_t* __restrict__ blk_dst,
-    const int64_t* __restrict__ offs_dev, int32_t* __restrict__ idx, T* __restrict__ Kg,
-    T* __restrict__ Vg) {
+    OffsArgs oa, int32_t* __restrict__ idx, T* __restrict__ Kg, T* __restrict__ Vg) {
   constexpr int EPL = Vec16<T>::N;
   constexpr int LPR = D / EPL;
   constexpr int RPI = kGatherThreads / LPR;
   __shared__ int32_t sel[256];
   __shared__ int32_t wave_cnt[kGatherThreads / kWave];
+  __shared__ __attribute__((aligned(16))) uint64_t bkeys[256];
+  __shared__ int32_t rank[256];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int64_t j = blockIdx.x;
   const int h = blockIdx.y, kvh = h / G;
   const int t = blk_t[(size_t)h * n_blocks + j];
-  const int64_t base = offs_dev[h], cap = offs_dev[h + 1] - base;
+  const int64_t base = oa.offs[h], cap = oa.offs[h + 1] - base;
   const int64_t dst0 = blk_dst[(size_t)h * n_blocks + j];
 
+  // Eq. 8: rank of every token inside the block, all 256 threads share the b*b comparisons;
+  // nothing to rank when the whole block is kept
+  bool keep = tid < b;
+  if (t < b) {
+    if (tid < b) {
+      bkeys[tid] = keys[(size_t)h * (n_blocks * b) + j * b + tid];
+      rank[tid] = 0;
+    }
+    __syncthreads();
+    // b is a power of two <= 256: thread (i = tid % b, part = tid / b) counts over one even-sized span
+    int parts = kGatherThreads / b;
+    if (parts > b / 2) parts = b / 2;
+    const int i = tid % b, part = tid / b, span = b / parts;
+    if (part < parts) {
+      const int cnt = count_greater(bkeys, part * span, (part + 1) * span, bkeys[i]);
+      if (cnt) atomicAdd(&rank[i], cnt);
+    }
+    __syncthreads();
+    keep = tid < b && rank[tid] < t;
+  }
   // compact the kept positions, in ascending position order
-  bool keep = false;
-  if (tid < b) keep = tokrank[(size_t)h * (n_blocks * b) + j * b + tid] < t;
   const unsigned long long mask = __ballot(keep);
   if (lane == 0) wave_cnt[wv] = __popcll(mask);
   __syncthreads();
@@ -367,35 +425,43 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   if (keep) sel[before] = tid;
   __syncthreads();
 
+  // copy the kept rows, kRows rows per thread in flight (2 * kRows 16-byte loads before the first store)
+  constexpr int kRows = kGatherRows;
   const int sub = tid % LPR;
-  for (int k = tid / LPR; k < t; k += RPI) {
-    const int64_t row = dst0 + k;
-    if (row >= cap) break;
-    const int64_t pos = pos0 + j * b + sel[k];
-    const size_t src = ((size_t)kvh * kv_stride + pos) * D + sub * EPL;
-    const size_t dst = (size_t)(base + row) * D + sub * EPL;
-    *reinterpret_cast<uint4*>(Kg + dst) = *reinterpret_cast<const uint4*>(K + src);
-    *reinterpret_cast<uint4*>(Vg + dst) = *reinterpret_cast<const uint4*>(V + src);
-    if (sub == 0) idx[base + row] = (int32_t)pos;
+  int n_keep = t;
+  if (dst0 + n_keep > cap) n_keep = cap > dst0 ? (int)(cap - dst0) : 0;
+  for (int k0 = tid / LPR; k0 < n_keep; k0 += kRows * RPI) {
+    uint4 kr[kRows], vr[kRows];
+    int64_t pos[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      const int k = k0 + u * RPI;
+      pos[u] = pos0 + j * b + sel[k < n_keep ? k : k0];
+      const size_t src = ((size_t)kvh * kv_stride + pos[u]) * D + sub * EPL;
+      kr[u] = *reinterpret_cast<const uint4*>(K + src);
+      vr[u] = *reinterpret_cast<const uint4*>(V + src);
+    }
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      const int k = k0 + u * RPI;
+      if (k < n_keep) {
+        const size_t dst = (size_t)(base + dst0 + k) * D + sub * EPL;
+        *reinterpret_cast<uint4*>(Kg + dst) = kr[u];
+        *reinterpret_cast<uint4*>(Vg + dst) = vr[u];
+        if (sub == 0) idx[base + dst0 + k] = (int32_t)pos[u];
+      }
+    }
   }
 }
 
-// offsets of the heads' regions, placed in the workspace by a tiny kernel so
-// that no host->device copy is needed
-struct OffsArgs { int64_t offs[TCA_MAX_HEADS + 1]; };
-__global__ void put_offsets_kernel(OffsArgs a, int n, int64_t* out) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) out[i] = a.offs[i];
-}
-
-template <typename T, int D>
+template <typename T, int D, bool RANK>
 static void launch_score(int G, dim3 grid, hipStream_t st, const T* K, const T* q, int64_t kv_stride,
                          int64_t pos0, int64_t n_tokens, int b, int64_t nb, int64_t nbt, int Hq,
-                         double scale, uint8_t* tokrank, double* stats) {
-#define TCA_SCORE_CASE(GG)                                                                      \
-  case GG:                                                                                      \
-    hipLaunchKernelGGL((score_kernel<T, D, GG>), grid, dim3(kScoreThreads), 0, st, K, q,        \
-                       kv_stride, pos0, n_tokens, b, nb, nbt, Hq, scale, tokrank, stats);       \
+                         double scale, uint8_t* tokrank, uint64_t* keys, double* stats) {
+#define TCA_SCORE_CASE(GG)                                                                           \
+  case GG:                                                                                           \
+    hipLaunchKernelGGL((score_kernel<T, D, GG, RANK>), grid, dim3(kScoreThreads), 0, st, K, q,       \
+                       kv_stride, pos0, n_tokens, b, nb, nbt, Hq, scale, tokrank, keys, stats);      \
     break;
   switch (G) {
     TCA_SCORE_CASE(1) TCA_SCORE_CASE(2) TCA_SCORE_CASE(3) TCA_SCORE_CASE(4)
@@ -414,12 +480,12 @@ void select_score_stage(const tca_params* prm, const void* q_last, const void* K
   const double sc = logit_scale(prm);
   if (prm->dtype == TCA_BF16) {
     using T = bf16_t;
-    if (prm->head_dim == 128) launch_score<T, 128>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
-    else launch_score<T, 64>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+    if (prm->head_dim == 128) launch_score<T, 128, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
+    else launch_score<T, 64, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
   } else {
     using T = float;
-    if (prm->head_dim == 128) launch_score<T, 128>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
-    else launch_score<T, 64>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.stats);
+    if (prm->head_dim == 128) launch_score<T, 128, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
+    else launch_score<T, 64, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
   }
 }
 
@@ -453,21 +519,18 @@ static int run_select(const tca_params* prm, const T* q_last, const T* K, const 
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
   const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
   SelectWs w = carve_select_ws(ws, Hq, b, n_tokens);
-  int64_t* offs_dev = (int64_t*)((char*)ws + w.bytes);
-
   OffsArgs oa;
   for (int h = 0; h <= Hq; ++h) oa.offs[h] = offs[h];
-  hipLaunchKernelGGL(put_offsets_kernel, dim3(1), dim3(TCA_MAX_HEADS + 1), 0, st, oa, Hq + 1, offs_dev);
 
-  launch_score<T, D>(G, dim3((unsigned)nbt, Hkv), st, K, q_last, kv_stride, pos0, n_tokens, b, nb, nbt,
-                     Hq, logit_scale(prm), w.tokrank, w.stats);
+  launch_score<T, D, false>(G, dim3((unsigned)nbt, Hkv), st, K, q_last, kv_stride, pos0, n_tokens, b, nb, nbt,
+                            Hq, logit_scale(prm), w.tokrank, w.keys, w.stats);
   if (nb == 0) return TCA_OK;
 
   int64_t cap[TCA_MAX_HEADS];
   for (int h = 0; h < Hq; ++h) cap[h] = offs[h + 1] - offs[h];
   select_assign_stage(prm, n_tokens, p, cap, w.stats, n_rows, w.blk_t, w.blk_dst, st);
   hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hq), dim3(kGatherThreads), 0, st, K, V,
-                     kv_stride, pos0, b, nb, G, w.tokrank, w.blk_t, w.blk_dst, offs_dev, idx, Kg, Vg);
+                     kv_stride, pos0, b, nb, G, w.keys, w.blk_t, w.blk_dst, oa, idx, Kg, Vg);
   return TCA_OK;
 }
 
@@ -478,7 +541,7 @@ using namespace tca;
 extern "C" size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens) {
   if (check_params(prm) != TCA_OK || n_tokens < 0) return 0;
   SelectWs w = carve_select_ws(nullptr, prm->n_q_heads, prm->block, n_tokens);
-  return w.bytes + align_up((TCA_MAX_HEADS + 1) * sizeof(int64_t), 256);
+  return w.bytes;
 }
 
 extern "C" int tca_select(const tca_params* prm, const void* q_last, const void* K, const void* V,
