@@ -201,7 +201,9 @@ int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq
  *   q      : device [B, Hq, d];  k_new, v_new: device [B, Hkv, d];  O: device [B, Hq, d]
  *   offs   : host [Hq+1] (capacity prefix sums, offs[Hq] == cache->cap_rows)
  *   p      : host [Hq][nk]
- * Does not synchronise; lengths live on the device, so steps can be queued back to back. */
+ * Does not synchronise; lengths live on the device, so steps can be queued back to back.
+ * The call only launches kernels on `stream` (no memset, no allocation, no read-back), so a
+ * step may be captured into a HIP graph and replayed. */
 int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs,
                const void* q, const void* k_new, const void* v_new, const double* p,
                void* O, void* ws, size_t ws_bytes, void* stream);

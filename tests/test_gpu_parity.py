@@ -266,6 +266,46 @@ def test_decode_from_empty_cache_batched(tb, bufs):
             assert np.array_equal(cache.idx[sq, o:o + n].cpu().numpy(), oc.S[h])
 
 
+def test_decode_step_replayed_from_a_hip_graph(tb, bufs):
+    """tca_decode only launches kernels on the given stream (no memset, no allocation, no host
+    read-back), so one step can be captured into a HIP graph and replayed: all state that
+    changes between steps (ring, global rows, n_rows, length) lives on the device.  Every replay
+    is checked against the eager run, with eager copies and synchronisations between replays."""
+    Hq, Hkv, d, b, w, steps, B = 4, 2, 64, 8, 16, 40, 3
+    P_gpu, _ = budgets_to_configs(tb, b, [0.2, 0.4, 0.6, 0.9])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    cap = np.array([tb.tca_decode_budget(b, p) for p in P_gpu]) * (steps // b + 1)
+    dec = wl.decode_inputs(Hq, Hkv, d, steps, "bf16", 62, batch=B)
+    qd, kd, vd = (bufs.to_device(dec[k]) for k in ("q", "k_new", "v_new"))
+
+    cache = bufs.DecodeCache(prm, B, cap)
+    wsd = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache.max_head_rows))
+    O_eager = torch.empty(steps, B, Hq, d, dtype=qd.dtype, device="cuda")
+    for s in range(steps):
+        tb.tca_decode(prm, cache.view, cache.offs, qd[s], kd[s], vd[s], P_gpu, O_eager[s], wsd)
+    torch.cuda.synchronize()
+    idx_eager, n_eager = cache.idx.clone(), cache.n_rows.clone()
+
+    cache2 = bufs.DecodeCache(prm, B, cap)
+    wsd2 = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache2.max_head_rows))
+    q_s, k_s, v_s = torch.empty_like(qd[0]), torch.empty_like(kd[0]), torch.empty_like(vd[0])
+    O_s = torch.empty_like(O_eager[0])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        tb.tca_decode(prm, cache2.view, cache2.offs, q_s, k_s, v_s, P_gpu, O_s, wsd2)
+    assert int(cache2.length.sum().item()) == 0          # capture launched nothing
+    for s in range(steps):
+        q_s.copy_(qd[s]); k_s.copy_(kd[s]); v_s.copy_(vd[s])
+        graph.replay()
+        got = O_s.clone()
+        if s % 7 == 0:
+            torch.cuda.synchronize()
+        assert torch.equal(got, O_eager[s]), f"replay {s} differs from the eager step"
+    torch.cuda.synchronize()
+    assert cache2.length.cpu().tolist() == [steps] * B
+    assert torch.equal(cache2.n_rows, n_eager) and torch.equal(cache2.idx, idx_eager)
+
+
 CALIB_CASES = [
     # kind, Hq, Hkv, d, L, dtype, b, M, seed
     ("lowrank", 4, 2, 64, 512, "f32", 16, 6, 71),
