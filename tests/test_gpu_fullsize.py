@@ -303,6 +303,41 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     assert worst <= H.TOL["bf16"]
 
 
+def test_longest_single_call_4096_blocks_512k_tokens(tb, bufs):
+    """The most one tca_select call ranks (4096 blocks of 128 = 524288 tokens), with prefill over
+    the same range: 32-bit tile offsets close to their 2 GiB guard, 2048 query tiles per head."""
+    Hq, Hkv, d, b, w = 4, 1, 128, 128, 4096
+    L = 4096 * b
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    x = wl.device_lowrank_inputs(Hq, Hkv, d, L, 4242)
+    fr = [0.08, 0.2, 0.35, 0.5]
+    P_gpu = np.stack([tb.tca_config_from_budget(b, 1.0, f) for f in fr])
+    P_orc = np.stack([orc.config_from_budget(b, 1.0, f) for f in fr])
+    total, rows = tb.tca_select_rows(prm, L // b, P_gpu)
+    gb = bufs.GlobalBuffers(prm, rows)
+    ws = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    tb.tca_select(prm, x["Q"][:, L - 1].contiguous(), x["K"], x["V"], L, 0, L, P_gpu, gb.offs, gb.n_rows,
+                  gb.idx, gb.Kg, gb.Vg, ws)
+    del ws
+    O = torch.empty_like(x["Q"])
+    wsp = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, x["Q"], 0, L, x["K"], x["V"], L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, wsp)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+    Kf, Vf = x["K"][0].double().cpu().numpy(), x["V"][0].double().cpu().numpy()
+    pos = _sample_positions(L, w, b, 6, 5)
+    worst = 0.0
+    for h in (0, Hq - 1):
+        sel = orc.select(x["Q"][h, L - 1].double().cpu().numpy(), Kf, b, P_orc[h], 0.5)
+        got = H.head_indices(gb, h)
+        H.assert_selection(sel, got, b, P_orc[h], tag=f"512K head {h}")
+        for i in pos:
+            ref = orc.attention_row(x["Q"][h, int(i)].double().cpu().numpy(), int(i), Kf, Vf, got, w)
+            worst = max(worst, float(np.abs(ref - O[h, int(i)].double().cpu().numpy()).max()))
+    print("max abs err on", 2 * len(pos), "rows:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
+
+
 def test_diagnostics_clock_and_mfma_probe(tb, bufs):
     """The MFMA probe returns plausible figures, and a bf16 prefill leaves the cycle / tick
     sums of its attention kernel at the head of its workspace."""
