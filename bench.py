@@ -229,6 +229,47 @@ def bench_decode(args, tb, bufs, wl, torch):
     return res
 
 
+def bench_mixed(args, tb, bufs, wl, torch):
+    """Config 5 (not part of the default run): 8 sequences of ragged length prefilled in
+    8192-token chunks, round-robin, with one decode step for the finished sequences after
+    every chunk.  Wall time of the whole schedule, host scheduling included."""
+    import paper_2512_09238_amd.schedule as sched
+    c = wl.CONFIGS[5]
+    Hq, Hkv, d, b, w, chunk = c["Hq"], c["Hkv"], c["d"], c["b"], c["w"], c["chunk"]
+    lengths = wl.config5_lengths()
+    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, c["alpha"], 0.0)
+    xc = wl.device_lowrank_inputs(Hq, Hkv, d, c["L_cal"], wl.calib_seed(5))
+    wsc = bufs.workspace(tb.tca_calibrate_workspace_bytes(prm, c["L_cal"], c["M"]))
+    cal = tb.tca_calibrate_budgets(prm, xc["Q"], xc["K"], c["L_cal"], c["M"], c["sigma"], c["tau"], wsc)
+    del xc, wsc
+    seqs = []
+    for i, L in enumerate(lengths):
+        x = wl.device_lowrank_inputs(Hq, Hkv, d, L, wl.data_seed(5) + 10 * i)
+        seqs.append(dict(Q=x["Q"], K=x["K"], V=x["V"], O=torch.empty_like(x["Q"])))
+    g = torch.Generator(device="cuda").manual_seed(77)
+    best = None
+    for rep in range(2):                       # the second pass has warm allocations
+        mb = sched.MixedBatch(prm, lengths, chunk, cal["p_star"])
+        n_calls = len(mb.events)
+        dq = torch.randn(n_calls, len(lengths), Hq, d, generator=g, device="cuda").to(torch.bfloat16)
+        dk = torch.randn(n_calls, len(lengths), Hkv, d, generator=g, device="cuda").to(torch.bfloat16)
+        dv = torch.randn(n_calls, len(lengths), Hkv, d, generator=g, device="cuda").to(torch.bfloat16)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        mb.run(seqs, lambda step, slots: (dq[step, :len(slots)].contiguous(), dk[step, :len(slots)].contiguous(),
+                                          dv[step, :len(slots)].contiguous()))
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+        n_dec_steps, n_done = mb.decode_calls, mb.n_done
+        del mb, dq, dk, dv
+    total = int(sum(lengths))
+    log(f"[bench] mixed batch: {total} prefill tokens in {len(lengths)} sequences, {n_dec_steps} decode steps: {1e3 * best:.1f} ms")
+    return {"lengths": lengths, "chunk": chunk, "prefill_tokens": total, "decode_steps": n_dec_steps,
+            "wall_ms": 1e3 * best, "prefill_tokens_per_s": total / best,
+            "what": "config 5: Hq=64 Hkv=8 d=128 bf16, chunked prefill interleaved with decode, host scheduling included"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -243,6 +284,7 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--calibrate", action="store_true", default=True)
     ap.add_argument("--no-calibrate", dest="calibrate", action="store_false")
+    ap.add_argument("--mixed", action="store_true", help="also time the config-5 ragged mixed batch (adds about a minute)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build covers one GPU only (no sharding, no collectives); run with --gpus 1")
@@ -276,6 +318,7 @@ def main():
     del host
     torch.cuda.empty_cache()
     dec = None if args.no_decode else bench_decode(args, tb, bufs, wl, torch)
+    mixed = bench_mixed(args, tb, bufs, wl, torch) if args.mixed else None
 
     cfg = res["cfg"]
     out = {
@@ -309,6 +352,8 @@ def main():
         "cpu_baseline": cpu,
         "decode": dec,
     }
+    if mixed is not None:
+        out["mixed_batch"] = mixed
     print(json.dumps(out), flush=True)
 
 
