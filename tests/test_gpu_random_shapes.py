@@ -1,0 +1,95 @@
+"""Seeded sweep over small random shapes: selection sets, prefill outputs and a few decode
+steps of the GPU path against the oracle, every row.  Shapes cover both head dims, every
+group size 1..8, blocks 2..256, windows of 1..8 blocks, ragged lengths, both storage types."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import tca_oracle as orc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    import paper_2512_09238_amd.binding as tb
+    import paper_2512_09238_amd.buffers as bufs
+    return tb, bufs
+
+
+def _draw(rng):
+    G = int(rng.integers(1, 9))
+    Hkv = int(rng.integers(1, 4))
+    d = int(rng.choice([64, 128]))
+    b = int(2 ** rng.integers(1, 9))
+    w = b * int(rng.integers(1, 9))
+    L = int(rng.integers(max(b, 8), 6 * w + 3 * b + 50))
+    dtype = str(rng.choice(["bf16", "f32"]))
+    kind = str(rng.choice(["lowrank", "centroid"]))
+    return kind, G * Hkv, Hkv, d, min(L, 1400), dtype, b, w
+
+
+CASES = [(_draw(np.random.default_rng(900 + i)), 900 + i) for i in range(48)]
+
+
+@pytest.mark.parametrize("case,seed", CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_random_shape_select_prefill_decode(mods, case, seed):
+    tb, bufs = mods
+    kind, Hq, Hkv, d, L, dtype, b, w = case
+    print("case", case, "seed", seed, flush=True)
+    rng = np.random.default_rng(seed)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = rng.uniform(0.03, 0.97, size=Hq)
+    P_gpu = np.stack([tb.tca_config_from_budget(b, 1.0, f) for f in fr])
+    P_orc = np.stack([orc.config_from_budget(b, 1.0, f) for f in fr])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    steps = int(min(2 * b + 3, 40))
+    _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
+    extra = np.array([tb.tca_decode_budget(b, p) for p in P_gpu]) * ((L + steps) // b - L // b + 1)
+    cache = bufs.DecodeCache(prm, 1, rows + extra)
+    Kd, Vd, Qd = bufs.to_device(x["K"]), bufs.to_device(x["V"]), bufs.to_device(x["Q"])
+    ws = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P_gpu, cache.offs, cache.n_rows[0],
+                  cache.idx[0], cache.Kg[0], cache.Vg[0], ws)
+    O = torch.full_like(Qd, float("nan"))
+    wsp = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(cache.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, cache.idx[0], cache.Kg[0], cache.Vg[0], cache.offs, cache.n_rows[0],
+                   O, None, wsp)
+    tb.tca_cache_load_window(prm, cache.view, 0, Kd, Vd, L, L)
+    torch.cuda.synchronize()
+
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    exact = True
+    for h in range(Hq):
+        o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
+        got = cache.idx[0, o:o + n].cpu().numpy().astype(np.int64)
+        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+            exact = False
+            Oref[h] = orc.tca_attention(Qf[h], Kf[h // (Hq // Hkv)], Vf[h // (Hq // Hkv)], got, w)
+    Og = bufs.to_host_f64(O)
+    assert not np.isnan(Og).any()
+    err = np.abs(Og - Oref).max()
+    assert err <= H.TOL[dtype], f"prefill max abs err {err}"
+    if not exact:
+        return                                   # a sub-margin tie: the decode replay below needs identical sets
+    ocache = orc.cache_after_prefill(Kf, Vf, sels)
+    dec = wl.decode_inputs(Hq, Hkv, d, steps, dtype, seed + 2, batch=1, gains=x["gains"])
+    qd, kd, vd = (bufs.to_device(dec[k]) for k in ("q", "k_new", "v_new"))
+    wsd = bufs.workspace(tb.tca_decode_workspace_bytes(prm, 1, cache.max_head_rows))
+    Od = torch.full((steps, 1, Hq, d), float("nan"), dtype=qd.dtype, device="cuda")
+    for s in range(steps):
+        tb.tca_decode(prm, cache.view, cache.offs, qd[s], kd[s], vd[s], P_gpu, Od[s], wsd)
+    torch.cuda.synchronize()
+    Odg = bufs.to_host_f64(Od)
+    worst = 0.0
+    for s in range(steps):
+        ref = orc.decode_step(ocache, wl.to_f64(dec["q"][s, 0]), wl.to_f64(dec["k_new"][s, 0]),
+                              wl.to_f64(dec["v_new"][s, 0]), b, w, P_orc)
+        worst = max(worst, np.abs(Odg[s, 0] - ref).max())
+    assert worst <= H.TOL[dtype], f"decode max abs err {worst}"
+    for h in range(Hq):
+        o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
+        assert np.array_equal(cache.idx[0, o:o + n].cpu().numpy(), ocache.S[h]), f"head {h} after decode"
