@@ -28,6 +28,20 @@ CASES = [
 ]
 
 
+def _draw_chunked(rng):
+    G, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 3))
+    d = int(rng.choice([64, 128]))
+    b = int(2 ** rng.integers(2, 8))
+    w = b * int(rng.integers(1, 5))
+    chunk = b * int(rng.integers(1, 9))                 # chunks are whole blocks; the last one may be ragged
+    L = int(rng.integers(chunk + 1, min(5 * chunk + 40, 1300) + chunk))
+    return (str(rng.choice(["lowrank", "centroid"])), G * Hkv, Hkv, d, L, str(rng.choice(["bf16", "f32"])), b, w,
+            chunk, int(rng.integers(1000, 9999)))
+
+
+CASES = CASES + [_draw_chunked(np.random.default_rng(700 + i)) for i in range(16)]
+
+
 @pytest.mark.parametrize("case", CASES, ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}-w{c[7]}-chunk{c[8]}")
 def test_chunked_prefill_matches_oracle(mods, case):
     tb, bufs, sched = mods
