@@ -6,9 +6,11 @@
 //   rowstats  : per query row j, max and sum of exp of the causal logits        (softmax denominators)
 //   colmeans  : per key column k, sum_{j>=k} exp(x_jk - max_j) / sum_j, divided
 //               by the structural column count L-k                              (Eq. 4 inner term)
-// Both kernels give one wavefront to a row (column); the wave is split into four
-// 16-lane groups that each take every fourth key (query); a lane holds a D/16
-// slice of the vectors.
+// Both kernels give one wavefront to a row (column).  Its four 16-lane groups take 16 keys
+// (queries) each per iteration; a lane holds a D/16 slice of the vectors and forms its slice of
+// all 16 dot products, and a transposed butterfly (each exchange halves the products a lane still
+// carries) leaves every lane with the total of a different key: 64 logits, and 64 useful
+// exponentials, per wave and iteration.
 // The selection of every candidate reuses the online-selection stages (scores
 // and in-block ranks once, budgets per candidate); cand_score sums the column
 // means of the tokens a candidate keeps (Eq. 4).
@@ -32,9 +34,9 @@ __device__ __forceinline__ void load_slice_f64(const T* p, double (&out)[EL]) {
   for (int e = 0; e < EL; ++e) out[e] = (double)tmp[e];
 }
 
-// merge (m, l) pairs of the four 16-lane groups of a wave
-__device__ __forceinline__ void merge_groups(double& m, double& l) {
-  for (int o = 16; o < 64; o <<= 1) {
+// merge the (m, l) pairs of all 64 lanes of a wave
+__device__ __forceinline__ void merge_lanes(double& m, double& l) {
+  for (int o = 1; o < 64; o <<= 1) {
     const double mo = __shfl_xor(m, o, kWave), lo = __shfl_xor(l, o, kWave);
     const double mn = fmax(m, mo);
     const double a = (m == -INFINITY) ? 0.0 : exp(m - mn);
@@ -42,6 +44,29 @@ __device__ __forceinline__ void merge_groups(double& m, double& l) {
     l = l * a + lo * b;
     m = mn;
   }
+}
+
+// Dot products of this lane's slice `fixed` with the same slice of 16 consecutive rows starting
+// at rows + r0 (rows at or beyond r_end count as zero), summed over the 16 lanes of the group.
+// Returns the total of row r0 + (the row index this lane ends up with), and that index.
+template <typename T, int D>
+__device__ __forceinline__ double dots16(const T* __restrict__ rows, int64_t r0, int64_t r_end, int sub,
+                                         const double (&fixed)[D / 16], int& which) {
+  constexpr int EL = D / 16;
+  using GR = GroupReduce<16, 16>;
+  double acc[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    acc[r] = 0.0;
+    if (r0 + r < r_end) {
+      double v[EL];
+      load_slice_f64<T, EL>(rows + (size_t)(r0 + r) * D + sub * EL, v);
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc[r] = fma(fixed[e], v[e], acc[r]);
+    }
+  }
+  which = GR::head_of(sub);
+  return GR::run(acc, sub);
 }
 
 // grid (ceil(L/4), Hq); block 256: one wave per query row
@@ -58,24 +83,16 @@ __global__ __launch_bounds__(kCalThreads) void cal_rowstats_kernel(
   load_slice_f64<T, EL>(Q + ((size_t)h * L + j) * D + sub * EL, q);
   const T* Kh = K + (size_t)kvh * L * D;
   double m = -INFINITY, l = 0.0;
-  for (int64_t k0 = 0; k0 <= j; k0 += 4) {
-    const int64_t k = k0 + grp;
-    const bool ok = k <= j;
-    double s = 0.0;
-    if (ok) {
-      double kv[EL];
-      load_slice_f64<T, EL>(Kh + (size_t)k * D + sub * EL, kv);
-#pragma unroll
-      for (int e = 0; e < EL; ++e) s = fma(q[e], kv[e], s);
-    }
-    s = group_sum(s, 16) * scale;
-    if (ok) {
+  for (int64_t k0 = 0; k0 <= j; k0 += 64) {
+    int r;
+    const double s = dots16<T, D>(Kh, k0 + grp * 16, j + 1, sub, q, r) * scale;
+    if (k0 + grp * 16 + r <= j) {
       const double mn = fmax(m, s);
       l = l * exp(m - mn) + exp(s - mn);
       m = mn;
     }
   }
-  merge_groups(m, l);
+  merge_lanes(m, l);
   if (lane == 0) {
     row_max[(size_t)h * L + j] = m;
     row_sum[(size_t)h * L + j] = l;
@@ -96,21 +113,13 @@ __global__ __launch_bounds__(kCalThreads) void cal_colmeans_kernel(
   load_slice_f64<T, EL>(K + ((size_t)kvh * L + k) * D + sub * EL, kv);
   const T* Qh = Q + (size_t)h * L * D;
   double acc = 0.0;
-  for (int64_t j0 = k; j0 < L; j0 += 4) {
-    const int64_t j = j0 + grp;
-    const bool ok = j < L;
-    double s = 0.0;
-    if (ok) {
-      double q[EL];
-      load_slice_f64<T, EL>(Qh + (size_t)j * D + sub * EL, q);
-#pragma unroll
-      for (int e = 0; e < EL; ++e) s = fma(q[e], kv[e], s);
-    }
-    s = group_sum(s, 16) * scale;
-    if (ok) acc += exp(s - row_max[(size_t)h * L + j]) / row_sum[(size_t)h * L + j];
+  for (int64_t j0 = k; j0 < L; j0 += 64) {
+    int r;
+    const double s = dots16<T, D>(Qh, j0 + grp * 16, L, sub, kv, r) * scale;
+    const int64_t j = j0 + grp * 16 + r;
+    if (j < L) acc += exp(s - row_max[(size_t)h * L + j]) / row_sum[(size_t)h * L + j];
   }
-  acc += __shfl_xor(acc, 16, kWave);
-  acc += __shfl_xor(acc, 32, kWave);
+  acc = group_sum(acc, kWave);
   if (lane == 0) abar[(size_t)h * L + k] = acc / (double)(L - k);
 }
 

@@ -54,56 +54,6 @@ __device__ __forceinline__ uint64_t ordered_key(double x) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
 }
 
-// Sum of G per-lane partials over the LPR lanes that share a row (LPR = 8, 16 or 32
-// consecutive lanes).  Exchange steps pair lane i with its mirror image inside
-// groups of 32 (LDS shuffle), 16, 8 (DPP mirrors), then xor 2 and xor 1 (DPP quad
-// permutes).  While a lane still carries more than one head, a step halves the
-// heads it carries: the lower lane of a pair keeps the lower half.  The total of
-// head g ends up in every lane whose position bits spell g.
-template <int G, int LPR>
-struct GroupReduce {
-  static constexpr int GP = G <= 1 ? 1 : (G <= 2 ? 2 : (G <= 4 ? 4 : 8));   // heads padded to a power of two
-  template <int W> __device__ static __forceinline__ double exchange(double v) {
-    if constexpr (W == 32) return __shfl_xor(v, 31, kWave) ;   // i <-> 31-i inside 32 lanes
-    else if constexpr (W == 16) return dpp_f64<kDppMirror>(v);
-    else if constexpr (W == 8) return dpp_f64<kDppHalfMirror>(v);
-    else if constexpr (W == 4) return dpp_f64<kDppXor2>(v);
-    else return dpp_f64<kDppXor1>(v);
-  }
-  // is this lane the upper one of its pair at width W?
-  template <int W> __device__ static __forceinline__ bool upper(int sub) {
-    if constexpr (W >= 8) return (sub & (W - 1)) >= W / 2;
-    else return (sub & (W / 2)) != 0;
-  }
-  template <int W, int N> __device__ static __forceinline__ void step(double (&acc)[GP], int sub) {
-    if constexpr (W >= 2) {
-      if constexpr (N > 1) {
-        const bool hi = upper<W>(sub);
-#pragma unroll
-        for (int i = 0; i < N / 2; ++i) {
-          const double send = hi ? acc[i] : acc[i + N / 2];
-          const double keep = hi ? acc[i + N / 2] : acc[i];
-          acc[i] = keep + exchange<W>(send);
-        }
-        step<W / 2, N / 2>(acc, sub);
-      } else {
-        acc[0] += exchange<W>(acc[0]);
-        step<W / 2, 1>(acc, sub);
-      }
-    }
-  }
-  __device__ static __forceinline__ double run(double (&acc)[GP], int sub) {
-    step<LPR, GP>(acc, sub);
-    return acc[0];
-  }
-  template <int W, int N> __device__ static __forceinline__ int head_bits(int sub, int g) {
-    if constexpr (W >= 2 && N > 1) return head_bits<W / 2, N / 2>(sub, (g << 1) | (upper<W>(sub) ? 1 : 0));
-    else return g;
-  }
-  // head whose total this lane holds after run()
-  __device__ static __forceinline__ int head_of(int sub) { return head_bits<LPR, GP>(sub, 0); }
-};
-
 // Number of keys of a block that beat key ki (higher logit, or the same logit at a lower
 // position): the rank of its token.  keys: b 64-bit keys in LDS, 16-byte aligned.
 __device__ __forceinline__ int count_greater(const uint64_t* keys, int o_begin, int o_end, uint64_t ki) {
