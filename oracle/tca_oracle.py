@@ -177,13 +177,21 @@ def token_scores(q_last: np.ndarray, K: np.ndarray, scale: float | None = None) 
 # --------------------------------------------------------------------------
 # Eq. 6 : block redundancy metric
 # --------------------------------------------------------------------------
-def block_metric(x: np.ndarray, b: int, alpha: float) -> np.ndarray:
+def block_metric(x: np.ndarray, b: int, alpha: float, metric: str = "hhi") -> np.ndarray:
     """h_j = (1-alpha) sum_{B_j} s + alpha (1 - sum s^2 / (sum s)^2)  (Eq. 6).
 
     x: logits of all L keys.  The first term uses s normalised over all L keys.
     The ratio in the second term is invariant to the normaliser, so it is
     evaluated from exp(x - max of the block).
+
+    metric="entropy": the concentration index of the appendix ablation ("Ablations on
+    Concentration Index"), which the paper names but does not write out.  Reading:
+    the second term becomes the entropy of the scores renormalised inside the block,
+    divided by ln b so that it spans [0, 1] like 1 - HHI does:
+        h_j = (1-alpha) sum_{B_j} s + alpha * ( -sum_i t_i ln t_i ) / ln b,  t_i = s_i / sum_{B_j} s.
     """
+    if metric not in ("hhi", "entropy"):
+        raise ValueError(metric)
     x = np.asarray(x, F64)
     L = x.shape[0]
     m = L // b
@@ -193,8 +201,13 @@ def block_metric(x: np.ndarray, b: int, alpha: float) -> np.ndarray:
         blk = slice(j * b, (j + 1) * b)
         mass = s[blk].sum()
         e = np.exp(x[blk] - x[blk].max())
-        hhi = (e * e).sum() / (e.sum() ** 2)
-        h[j] = (1.0 - alpha) * mass + alpha * (1.0 - hhi)
+        if metric == "hhi":
+            spread = 1.0 - (e * e).sum() / (e.sum() ** 2)
+        else:
+            t = e / e.sum()
+            nz = t > 0.0                          # 0 ln 0 = 0
+            spread = -(t[nz] * np.log(t[nz])).sum() / np.log(b)
+        h[j] = (1.0 - alpha) * mass + alpha * spread
     return h
 
 
@@ -235,13 +248,13 @@ class Selection:
     t: np.ndarray                 # Eq. 7 per block
 
 
-def select(q_last, K, b: int, p, alpha: float, scale: float | None = None) -> Selection:
+def select(q_last, K, b: int, p, alpha: float, scale: float | None = None, metric: str = "hhi") -> Selection:
     """Alg. 2 lines 1-6 for one head: scores, blocks, metric, ranking, budgets, top-t."""
     K = np.asarray(K, F64)
     L = K.shape[0]
     m = L // b
     x = last_query_logits(q_last, K, scale)
-    h = block_metric(x, b, alpha)
+    h = block_metric(x, b, alpha, metric)
     t = block_budgets(b, h, p)
     parts = [j * b + top_t(x[j * b:(j + 1) * b], int(t[j])) for j in range(m)]
     S = np.concatenate(parts).astype(np.int64) if parts else np.zeros(0, np.int64)
@@ -252,10 +265,10 @@ def kv_head_of(h: int, n_q_heads: int, n_kv_heads: int) -> int:
     return h // (n_q_heads // n_kv_heads)
 
 
-def select_all_heads(q_last, K, b, p, alpha, scale=None) -> list[Selection]:
+def select_all_heads(q_last, K, b, p, alpha, scale=None, metric: str = "hhi") -> list[Selection]:
     """q_last [Hq,d], K [Hkv,L,d], p [Hq,nk]: one independent selection per query head."""
     Hq, Hkv = q_last.shape[0], K.shape[0]
-    return [select(q_last[h], K[kv_head_of(h, Hq, Hkv)], b, p[h], alpha, scale) for h in range(Hq)]
+    return [select(q_last[h], K[kv_head_of(h, Hq, Hkv)], b, p[h], alpha, scale, metric) for h in range(Hq)]
 
 
 # --------------------------------------------------------------------------

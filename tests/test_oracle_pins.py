@@ -93,6 +93,33 @@ def test_eq6_hand_worked():
     np.testing.assert_allclose(orc.block_metric(x, 2, 0.25), gold, atol=1e-15)
 
 
+def test_eq6_entropy_variant_hand_worked_and_closed_forms():
+    gold = read_rows("eq6_entropy_b2_L4.txt")[0]
+    x = np.array([0.0, math.log(3.0), 0.0, 0.0])
+    np.testing.assert_allclose(orc.block_metric(x, 2, 0.5, "entropy"), gold, atol=1e-15)
+    b, alpha = 8, 0.3
+    # uniform logits: the renormalised block distribution is uniform, entropy / ln b = 1
+    x = np.full(3 * b + 5, -0.4)
+    np.testing.assert_allclose(orc.block_metric(x, b, alpha, "entropy"),
+                               (1 - alpha) * b / len(x) + alpha * 1.0, atol=1e-15)
+    # two equal tokens carry a block, the rest are negligible: entropy = ln 2
+    x = np.full(2 * b, -800.0)
+    x[b + 1] = x[b + 5] = 0.0
+    h = orc.block_metric(x, b, alpha, "entropy")
+    np.testing.assert_allclose(h[1], (1 - alpha) * 1.0 + alpha * math.log(2) / math.log(b), atol=1e-15)
+    # alpha = 0 removes the concentration term: both metrics give the block mass
+    x = np.random.default_rng(3).normal(size=4 * b)
+    np.testing.assert_allclose(orc.block_metric(x, b, 0.0, "entropy"), orc.block_metric(x, b, 0.0), atol=0)
+    # entropy in nats against scipy, block by block
+    from scipy.stats import entropy as sp_entropy
+    s = orc.softmax(x)
+    ref = np.array([0.5 * s[j * b:(j + 1) * b].sum() + 0.5 * sp_entropy(s[j * b:(j + 1) * b]) / math.log(b)
+                    for j in range(4)])
+    np.testing.assert_allclose(orc.block_metric(x, b, 0.5, "entropy"), ref, atol=1e-14)
+    with pytest.raises(ValueError):
+        orc.block_metric(x, b, 0.5, "gini")
+
+
 def test_eq6_closed_forms_and_invariances():
     b, alpha = 8, 0.5
     # uniform logits: every block has mass b/L and concentration 1/b
