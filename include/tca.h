@@ -58,6 +58,9 @@ extern "C" {
 #define TCA_ERR_WORKSPACE   -3   /* ws_bytes too small or ws misaligned                       */
 #define TCA_ERR_HIP         -4   /* a HIP runtime call failed (see tca_last_error)            */
 
+#define TCA_METRIC_HHI      0
+#define TCA_METRIC_ENTROPY  1
+
 #define TCA_MAX_HEADS   128
 #define TCA_MAX_GROUP   8
 #define TCA_MAX_COUNTS  9        /* log2(256) + 1 */
@@ -72,6 +75,9 @@ typedef struct tca_params {
   int32_t dtype;       /* TCA_BF16 or TCA_F32: type of Q, K, V, O, Kg, Vg     */
   double  alpha;       /* balance of Eq. 6 (paper: 0.5)                       */
   double  scale;       /* logit scale; 0 selects 1/sqrt(head_dim) of Eq. 1    */
+  int32_t metric;      /* concentration index of Eq. 6: TCA_METRIC_HHI (the method's) or
+                          TCA_METRIC_ENTROPY (the appendix ablation: entropy of the scores
+                          renormalised inside the block, divided by ln b)          */
 } tca_params;
 
 /* ------------------------------------------------------------------ host --

@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtca.so")
 
 TCA_BF16, TCA_F32 = 0, 1
+TCA_METRIC_HHI, TCA_METRIC_ENTROPY = 0, 1
 TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
 
 if not os.path.exists(LIB_PATH):
@@ -31,7 +32,7 @@ class tca_params(C.Structure):
     _fields_ = [
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32),
-        ("alpha", C.c_double), ("scale", C.c_double),
+        ("alpha", C.c_double), ("scale", C.c_double), ("metric", C.c_int32),
     ]
 
 
@@ -112,8 +113,9 @@ def _stream(stream):
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha=0.5, scale=0.0) -> tca_params:
-    return tca_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha, scale)
+def make_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha=0.5, scale=0.0,
+                metric=TCA_METRIC_HHI) -> tca_params:
+    return tca_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha, scale, metric)
 
 
 # ---------------------------------------------------------------- host --

@@ -54,6 +54,8 @@ int check_params(const tca_params* prm) {
     return fail(TCA_ERR_INVALID, "alpha=%g outside [0,1]", prm->alpha);
   if (!(prm->scale >= 0.0) || !std::isfinite(prm->scale))
     return fail(TCA_ERR_INVALID, "scale=%g must be finite and >= 0", prm->scale);
+  if (prm->metric != TCA_METRIC_HHI && prm->metric != TCA_METRIC_ENTROPY)
+    return fail(TCA_ERR_UNSUPPORTED, "metric=%d", prm->metric);
   return TCA_OK;
 }
 

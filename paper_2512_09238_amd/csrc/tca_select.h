@@ -10,7 +10,7 @@ namespace tca {
 struct SelectWs {
   uint8_t* tokrank;   // [Hq][n_blocks*b]  rank of each token inside its block (0 = highest logit); calibration only
   uint64_t* keys;     // [Hq][n_blocks*b]  ranking key of each token (ordered logit bits, position in the low byte)
-  double* stats;      // [Hq][nbt][3]      per block: max logit, sum e^(x-max), sum e^(2(x-max))
+  double* stats;      // [Hq][nbt][4]      per block: max logit M, sum e^(x-M), sum e^(2(x-M)), sum e^(x-M) (x-M)
   int32_t* blk_t;     // [Hq][n_blocks]    budget t_j of each block (Eq. 7)
   int32_t* blk_dst;   // [Hq][n_blocks]    first destination row of each block inside the head's region
   size_t bytes;

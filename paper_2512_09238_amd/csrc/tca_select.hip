@@ -32,6 +32,7 @@ constexpr int kAssignThreads = 1024;
 constexpr int kGatherThreads = 256;
 constexpr int kGatherRows = 2;        // rows per thread in flight in the copy loop (4 measured the same)
 constexpr int kHeadsPerLaunch = 32;
+constexpr int kBlockStats = 4;        // doubles per (head, block) in SelectWs::stats
 
 SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
   int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
@@ -40,7 +41,7 @@ SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
   char* base = (char*)ws;
   w.tokrank = (uint8_t*)(base + off); off = align_up(off + (size_t)Hq * nb * b, 256);
   w.keys = (uint64_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * b * sizeof(uint64_t), 256);
-  w.stats = (double*)(base + off);    off = align_up(off + (size_t)Hq * nbt * 3 * sizeof(double), 256);
+  w.stats = (double*)(base + off);    off = align_up(off + (size_t)Hq * nbt * kBlockStats * sizeof(double), 256);
   w.blk_t = (int32_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
   w.blk_dst = (int32_t*)(base + off); off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
   w.bytes = off;
@@ -139,17 +140,20 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     double mx = -INFINITY;
     for (int i = lane; i < b; i += kWave) mx = fmax(mx, xs[g][i]);
     mx = group_max(mx, kWave);
-    double e1 = 0.0, e2 = 0.0;
+    double e1 = 0.0, e2 = 0.0, e3 = 0.0;
     for (int i = lane; i < b; i += kWave) {
-      const double e = exp(xs[g][i] - mx);
+      const double dx = xs[g][i] - mx;
+      const double e = exp(dx);
       e1 += e;
       e2 += e * e;
+      if (e > 0.0) e3 += e * dx;                         // 0 * (-inf) counts as 0
     }
     e1 = group_sum(e1, kWave);
     e2 = group_sum(e2, kWave);
+    e3 = group_sum(e3, kWave);
     if (lane == 0) {
-      double* st = stats + ((size_t)(kvh * G + g) * nbt + j) * 3;
-      st[0] = mx; st[1] = e1; st[2] = e2;
+      double* st = stats + ((size_t)(kvh * G + g) * nbt + j) * kBlockStats;
+      st[0] = mx; st[1] = e1; st[2] = e2; st[3] = e3;
     }
   }
   if (j >= n_blocks) return;             // the tail block only feeds the normaliser
@@ -203,7 +207,7 @@ __device__ __forceinline__ double block_reduce_sum(double v, double* red) {
 
 // grid (heads in this launch); block 1024.
 __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
-    AssignArgs args, int head0, int nk, int m, int nbt, double alpha,
+    AssignArgs args, int head0, int nk, int m, int nbt, int b, double alpha, int metric,
     const double* __restrict__ stats, int32_t* __restrict__ n_rows,
     int32_t* __restrict__ blk_t, int32_t* __restrict__ blk_dst) {
   __shared__ double hs[TCA_MAX_BLOCKS];
@@ -213,18 +217,18 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
   __shared__ int32_t scan[kAssignThreads];
   const int tid = threadIdx.x;
   const int hl = blockIdx.x, h = head0 + hl;
-  const double* st = stats + (size_t)h * nbt * 3;
+  const double* st = stats + (size_t)h * nbt * kBlockStats;
 
   // the statistics of this thread's blocks (block j = tid + k * 1024, tail block included), read once
   constexpr int KMAX = TCA_MAX_BLOCKS / kAssignThreads + 1;
-  double bM[KMAX], bE1[KMAX], bE2[KMAX];
+  double bM[KMAX], bE1[KMAX], bE2[KMAX];              // bE2: the statistic the chosen index needs
 #pragma unroll
   for (int k = 0; k < KMAX; ++k) {
     const int j = tid + k * kAssignThreads;
     const bool in = j < nbt;
-    bM[k] = in ? st[j * 3] : -INFINITY;
-    bE1[k] = in ? st[j * 3 + 1] : 0.0;
-    bE2[k] = in ? st[j * 3 + 2] : 0.0;
+    bM[k] = in ? st[j * kBlockStats] : -INFINITY;
+    bE1[k] = in ? st[j * kBlockStats + 1] : 0.0;
+    bE2[k] = in ? st[j * kBlockStats + (metric == TCA_METRIC_ENTROPY ? 3 : 2)] : 0.0;
   }
   // global normaliser of Eq. 5 over every scored token, tail included
   double mx = -INFINITY;
@@ -245,8 +249,12 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
     const int j = tid + k * kAssignThreads;
     if (j < m) {
       const double mass = bM[k] / z;
-      const double hhi = bE2[k] / (bE1[k] * bE1[k]);
-      hs[j] = (1.0 - alpha) * mass + alpha * (1.0 - hhi);
+      // HHI of the block (Eq. 6), or the entropy of the scores renormalised inside it:
+      // t_i = e_i / E1  =>  -sum t_i ln t_i = ln E1 - (sum e_i (x_i - M)) / E1
+      const double spread = metric == TCA_METRIC_ENTROPY
+                                ? (log(bE1[k]) - bE2[k] / bE1[k]) / log((double)b)
+                                : 1.0 - bE2[k] / (bE1[k] * bE1[k]);
+      hs[j] = (1.0 - alpha) * mass + alpha * spread;
     }
   }
   __syncthreads();
@@ -457,7 +465,7 @@ void select_assign_stage(const tca_params* prm, int64_t n_tokens, const double* 
       aa.cap[hl] = cap[h0 + hl];
     }
     hipLaunchKernelGGL(assign_kernel, dim3(nh), dim3(kAssignThreads), 0, st, aa, h0, nk, (int)nb,
-                       (int)nbt, prm->alpha, stats, n_rows, blk_t, blk_dst);
+                       (int)nbt, b, prm->alpha, prm->metric, stats, n_rows, blk_t, blk_dst);
   }
 }
 

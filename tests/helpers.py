@@ -13,8 +13,9 @@ MARGIN = 1e-6
 TOL = {"bf16": 2e-2, "f32": 1e-4}      # max-abs output tolerance per storage type
 
 
-def params_for(tb, Hq, Hkv, d, b, w, dtype, alpha=0.5):
-    return tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16 if dtype == "bf16" else tb.TCA_F32, alpha, 0.0)
+def params_for(tb, Hq, Hkv, d, b, w, dtype, alpha=0.5, metric="hhi"):
+    return tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16 if dtype == "bf16" else tb.TCA_F32, alpha, 0.0,
+                          tb.TCA_METRIC_ENTROPY if metric == "entropy" else tb.TCA_METRIC_HHI)
 
 
 def gpu_select(tb, bufs_mod, prm, x, P, L=None, pos0=0, gb=None):

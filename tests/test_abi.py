@@ -68,6 +68,7 @@ def test_argument_errors_are_codes_not_crashes():
         tb.tca_select_rows(bad, 4, np.ones((6, 8)) / 8)
     assert tb.tca_select_workspace_bytes(bad, 1024) == 0
     for prm in (tb.make_params(4, 2, 96, 128, 4096, tb.TCA_BF16), tb.make_params(4, 2, 128, 128, 100, tb.TCA_BF16),
+                tb.make_params(4, 2, 128, 128, 4096, tb.TCA_BF16, 0.5, 0.0, 2),
                 tb.make_params(4, 2, 128, 128, 4096, 7), tb.make_params(256, 256, 128, 128, 4096, 0)):
         with pytest.raises(tb.TcaError):
             tb.tca_select_rows(prm, 4, np.ones((prm.n_q_heads, 8)) / 8)

@@ -70,6 +70,27 @@ def test_select_matches_oracle(tb, bufs, case):
         assert torch.equal(kg, kref) and torch.equal(vg, vref)
 
 
+@pytest.mark.parametrize("case", [SELECT_CASES[1], SELECT_CASES[2], SELECT_CASES[3], SELECT_CASES[5]],
+                         ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}")
+def test_select_with_the_entropy_index_matches_oracle(tb, bufs, case):
+    """Eq. 6 with the entropy concentration index of the appendix ablation instead of the HHI;
+    alpha = 0.7 so that the index, not the block mass, decides most of the ranking."""
+    kind, Hq, Hkv, d, L, dtype, b, w, seed = case
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype, alpha=0.7, metric="entropy")
+    gb, *_ = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    sels = orc.select_all_heads(wl.to_f64(x["Q"][:, L - 1]), wl.to_f64(x["K"]), b, P_orc, 0.7, metric="entropy")
+    sels_hhi = orc.select_all_heads(wl.to_f64(x["Q"][:, L - 1]), wl.to_f64(x["K"]), b, P_orc, 0.7)
+    differs = False
+    for h in range(Hq):
+        H.assert_selection(sels[h], H.head_indices(gb, h), b, P_orc[h], tag=f"head {h}")
+        differs |= not np.array_equal(sels[h].S, sels_hhi[h].S)
+    if L // b >= 8:
+        assert differs, "the two indices picked identical sets for every head: the switch is not exercised"
+
+
 def test_select_rejects_more_blocks_than_it_can_rank(tb, bufs):
     Hq, Hkv, d, b, w = 2, 1, 64, 2, 16
     L = 2 * (4096 + 1)
