@@ -35,6 +35,11 @@ here and the only behaviour the GPU path implements):
     global subset; they become visible once they leave the window.
   * chunked prefill is not in the paper; `tca_prefill_chunked` states the rule
     used (each chunk scored by its own last query over its own keys).
+  * group-shared selection (share=True; an extension for GQA, not in the paper):
+    one index set per KV head, chosen by the mean over the group's query heads of
+    their Eq. 5 scores; Eq. 6-8 then run on that mean score unchanged, and every
+    query head of the group attends to the shared set.  See the section
+    "Group-shared selection" below.
 
 Functions pinned by tests/test_oracle_pins.py; none is "parity unpinned"
 except the readings listed above, which are choices rather than facts.
@@ -272,6 +277,64 @@ def select_all_heads(q_last, K, b, p, alpha, scale=None, metric: str = "hhi") ->
 
 
 # --------------------------------------------------------------------------
+# Group-shared selection for GQA (extension; the paper applies Eq. 5-8 per head)
+# --------------------------------------------------------------------------
+def group_scores_from_logits(X: np.ndarray) -> np.ndarray:
+    """sbar_i = (1/G) sum_g softmax(X_g)_i : the mean of the group's Eq. 5 scores.
+    X [G, L] holds the last-query logits of the G query heads that share one KV head."""
+    X = np.asarray(X, F64)
+    return np.stack([softmax(X[g]) for g in range(X.shape[0])]).sum(axis=0) / X.shape[0]
+
+
+def block_metric_of_scores(s: np.ndarray, b: int, alpha: float, metric: str = "hhi") -> np.ndarray:
+    """Eq. 6 written on scores rather than logits:
+    h_j = (1-alpha) sum_{B_j} s + alpha (1 - sum s^2 / (sum s)^2), or with the entropy of
+    s / sum_{B_j} s over ln b as the second term.  s must not underflow to zero over a whole block."""
+    if metric not in ("hhi", "entropy"):
+        raise ValueError(metric)
+    s = np.asarray(s, F64)
+    m = s.shape[0] // b
+    h = np.empty(m, F64)
+    for j in range(m):
+        sb = s[j * b:(j + 1) * b]
+        mass = sb.sum()
+        if metric == "hhi":
+            spread = 1.0 - (sb * sb).sum() / (mass * mass)
+        else:
+            t = sb / mass
+            nz = t > 0.0
+            spread = -(t[nz] * np.log(t[nz])).sum() / np.log(b)
+        h[j] = (1.0 - alpha) * mass + alpha * spread
+    return h
+
+
+def select_shared(q_group, K, b: int, p, alpha: float, scale: float | None = None,
+                  metric: str = "hhi") -> Selection:
+    """Alg. 2 lines 1-6 for one KV head shared by the query heads q_group [G, d]:
+    the token score is the group mean of Eq. 5; Eq. 6, 7, 8 as for a single head.
+    Selection.x holds ln(sbar) (the quantity comparable to a logit)."""
+    K = np.asarray(K, F64)
+    q_group = np.asarray(q_group, F64)
+    L = K.shape[0]
+    m = L // b
+    X = np.stack([last_query_logits(q_group[g], K, scale) for g in range(q_group.shape[0])])
+    sbar = group_scores_from_logits(X)
+    h = block_metric_of_scores(sbar, b, alpha, metric)
+    t = block_budgets(b, h, p)
+    parts = [j * b + top_t(sbar[j * b:(j + 1) * b], int(t[j])) for j in range(m)]
+    S = np.concatenate(parts).astype(np.int64) if parts else np.zeros(0, np.int64)
+    with np.errstate(divide="ignore"):
+        return Selection(S=S, x=np.log(sbar), h=h, t=t)
+
+
+def select_all_groups(q_last, K, b, p, alpha, scale=None, metric: str = "hhi") -> list[Selection]:
+    """q_last [Hq,d], K [Hkv,L,d], p [Hkv,nk]: one selection per KV head."""
+    Hq, Hkv = q_last.shape[0], K.shape[0]
+    G = Hq // Hkv
+    return [select_shared(q_last[g * G:(g + 1) * G], K[g], b, p[g], alpha, scale, metric) for g in range(Hkv)]
+
+
+# --------------------------------------------------------------------------
 # Eq. 1 and Eq. 2 : attention
 # --------------------------------------------------------------------------
 def dense_causal_attention(Q, K, V, scale: float | None = None) -> np.ndarray:
@@ -311,20 +374,23 @@ def tca_attention(Q, K, V, S, w: int, scale: float | None = None, q_pos0: int = 
     return np.stack([attention_row(Q[r], q_pos0 + r, K, V, S, w, scale) for r in range(Q.shape[0])])
 
 
-def tca_prefill(Q, K, V, b: int, w: int, p, alpha: float, scale: float | None = None):
-    """Alg. 2 for all heads.  Q [Hq,L,d], K,V [Hkv,L,d], p [Hq,nk].
-    Returns (O [Hq,L,d], list of Selection)."""
+def tca_prefill(Q, K, V, b: int, w: int, p, alpha: float, scale: float | None = None, share: bool = False):
+    """Alg. 2 for all heads.  Q [Hq,L,d], K,V [Hkv,L,d], p [Hq,nk] (share: [Hkv,nk]).
+    Returns (O [Hq,L,d], list of Selection: one per query head, or per KV head when share)."""
     Hq, L, _ = Q.shape
     Hkv = K.shape[0]
-    sels = select_all_heads(np.asarray(Q)[:, L - 1, :], K, b, p, alpha, scale)
+    q_last = np.asarray(Q)[:, L - 1, :]
+    sels = select_all_groups(q_last, K, b, p, alpha, scale) if share else select_all_heads(q_last, K, b, p, alpha, scale)
     O = np.stack([
-        tca_attention(Q[h], K[kv_head_of(h, Hq, Hkv)], V[kv_head_of(h, Hq, Hkv)], sels[h].S, w, scale)
+        tca_attention(Q[h], K[kv_head_of(h, Hq, Hkv)], V[kv_head_of(h, Hq, Hkv)],
+                      sels[kv_head_of(h, Hq, Hkv) if share else h].S, w, scale)
         for h in range(Hq)
     ])
     return O, sels
 
 
-def tca_prefill_chunked(Q, K, V, b: int, w: int, p, alpha: float, chunk: int, scale: float | None = None):
+def tca_prefill_chunked(Q, K, V, b: int, w: int, p, alpha: float, chunk: int, scale: float | None = None,
+                        share: bool = False):
     """Chunked prefill.  NOT in the paper: a serving extension, defined here as
     follows.  The sequence arrives in chunks of `chunk` tokens (a multiple of b).
     For the chunk covering positions [c0, c1): the chunk's last query scores the
@@ -336,23 +402,27 @@ def tca_prefill_chunked(Q, K, V, b: int, w: int, p, alpha: float, chunk: int, sc
     plus its window.  With one chunk covering the sequence this is Alg. 2.
 
     Q [Hq,L,d], K,V [Hkv,L,d], p [Hq,nk].  Returns (O [Hq,L,d], list of index sets).
+    share: one set per KV head (p [Hkv,nk]), each chunk scored by the group mean of its last queries.
     """
     Q, K, V = (np.asarray(a, F64) for a in (Q, K, V))
     Hq, L, _ = Q.shape
     Hkv = K.shape[0]
     if chunk % b != 0:
         raise ValueError("chunk must be a multiple of the block size")
-    S = [np.zeros(0, np.int64) for _ in range(Hq)]
+    G = Hq // Hkv
+    S = [np.zeros(0, np.int64) for _ in range(Hkv if share else Hq)]
     O = np.empty((Hq, L, V.shape[2]), F64)
     for c0 in range(0, L, chunk):
         c1 = min(L, c0 + chunk)
+        for n in range(len(S)):
+            if share:
+                sel = select_shared(Q[n * G:(n + 1) * G, c1 - 1], K[n, c0:c1], b, p[n], alpha, scale)
+            else:
+                sel = select(Q[n, c1 - 1], K[kv_head_of(n, Hq, Hkv), c0:c1], b, p[n], alpha, scale)
+            S[n] = np.concatenate([S[n], c0 + sel.S]).astype(np.int64)
         for h in range(Hq):
             g = kv_head_of(h, Hq, Hkv)
-            sel = select(Q[h, c1 - 1], K[g, c0:c1], b, p[h], alpha, scale)
-            S[h] = np.concatenate([S[h], c0 + sel.S]).astype(np.int64)
-        for h in range(Hq):
-            g = kv_head_of(h, Hq, Hkv)
-            O[h, c0:c1] = tca_attention(Q[h, c0:c1], K[g, :c1], V[g, :c1], S[h], w, scale, q_pos0=c0)
+            O[h, c0:c1] = tca_attention(Q[h, c0:c1], K[g, :c1], V[g, :c1], S[g if share else h], w, scale, q_pos0=c0)
     return O, S
 
 
@@ -364,7 +434,7 @@ class HeadCache:
     """KV cache of one sequence: per query head the global subset (positions,
     ascending), plus every dense row seen so far so the window can be read from
     it (a real cache keeps only the last w of them)."""
-    S: list = field(default_factory=list)      # [Hq] int64 arrays
+    S: list = field(default_factory=list)      # [Hq] int64 arrays ([Hkv] with group-shared selection)
     K: np.ndarray | None = None                # [Hkv, T, d] all rows so far
     V: np.ndarray | None = None
 
@@ -378,7 +448,8 @@ def cache_after_prefill(K, V, sels: list[Selection]) -> HeadCache:
     return HeadCache(S=[s.S.copy() for s in sels], K=np.asarray(K, F64).copy(), V=np.asarray(V, F64).copy())
 
 
-def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: float | None = None) -> np.ndarray:
+def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: float | None = None,
+                share: bool = False) -> np.ndarray:
     """One generated token.  q [Hq,d]; k_new, v_new [Hkv,d] are the rows of the
     token at position T = cache.length, appended before attending.
 
@@ -386,6 +457,8 @@ def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: flo
     Selection: if T is the last position of a block, that block's b rows are
     scored with this step's query (Eq. 5 restricted to the block) and the top
     t = floor(sum_k k p_k) positions are appended to the head's global subset.
+    share: cache.S and p are per KV head; the block's rows are ranked by the group
+    mean of the heads' scores, each normalised over the block.
     """
     q = np.asarray(q, F64)
     Hq, d = q.shape
@@ -398,14 +471,19 @@ def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: flo
     out = np.empty((Hq, cache.V.shape[2]), F64)
     for h in range(Hq):
         g = kv_head_of(h, Hq, Hkv)
-        out[h] = attention_row(q[h], T, cache.K[g], cache.V[g], cache.S[h], w, scale)
+        out[h] = attention_row(q[h], T, cache.K[g], cache.V[g], cache.S[g if share else h], w, scale)
     if (T + 1) % b == 0:
         j = T // b
-        for h in range(Hq):
-            g = kv_head_of(h, Hq, Hkv)
-            x = last_query_logits(q[h], cache.K[g, j * b:(j + 1) * b], scale)
-            keep = j * b + top_t(x, decode_budget(b, p[h]))
-            cache.S[h] = np.concatenate([cache.S[h], keep]).astype(np.int64)
+        G = Hq // Hkv
+        for n in range(len(cache.S)):
+            if share:
+                X = np.stack([last_query_logits(q[h], cache.K[n, j * b:(j + 1) * b], scale)
+                              for h in range(n * G, (n + 1) * G)])
+                x = group_scores_from_logits(X)
+            else:
+                x = last_query_logits(q[n], cache.K[kv_head_of(n, Hq, Hkv), j * b:(j + 1) * b], scale)
+            keep = j * b + top_t(x, decode_budget(b, p[n]))
+            cache.S[n] = np.concatenate([cache.S[n], keep]).astype(np.int64)
     return out
 
 
@@ -464,11 +542,36 @@ def calibrate_head(Q, K, b: int, cands: np.ndarray, tau: float, alpha: float,
     return Calibration(last, cands[last].copy(), a, n, True)
 
 
+def calibrate_group(Qg, K, b: int, cands: np.ndarray, tau: float, alpha: float,
+                    scale: float | None = None) -> Calibration:
+    """Alg. 1 for one KV head with group-shared selection: Qg [G,L,d].  The importance of
+    key k is the mean over the group of the heads' column means (Eq. 4 inner term), the
+    candidate sets come from `select_shared`."""
+    Qg = np.asarray(Qg, F64)
+    G, L, _ = Qg.shape
+    abar = np.stack([column_means(dense_causal_probs(Qg[g], K, scale)) for g in range(G)]).sum(axis=0) / G
+    a = np.empty(len(cands), F64)
+    n = np.empty(len(cands), np.int64)
+    for i, p in enumerate(cands):
+        S = select_shared(Qg[:, L - 1], K, b, p, alpha, scale).S
+        a[i] = cumulative_score(abar, S)
+        n[i] = len(S)
+    valid = [i for i in range(len(cands)) if a[i] >= tau]
+    if valid:
+        best = min(valid, key=lambda i: (n[i], i))
+        return Calibration(best, cands[best].copy(), a, n, False)
+    last = len(cands) - 1
+    return Calibration(last, cands[last].copy(), a, n, True)
+
+
 def calibrate(Q, K, b: int, M: int, sigma: float, tau: float, alpha: float,
-              scale: float | None = None) -> list[Calibration]:
-    """Alg. 1 for all heads.  Q [Hq,L,d], K [Hkv,L,d]."""
+              scale: float | None = None, share: bool = False) -> list[Calibration]:
+    """Alg. 1 for all heads.  Q [Hq,L,d], K [Hkv,L,d].  share: one result per KV head."""
     Hq, Hkv = Q.shape[0], K.shape[0]
     cands = candidates(b, M, sigma)
+    if share:
+        G = Hq // Hkv
+        return [calibrate_group(Q[g * G:(g + 1) * G], K[g], b, cands, tau, alpha, scale) for g in range(Hkv)]
     return [calibrate_head(Q[h], K[kv_head_of(h, Hq, Hkv)], b, cands, tau, alpha, scale) for h in range(Hq)]
 
 

@@ -486,3 +486,125 @@ def test_chunked_prefill_reduces_to_alg2_and_follows_its_definition():
     # chunk not a multiple of b is rejected
     with pytest.raises(ValueError):
         orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=10)
+
+
+# ------------------------------------------------- group-shared selection --
+def test_group_shared_hand_worked():
+    sbar, h, t, S = read_rows("group_shared_b2_L4.txt")
+    X = np.log(np.array([[4.0, 1.0, 3.0, 2.0], [1.0, 2.0, 3.0, 4.0]]))
+    np.testing.assert_allclose(orc.group_scores_from_logits(X), sbar, atol=1e-15)
+    np.testing.assert_allclose(orc.block_metric_of_scores(np.array(sbar), 2, 0.5), h, atol=1e-15)
+    # through select_shared: d = 4, K = identity rows, so that q_g . k_i = q_g[i]; scale 1
+    sel = orc.select_shared(X, np.eye(4), 2, np.array([0.5, 0.5]), 0.5, scale=1.0)
+    np.testing.assert_allclose(sel.h, h, atol=1e-15)
+    assert list(sel.t) == [int(v) for v in t] and list(sel.S) == [int(v) for v in S]
+    np.testing.assert_allclose(np.exp(sel.x), sbar, atol=1e-15)
+
+
+def test_group_shared_reduces_to_per_head_selection():
+    rng = np.random.default_rng(21)
+    L, d, b = 75, 8, 8
+    K = rng.standard_normal((L, d))
+    q = 2 * rng.standard_normal((3, d))
+    p = rng.dirichlet(np.ones(4))
+    for metric in ("hhi", "entropy"):
+        one = orc.select(q[0], K, b, p, 0.4, metric=metric)
+        # a group of one head, and a group of identical heads, are that head
+        for grp in (q[:1], np.repeat(q[:1], 3, axis=0)):
+            sh = orc.select_shared(grp, K, b, p, 0.4, metric=metric)
+            assert list(sh.S) == list(one.S) and list(sh.t) == list(one.t)
+            np.testing.assert_allclose(sh.h, one.h, rtol=1e-12, atol=1e-15)
+    # the metric written on scores equals the one written on logits
+    x = orc.last_query_logits(q[1], K)
+    for metric in ("hhi", "entropy"):
+        np.testing.assert_allclose(orc.block_metric_of_scores(orc.softmax(x), b, 0.3, metric),
+                                   orc.block_metric(x, b, 0.3, metric), rtol=1e-12)
+
+
+def test_group_shared_invariants_and_brute_force():
+    rng = np.random.default_rng(22)
+    L, d, b, G = 53, 6, 4, 3
+    K = rng.standard_normal((L, d))
+    q = 3 * rng.standard_normal((G, d))
+    p = np.array([0.3, 0.45, 0.25])
+    sel = orc.select_shared(q, K, b, p, 0.5)
+    m = L // b
+    assert len(sel.S) == orc.selected_rows(b, m, p)
+    assert abs(np.exp(sel.x).sum() - 1.0) < 1e-13                      # a mean of distributions is one
+    # the order of the heads inside the group does not matter
+    sel2 = orc.select_shared(q[[2, 0, 1]], K, b, p, 0.5)
+    assert list(sel2.S) == list(sel.S)
+    # brute force with python loops and library softmax
+    sc = 1.0 / math.sqrt(d)
+    sbar = [0.0] * L
+    for g in range(G):
+        sg = scipy_softmax([sum(q[g][e] * K[i][e] for e in range(d)) * sc for i in range(L)])
+        for i in range(L):
+            sbar[i] += sg[i] / G
+    hb = []
+    for j in range(m):
+        blk = sbar[j * b:(j + 1) * b]
+        hb.append(0.5 * sum(blk) + 0.5 * (1.0 - sum(v * v for v in blk) / sum(blk) ** 2))
+    np.testing.assert_allclose(sel.h, hb, rtol=1e-12)
+    order = sorted(range(m), key=lambda j: (hb[j], j))
+    psi = list(orc.psi_list(b, m, p))
+    expect = []
+    for r, j in enumerate(order):
+        best = sorted(range(b), key=lambda i: (-sbar[j * b + i], i))[:psi[r]]
+        expect += [j * b + i for i in best]
+    assert sorted(expect) == list(sel.S)
+    # it is not the per-head selection of any single head, nor the selection by mean logits
+    assert any(list(orc.select(q[g], K, b, p, 0.5).S) != list(sel.S) for g in range(G))
+    assert list(orc.select(q.mean(axis=0), K, b, p, 0.5).S) != list(sel.S)
+
+
+def test_group_shared_attention_decode_and_calibration():
+    rng = np.random.default_rng(23)
+    Hq, Hkv, L, d, b, w = 4, 2, 40, 8, 4, 8
+    Q = rng.standard_normal((Hq, L, d))
+    K = rng.standard_normal((Hkv, L, d))
+    V = rng.standard_normal((Hkv, L, d))
+    p = rng.dirichlet(np.ones(3), size=Hkv)
+    O, sels = orc.tca_prefill(Q, K, V, b, w, p, 0.5, share=True)
+    assert len(sels) == Hkv
+    # every query head attends to its group's set: the row recomputed from Eq. 2
+    for h in range(Hq):
+        np.testing.assert_allclose(O[h, 33], orc.attention_row(Q[h, 33], 33, K[h // 2], V[h // 2], sels[h // 2].S, w),
+                                   rtol=1e-13)
+    # full budget: dense attention, shared or not
+    full = np.tile(np.array([0.0, 0.0, 1.0]), (Hkv, 1))
+    Od, _ = orc.tca_prefill(Q, K, V, b, w, full, 0.5, share=True)
+    for h in range(Hq):
+        np.testing.assert_allclose(Od[h], orc.dense_causal_attention(Q[h], K[h // 2], V[h // 2]), rtol=1e-12)
+    # one chunk = Alg. 2; two chunks: the second chunk's set comes from its own keys and last queries
+    Oc, Sc = orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=L, share=True)
+    np.testing.assert_allclose(Oc, O, rtol=1e-13)
+    Oc2, Sc2 = orc.tca_prefill_chunked(Q, K, V, b, w, p, 0.5, chunk=20, share=True)
+    for g in range(Hkv):
+        first = orc.select_shared(Q[2 * g:2 * g + 2, 19], K[g, :20], b, p[g], 0.5).S
+        second = 20 + orc.select_shared(Q[2 * g:2 * g + 2, 39], K[g, 20:40], b, p[g], 0.5).S
+        assert list(Sc2[g]) == list(first) + list(second)
+    # decode: the step that follows prefill reproduces the last prefill row; a completed block is
+    # ranked by the group mean of the block-normalised scores
+    cache = orc.HeadCache(S=[s.S.copy() for s in sels], K=K[:, : L - 1].copy(), V=V[:, : L - 1].copy())
+    before = [s.copy() for s in cache.S]
+    out = orc.decode_step(cache, Q[:, L - 1], K[:, L - 1], V[:, L - 1], b, w, p, share=True)
+    np.testing.assert_allclose(out, O[:, L - 1], rtol=1e-12)
+    j = (L - 1) // b
+    for g in range(Hkv):
+        sb = np.mean([scipy_softmax(K[g, j * b:(j + 1) * b] @ Q[h, L - 1] / math.sqrt(d)) for h in (2 * g, 2 * g + 1)], axis=0)
+        t = orc.decode_budget(b, p[g])
+        keep = sorted(j * b + i for i in sorted(range(b), key=lambda i: (-sb[i], i))[:t])
+        assert list(cache.S[g]) == list(before[g]) + keep
+    # calibration: a group of identical heads calibrates like the single head
+    Qs = np.repeat(Q[:1], 2, axis=0)
+    one = orc.calibrate(Qs[:1], K[:1], b, 5, 1.0, 0.6, 0.5)[0]
+    grp = orc.calibrate(Qs, K[:1], b, 5, 1.0, 0.6, 0.5, share=True)[0]
+    assert grp.index == one.index and list(grp.n) == list(one.n)
+    np.testing.assert_allclose(grp.a, one.a, rtol=1e-12)
+    # and for distinct heads a_i is the sum over the shared set of the group-mean column means
+    cal = orc.calibrate(Q[:2], K[:1], b, 5, 1.0, 0.6, 0.5, share=True)[0]
+    cands = orc.candidates(b, 5, 1.0)
+    S2 = orc.select_shared(Q[:2, L - 1], K[0], b, cands[2], 0.5).S
+    cm = 0.5 * (orc.column_means(orc.dense_causal_probs(Q[0], K[0])) + orc.column_means(orc.dense_causal_probs(Q[1], K[0])))
+    assert abs(cal.a[2] - cm[S2].sum()) < 1e-13
