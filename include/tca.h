@@ -22,10 +22,16 @@
  *       K, V : [n_kv_heads, kv_stride rows, head_dim]  (kv_stride >= rows used)
  *     Element type per tca_params.dtype: TCA_BF16 (bfloat16) or TCA_F32 (float).
  *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).  Every query head
- *     owns its own selection (the method is applied to each head independently, Sec. IV).
- *   - Compacted global subset: idx / Kg / Vg hold, for head h, rows
- *     offs[h] .. offs[h] + n_rows[h] - 1 of a flat buffer (offs = capacity prefix
- *     sums, host array of n_q_heads+1 entries; App. C "flatten all head tokens
+ *     owns its own selection (the method is applied to each head independently, Sec. IV):
+ *     there are Hs = n_q_heads "selection heads".  With tca_params.share =
+ *     TCA_SHARE_GROUP (an extension for grouped-query attention, not in the paper)
+ *     the query heads of a group share one selection, Hs = n_kv_heads, and selection
+ *     head n serves query heads n*G .. n*G+G-1; tca_selection_heads() returns Hs.
+ *     Every per-head argument below that concerns the selection (p, offs, n_rows,
+ *     rows_out, the regions of idx / Kg / Vg) has one entry per selection head.
+ *   - Compacted global subset: idx / Kg / Vg hold, for selection head n, rows
+ *     offs[n] .. offs[n] + n_rows[n] - 1 of a flat buffer (offs = capacity prefix
+ *     sums, host array of Hs+1 entries; App. C "flatten all head tokens
  *     into a single contiguous buffer and precompute offsets").  idx is the
  *     absolute token position of each row, ascending within a head.
  *   - Positions are 0-based.  The local subset of the query at position i is the
@@ -61,6 +67,9 @@ extern "C" {
 #define TCA_METRIC_HHI      0
 #define TCA_METRIC_ENTROPY  1
 
+#define TCA_SHARE_HEAD      0
+#define TCA_SHARE_GROUP     1
+
 #define TCA_MAX_HEADS   128
 #define TCA_MAX_GROUP   8
 #define TCA_MAX_COUNTS  9        /* log2(256) + 1 */
@@ -78,11 +87,19 @@ typedef struct tca_params {
   int32_t metric;      /* concentration index of Eq. 6: TCA_METRIC_HHI (the method's) or
                           TCA_METRIC_ENTROPY (the appendix ablation: entropy of the scores
                           renormalised inside the block, divided by ln b)          */
+  int32_t share;       /* TCA_SHARE_HEAD: one selection per query head (the method's);
+                          TCA_SHARE_GROUP: one per KV head, tokens scored by the mean over
+                          the group's query heads of their Eq. 5 scores, so that the
+                          compacted cache holds each kept row once per KV head          */
 } tca_params;
 
 /* ------------------------------------------------------------------ host --
  * Small fp64 host routines: configurations (Eq. 3), the rank->budget map
  * (Eq. 7) and the sizes that follow from them.  No GPU is touched. */
+
+/* Hs, the number of selections kept per layer: n_q_heads, or n_kv_heads with
+ * TCA_SHARE_GROUP.  Negative on invalid params. */
+int tca_selection_heads(const tca_params* prm);
 
 /* Number of entries of a configuration p: |K| = log2(b)+1 for K={1,2,4,..,b}
  * (Sec. IV-A).  Returns TCA_ERR_UNSUPPORTED if b is not a supported block size. */
@@ -104,8 +121,8 @@ int tca_config_from_budget(int b, double sigma, double frac, double* p_out);
 int tca_psi_counts(int b, int64_t m, const double* p, int64_t* counts_out);
 
 /* Rows one tca_select call over n_blocks full blocks appends per head:
- * sum_k k c_k, independent of the data.  p: host [Hq][nk].  rows_out: host
- * [Hq] (nullable).  Returns the total over heads, or a negative error. */
+ * sum_k k c_k, independent of the data.  p: host [Hs][nk].  rows_out: host
+ * [Hs] (nullable).  Returns the total over heads, or a negative error. */
 int64_t tca_select_rows(const tca_params* prm, int64_t n_blocks, const double* p, int64_t* rows_out);
 
 /* t = floor(sum_k k p_k): rows kept from a block completed during decoding
@@ -113,7 +130,7 @@ int64_t tca_select_rows(const tca_params* prm, int64_t n_blocks, const double* p
 int tca_decode_budget(int b, const double* p);
 
 size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens);
-/* cap_rows: total rows of the flat global buffer (offs[Hq]). */
+/* cap_rows: total rows of the flat global buffer (offs[Hs]). */
 size_t tca_prefill_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows);
 /* max_head_rows: the largest capacity of one head's region, max_h (offs[h+1]-offs[h]). */
 size_t tca_decode_workspace_bytes(const tca_params* prm, int batch, int64_t max_head_rows);
@@ -134,13 +151,15 @@ size_t tca_calibrate_workspace_bytes(const tca_params* prm, int64_t L_cal, int M
  * ascending position order, to each head's region of idx / Kg / Vg, starting
  * at row offs[h] + n_rows[h]; n_rows[h] grows by tca_select_rows()[h].
  * Rows that would pass offs[h+1] are dropped (never written).
+ * TCA_SHARE_GROUP: the score of token j is sbar_j = (1/G) sum_g s_{g,j} over the G query
+ * heads of the group, each s_g the softmax of Eq. 5 for that head; Eq. 6-8 run on sbar.
  *
  *   q_last : device [Hq, d]
  *   K, V   : device [Hkv, kv_stride, d]; pos0 is a multiple of b; pos0+n_tokens <= kv_stride
- *   p      : host [Hq][nk]
- *   offs   : host [Hq+1]
- *   n_rows : device int32 [Hq], in/out (zero it before the first call)
- *   idx    : device int32 [offs[Hq]]; Kg, Vg: device [offs[Hq], d]
+ *   p      : host [Hs][nk]
+ *   offs   : host [Hs+1]
+ *   n_rows : device int32 [Hs], in/out (zero it before the first call)
+ *   idx    : device int32 [offs[Hs]]; Kg, Vg: device [offs[Hs], d]
  * All scoring arithmetic is fp64.  Inside a block, tokens whose scores agree to within
  * 2^-44 relative are ordered by position, like exact ties (the ranking key drops the last
  * 8 mantissa bits), so the selected sets agree with an fp64 reference except at such
@@ -159,7 +178,7 @@ int tca_select(const tca_params* prm, const void* q_last, const void* K, const v
  *
  *   Q, O   : device [Hq, n_queries, d]
  *   K, V   : device [Hkv, kv_stride, d], dense rows; q_pos0 + n_queries <= kv_stride
- *   idx, Kg, Vg, offs, n_rows : as written by tca_select (n_rows: device int32 [Hq])
+ *   idx, Kg, Vg, offs, n_rows : as written by tca_select (n_rows: device int32 [Hs])
  *   lse    : device float [Hq, n_queries] or NULL: natural-log sum of exp of the scaled logits
  * TCA_BF16: bf16 MFMA products, fp32 softmax and accumulation.  TCA_F32: fp32 throughout.
  * TCA_BF16 limit: (q_pos0 + n_queries + w + 128) * d * 2 bytes and every head's region must stay
@@ -175,11 +194,11 @@ int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_
  * (budgets belong to the model, Sec. IV-A).  All pointers are device memory. */
 typedef struct tca_cache {
   int32_t  batch;      /* B                                                            */
-  int64_t  cap_rows;   /* rows of the flat global buffer per sequence (= offs[Hq])      */
+  int64_t  cap_rows;   /* rows of the flat global buffer per sequence (= offs[Hs])      */
   int32_t* idx;        /* [B, cap_rows]     positions of the global rows                */
   void*    Kg;         /* [B, cap_rows, d]                                              */
   void*    Vg;         /* [B, cap_rows, d]                                              */
-  int32_t* n_rows;     /* [B, Hq]           rows filled per head (updated by the library) */
+  int32_t* n_rows;     /* [B, Hs]           rows filled per head (updated by the library) */
   void*    ringK;      /* [B, Hkv, w, d]    last w dense rows, position P at slot P mod w */
   void*    ringV;      /* [B, Hkv, w, d]                                                */
   int64_t* length;     /* [B]               tokens seen so far (updated by the library)  */
@@ -203,10 +222,12 @@ int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq
  * t = floor(sum_k k p_k) best (ties: lower position), in ascending position
  * order, are appended to the head's global region (dropped beyond capacity);
  * finally length[s] = T+1.
+ * TCA_SHARE_GROUP: the block's rows are ranked by the mean over the group's query heads of
+ * their scores, each normalised over the block, and appended once per KV head.
  *
  *   q      : device [B, Hq, d];  k_new, v_new: device [B, Hkv, d];  O: device [B, Hq, d]
- *   offs   : host [Hq+1] (capacity prefix sums, offs[Hq] == cache->cap_rows)
- *   p      : host [Hq][nk]
+ *   offs   : host [Hs+1] (capacity prefix sums, offs[Hs] == cache->cap_rows)
+ *   p      : host [Hs][nk]
  * Does not synchronise; lengths live on the device, so steps can be queued back to back.
  * The call only launches kernels on `stream` (no memset, no allocation, no read-back), so a
  * step may be captured into a HIP graph and replayed. */
@@ -223,12 +244,14 @@ int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* off
  * a_i = sum over S_i of the column means (Eq. 4), and the valid candidate
  * (a_i >= tau) that keeps the fewest rows (ties: lower i).  If none is valid the
  * last candidate is returned and fallback[h] = 1.
+ * TCA_SHARE_GROUP: one result per KV head; the candidates' sets come from the shared
+ * selection and a_i sums the mean over the group's query heads of their column means.
  *
  *   Qcal : device [Hq, L_cal, d];  Kcal: device [Hkv, L_cal, d]
- *   p_star   : host [Hq][nk]   chosen configuration
- *   cand_idx : host [Hq]       its 0-based index
- *   a_out    : host [Hq][M] or NULL: a_i;  n_out: host int64 [Hq][M] or NULL: |S_i|
- *   fallback : host [Hq] or NULL
+ *   p_star   : host [Hs][nk]   chosen configuration
+ *   cand_idx : host [Hs]       its 0-based index
+ *   a_out    : host [Hs][M] or NULL: a_i;  n_out: host int64 [Hs][M] or NULL: |S_i|
+ *   fallback : host [Hs] or NULL
  * Waits for `stream` before returning (results are host arrays). */
 int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, const void* Kcal, int64_t L_cal,
                           int M, double sigma, double tau,

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libtca.so")
 
 TCA_BF16, TCA_F32 = 0, 1
 TCA_METRIC_HHI, TCA_METRIC_ENTROPY = 0, 1
+TCA_SHARE_HEAD, TCA_SHARE_GROUP = 0, 1
 TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
 
 if not os.path.exists(LIB_PATH):
@@ -32,7 +33,7 @@ class tca_params(C.Structure):
     _fields_ = [
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block", C.c_int32), ("window", C.c_int32), ("dtype", C.c_int32),
-        ("alpha", C.c_double), ("scale", C.c_double), ("metric", C.c_int32),
+        ("alpha", C.c_double), ("scale", C.c_double), ("metric", C.c_int32), ("share", C.c_int32),
     ]
 
 
@@ -48,6 +49,7 @@ _P = C.POINTER
 _dbl_p, _i64_p, _i32_p = _P(C.c_double), _P(C.c_int64), _P(C.c_int32)
 
 EXPORTS = {
+    "tca_selection_heads": (C.c_int, [_P(tca_params)]),
     "tca_num_counts": (C.c_int, [C.c_int]),
     "tca_make_candidates": (C.c_int, [C.c_int, C.c_int, C.c_double, _dbl_p]),
     "tca_config_from_budget": (C.c_int, [C.c_int, C.c_double, C.c_double, _dbl_p]),
@@ -114,11 +116,15 @@ def _stream(stream):
 
 
 def make_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha=0.5, scale=0.0,
-                metric=TCA_METRIC_HHI) -> tca_params:
-    return tca_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha, scale, metric)
+                metric=TCA_METRIC_HHI, share=TCA_SHARE_HEAD) -> tca_params:
+    return tca_params(n_q_heads, n_kv_heads, head_dim, block, window, dtype, alpha, scale, metric, share)
 
 
 # ---------------------------------------------------------------- host --
+def tca_selection_heads(prm: tca_params) -> int:
+    return _check(lib.tca_selection_heads(C.byref(prm)))
+
+
 def tca_num_counts(b: int) -> int:
     return _check(lib.tca_num_counts(b))
 
@@ -144,7 +150,7 @@ def tca_psi_counts(b: int, m: int, p) -> np.ndarray:
 
 def tca_select_rows(prm: tca_params, n_blocks: int, p):
     p = _host(p, np.float64)
-    rows = np.empty(prm.n_q_heads, np.int64)
+    rows = np.empty(tca_selection_heads(prm), np.int64)
     total = _check(lib.tca_select_rows(C.byref(prm), n_blocks, p.ctypes.data_as(_dbl_p), rows.ctypes.data_as(_i64_p)))
     return total, rows
 
@@ -213,8 +219,8 @@ def tca_decode(prm, cache, offs, q, k_new, v_new, p, O, ws, stream=None):
 
 
 def tca_calibrate_budgets(prm, Qcal, Kcal, L_cal, M, sigma, tau, ws, stream=None):
-    """Returns dict(p_star [Hq,nk], cand_idx [Hq], a [Hq,M], n [Hq,M], fallback [Hq])."""
-    Hq, nk = prm.n_q_heads, tca_num_counts(prm.block)
+    """Returns dict(p_star [Hs,nk], cand_idx [Hs], a [Hs,M], n [Hs,M], fallback [Hs])."""
+    Hq, nk = tca_selection_heads(prm), tca_num_counts(prm.block)
     p_star = np.empty((Hq, nk), np.float64)
     cand = np.empty(Hq, np.int32)
     a = np.empty((Hq, M), np.float64)

@@ -28,7 +28,7 @@ def workspace(nbytes: int, device="cuda:0") -> torch.Tensor:
 
 
 class GlobalBuffers:
-    """idx / Kg / Vg / n_rows for one sequence with per-head capacities `cap`."""
+    """idx / Kg / Vg / n_rows for one sequence with capacities `cap`, one per selection head."""
 
     def __init__(self, prm, cap, device="cuda:0"):
         cap = np.asarray(cap, np.int64)
@@ -38,7 +38,7 @@ class GlobalBuffers:
         self.idx = torch.zeros(total, dtype=torch.int32, device=device)
         self.Kg = torch.zeros(total, d, dtype=torch_dtype(prm), device=device)
         self.Vg = torch.zeros(total, d, dtype=torch_dtype(prm), device=device)
-        self.n_rows = torch.zeros(prm.n_q_heads, dtype=torch.int32, device=device)
+        self.n_rows = torch.zeros(tb.tca_selection_heads(prm), dtype=torch.int32, device=device)
 
 
 class DecodeCache:
@@ -50,7 +50,7 @@ class DecodeCache:
         self.cap_rows = int(self.offs[-1])
         self.max_head_rows = int(cap.max()) if len(cap) else 0
         rows = max(self.cap_rows, 1)
-        d, w, Hkv, Hq = prm.head_dim, prm.window, prm.n_kv_heads, prm.n_q_heads
+        d, w, Hkv, Hq = prm.head_dim, prm.window, prm.n_kv_heads, tb.tca_selection_heads(prm)
         dt = torch_dtype(prm)
         self.idx = torch.zeros(batch, rows, dtype=torch.int32, device=device)
         self.Kg = torch.zeros(batch, rows, d, dtype=dt, device=device)

@@ -123,20 +123,24 @@ __global__ __launch_bounds__(kCalThreads) void cal_colmeans_kernel(
   if (lane == 0) abar[(size_t)h * L + k] = acc / (double)(L - k);
 }
 
-// grid (M, Hq); block 256.  a[h][i] = sum of abar over tokens with rank < t_block (Eq. 4).
+// grid (M, Hs); block 256.  a[h][i] = sum of abar over tokens with rank < t_block (Eq. 4).
+// Selection head h serves query heads h*GS .. h*GS+GS-1; with GS > 1 the importance of a
+// key is the mean of their column means.
 __global__ __launch_bounds__(kCalThreads) void cal_cand_score_kernel(
     const uint8_t* __restrict__ tokrank, const int32_t* __restrict__ blk_t, const double* __restrict__ abar,
-    int64_t L, int b, int64_t nb, int Hq, int M, double* __restrict__ a_out, int64_t* __restrict__ n_out) {
+    int64_t L, int b, int64_t nb, int Hs, int GS, int M, double* __restrict__ a_out, int64_t* __restrict__ n_out) {
   __shared__ double red[kCalThreads];
   __shared__ long long redn[kCalThreads];
   const int i = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
-  const int32_t* bt = blk_t + ((size_t)i * Hq + h) * nb;
+  const int32_t* bt = blk_t + ((size_t)i * Hs + h) * nb;
   const uint8_t* tr = tokrank + (size_t)h * (nb * b);
   double acc = 0.0;
   long long cnt = 0;
   for (int64_t k = tid; k < nb * b; k += kCalThreads) {
     if (tr[k] < bt[k / b]) {
-      acc += abar[(size_t)h * L + k];
+      double v = 0.0;
+      for (int g = 0; g < GS; ++g) v += abar[(size_t)(h * GS + g) * L + k];
+      acc += GS > 1 ? v / (double)GS : v;
       ++cnt;
     }
   }
@@ -163,11 +167,11 @@ struct CalWs {
   double* row_max;      // [Hq][L]
   double* row_sum;      // [Hq][L]
   double* abar;         // [Hq][L]
-  int32_t* blk_t;       // [M][Hq][nb]
-  int32_t* blk_dst;     // [M][Hq][nb]
-  int32_t* n_rows;      // [M][Hq]
-  double* a_dev;        // [Hq][M]
-  int64_t* n_dev;       // [Hq][M]
+  int32_t* blk_t;       // [M][Hs][nb]   (Hs selection heads <= Hq; sized for Hq)
+  int32_t* blk_dst;     // [M][Hs][nb]
+  int32_t* n_rows;      // [M][Hs]
+  double* a_dev;        // [Hs][M]
+  int64_t* n_dev;       // [Hs][M]
   void* q_last;         // [Hq][D] contiguous copy of the last query rows
   size_t bytes;
 };
@@ -178,7 +182,7 @@ static CalWs carve_cal_ws(void* ws, const tca_params* prm, int64_t L, int M) {
   size_t off = 0;
   const int Hq = prm->n_q_heads;
   const int64_t nb = L / prm->block;
-  const size_t sel = carve_select_ws(nullptr, Hq, prm->block, L).bytes;
+  const size_t sel = carve_select_ws(nullptr, prm, L).bytes;
   c.select_ws = base + off;          off = align_up(off + sel, 256);
   c.row_max = (double*)(base + off); off = align_up(off + (size_t)Hq * L * 8, 256);
   c.row_sum = (double*)(base + off); off = align_up(off + (size_t)Hq * L * 8, 256);
@@ -229,7 +233,7 @@ extern "C" int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, co
     return fail(TCA_ERR_INVALID, "tca_calibrate_budgets: NULL pointer argument");
   if (L_cal < 1 || M < 1 || M > 256 || !(sigma > 0.0))
     return fail(TCA_ERR_INVALID, "tca_calibrate_budgets: L_cal=%lld M=%d sigma=%g", (long long)L_cal, M, sigma);
-  const int Hq = prm->n_q_heads, b = prm->block, nk = block_log2(b) + 1;
+  const int Hs = sel_heads(prm), b = prm->block, nk = block_log2(b) + 1;
   const int64_t nb = L_cal / b;
   if (nb > TCA_MAX_BLOCKS)
     return fail(TCA_ERR_UNSUPPORTED, "tca_calibrate_budgets: %lld blocks exceed the limit of %d", (long long)nb,
@@ -256,24 +260,24 @@ extern "C" int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, co
   }
 
   // selection of every candidate (Alg. 1 line 4): scores and ranks once, budgets per candidate
-  SelectWs sw = carve_select_ws(c.select_ws, Hq, b, L_cal);
+  SelectWs sw = carve_select_ws(c.select_ws, prm, L_cal);
   select_score_stage(prm, c.q_last, Kcal, L_cal, L_cal, sw, st);
-  std::vector<double> a_host((size_t)Hq * M, 0.0);
-  std::vector<int64_t> n_host((size_t)Hq * M, 0);
+  std::vector<double> a_host((size_t)Hs * M, 0.0);
+  std::vector<int64_t> n_host((size_t)Hs * M, 0);
   if (nb > 0) {
-    const int64_t nz = (int64_t)M * Hq;
+    const int64_t nz = (int64_t)M * Hs;
     hipLaunchKernelGGL(cal_zero_kernel, dim3((unsigned)((nz + 255) / 256)), dim3(256), 0, st, c.n_rows, nz);
-    std::vector<double> p_all((size_t)Hq * nk);
+    std::vector<double> p_all((size_t)Hs * nk);
     int64_t cap[TCA_MAX_HEADS];
-    for (int h = 0; h < Hq; ++h) cap[h] = INT32_MAX;
+    for (int h = 0; h < Hs; ++h) cap[h] = INT32_MAX;
     for (int i = 0; i < M; ++i) {
-      for (int h = 0; h < Hq; ++h)
+      for (int h = 0; h < Hs; ++h)
         for (int e = 0; e < nk; ++e) p_all[(size_t)h * nk + e] = cands[(size_t)i * nk + e];
-      select_assign_stage(prm, L_cal, p_all.data(), cap, sw.stats, c.n_rows + (size_t)i * Hq,
-                          c.blk_t + (size_t)i * Hq * nb, c.blk_dst + (size_t)i * Hq * nb, st);
+      select_assign_stage(prm, L_cal, p_all.data(), cap, sw.sel_stats, c.n_rows + (size_t)i * Hs,
+                          c.blk_t + (size_t)i * Hs * nb, c.blk_dst + (size_t)i * Hs * nb, st);
     }
-    hipLaunchKernelGGL(cal_cand_score_kernel, dim3(M, Hq), dim3(kCalThreads), 0, st, sw.tokrank, c.blk_t, c.abar,
-                       L_cal, b, nb, Hq, M, c.a_dev, c.n_dev);
+    hipLaunchKernelGGL(cal_cand_score_kernel, dim3(M, Hs), dim3(kCalThreads), 0, st, sw.tokrank, c.blk_t, c.abar,
+                       L_cal, b, nb, Hs, sel_group(prm), M, c.a_dev, c.n_dev);
     TCA_HIP_CHECK(hipGetLastError());
     TCA_HIP_CHECK(hipMemcpyAsync(a_host.data(), c.a_dev, a_host.size() * 8, hipMemcpyDeviceToHost, st));
     TCA_HIP_CHECK(hipMemcpyAsync(n_host.data(), c.n_dev, n_host.size() * 8, hipMemcpyDeviceToHost, st));
@@ -282,7 +286,7 @@ extern "C" int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, co
   TCA_HIP_CHECK(hipGetLastError());
 
   // Alg. 1 lines 6-8: the valid candidate with the fewest kept tokens (ties: lower index)
-  for (int h = 0; h < Hq; ++h) {
+  for (int h = 0; h < Hs; ++h) {
     int best = -1;
     for (int i = 0; i < M; ++i) {
       if (a_host[(size_t)h * M + i] >= tau &&

@@ -32,6 +32,9 @@ void psi_counts(int nk, int64_t m, const double* p, int64_t* c);
 inline double logit_scale(const tca_params* prm) {
   return prm->scale != 0.0 ? prm->scale : 1.0 / __builtin_sqrt((double)prm->head_dim);
 }
+// Selections kept per layer, and query heads served by each of them.
+inline int sel_heads(const tca_params* prm) { return prm->share == TCA_SHARE_GROUP ? prm->n_kv_heads : prm->n_q_heads; }
+inline int sel_group(const tca_params* prm) { return prm->share == TCA_SHARE_GROUP ? prm->n_q_heads / prm->n_kv_heads : 1; }
 inline size_t elem_bytes(const tca_params* prm) { return prm->dtype == TCA_BF16 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -5,17 +5,21 @@
 //   prep    : write the new K/V row into the ring; per head, count the global
 //             rows that have left the window (idx <= T-w; idx is ascending so
 //             this is a prefix).
-//   partial : split-K attention.  grid (slot, head, sequence); a slot is a chunk
-//             of kChunk rows of the head's global region or of the ring.  The
-//             256 threads form sixteen 16-lane groups, each streaming whole rows
-//             with 16-byte loads and keeping its own online softmax; groups are
-//             merged into one (max, sum, acc[D]) partial per slot.  HBM-bound:
-//             every K/V row is read once per query head.
+//   partial : split-K attention.  grid (slot, selection head, sequence); a slot is
+//             a chunk of kChunk rows of the head's global region or of the ring.
+//             The 256 threads form sixteen 16-lane groups, each streaming whole
+//             rows with 16-byte loads and keeping its own online softmax; groups
+//             are merged into one (max, sum, acc[D]) partial per slot and query
+//             head.  HBM-bound: every K/V row is read once per selection head -
+//             once per query head, or, when the group shares one selection, once
+//             per KV head with every row scored against the group's G queries.
 //   merge   : log-sum-exp merge of a head's partials -> O.  If the new token
 //             completes a block, the same workgroup scores the block's b rows
 //             with this step's query in fp64 (Eq. 5 restricted to the block),
 //             ranks them and appends the top t = floor(sum k p_k) to the head's
-//             global region in position order.
+//             global region in position order.  Shared selection: the group's
+//             first workgroup ranks by the sum over the group's heads of their
+//             block-normalised scores and appends once per KV head.
 //   advance : length += 1.
 #include <hip/hip_runtime.h>
 
@@ -34,7 +38,7 @@ struct DecodeHeads {
 };
 
 struct DecodeWs {
-  int32_t* n_vis;    // [B][Hq]
+  int32_t* n_vis;    // [B][Hs]
   float* part;       // [B][Hq][n_slots][D+2]
   size_t bytes;
 };
@@ -43,7 +47,7 @@ static DecodeWs carve_decode_ws(void* ws, int B, int Hq, int D, int n_slots) {
   DecodeWs w;
   char* base = (char*)ws;
   size_t off = 0;
-  w.n_vis = (int32_t*)(base + off); off = align_up(off + (size_t)B * Hq * sizeof(int32_t), 256);
+  w.n_vis = (int32_t*)(base + off); off = align_up(off + (size_t)B * Hq * sizeof(int32_t), 256);   // sized for Hs = Hq
   w.part = (float*)(base + off);    off = align_up(off + (size_t)B * Hq * n_slots * (D + 2) * sizeof(float), 256);
   w.bytes = off;
   return w;
@@ -63,7 +67,7 @@ __device__ __forceinline__ int count_le_dev(const int32_t* idx, int n, int64_t b
 
 // grid (B); block 256
 template <typename T>
-__global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hq, int Hkv, int D, int w,
+__global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv, int D, int w,
                                    const T* __restrict__ k_new, const T* __restrict__ v_new,
                                    int32_t* __restrict__ n_vis) {
   const int s = blockIdx.x;
@@ -77,34 +81,37 @@ __global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hq, int Hkv,
     rk[dst] = k_new[(size_t)s * Hkv * D + e];
     rv[dst] = v_new[(size_t)s * Hkv * D + e];
   }
-  for (int h = threadIdx.x; h < Hq; h += blockDim.x) {
+  for (int h = threadIdx.x; h < Hs; h += blockDim.x) {
     const int32_t* ix = c.idx + (size_t)s * c.cap_rows + dh.offs[h];
-    n_vis[s * Hq + h] = count_le_dev(ix, c.n_rows[s * Hq + h], Tpos - w);
+    n_vis[s * Hs + h] = count_le_dev(ix, c.n_rows[s * Hs + h], Tpos - w);
   }
 }
 
-// grid (n_slots, Hq, B); block 256
-template <typename T, int D>
+// grid (n_slots, Hs, B); block 256.  Selection head hs = blockIdx.y serves the GQ query
+// heads hs*GQ .. hs*GQ+GQ-1 (GQ = 1: one selection per query head).
+template <typename T, int D, int GQ>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
   constexpr int EL = D / 16;
-  __shared__ float red[kDecThreads / kWave][16][EL + 2];
+  constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
+  __shared__ float red[kDecThreads / kWave][16][GQ * PW];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int grp = tid >> 4, sub = tid & 15;           // 16 groups of 16 lanes
-  const int slot = blockIdx.x, h = blockIdx.y, s = blockIdx.z;
-  const int G = Hq / Hkv, kvh = h / G;
-  float* out = part + (((size_t)s * Hq + h) * n_slots + slot) * (D + 2);
+  const int slot = blockIdx.x, hs = blockIdx.y, s = blockIdx.z;
+  const int Hs = Hq / GQ, h0 = hs * GQ, kvh = h0 / (Hq / Hkv);
+  float* out = part + (((size_t)s * Hq + h0) * n_slots + slot) * (D + 2);   // head h0 + g: + g * n_slots * (D+2)
+  const size_t out_head = (size_t)n_slots * (D + 2);
   const int64_t Tpos = c.length[s];
 
   const T *kbase, *vbase;
   int r_begin, r_end;            // rows of this chunk, relative to kbase
   bool is_window = slot >= g_slots;
   if (!is_window) {
-    const int nv = n_vis[s * Hq + h];
+    const int nv = n_vis[s * Hs + hs];
     r_begin = slot * kChunk;
     r_end = min(nv, r_begin + kChunk);
-    const size_t base = (size_t)s * c.cap_rows + dh.offs[h];
+    const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
     kbase = (const T*)c.Kg + base * D;
     vbase = (const T*)c.Vg + base * D;
   } else {
@@ -115,18 +122,26 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     vbase = (const T*)c.ringV + base * D;
   }
   if (r_begin >= r_end) {
-    if (tid == 0) { out[0] = -INFINITY; out[1] = 0.f; }
+    if (tid < GQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
     return;
   }
 
-  float qv[EL];
-  load_slice<T, EL>(q + ((size_t)s * Hq + h) * D + sub * EL, qv);
+  float qv[GQ][EL];
 #pragma unroll
-  for (int e = 0; e < EL; ++e) qv[e] *= scale;
+  for (int g = 0; g < GQ; ++g) {
+    load_slice<T, EL>(q + ((size_t)s * Hq + h0 + g) * D + sub * EL, qv[g]);
+#pragma unroll
+    for (int e = 0; e < EL; ++e) qv[g][e] *= scale;
+  }
 
-  float m = -INFINITY, l = 0.f, acc[EL];
+  float m[GQ], l[GQ], acc[GQ][EL];
 #pragma unroll
-  for (int e = 0; e < EL; ++e) acc[e] = 0.f;
+  for (int g = 0; g < GQ; ++g) {
+    m[g] = -INFINITY;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[g][e] = 0.f;
+  }
 
   // kUnr rows per group are loaded (K and V) before any of them is used, so that
   // each lane keeps 2*kUnr 16-byte loads in flight
@@ -150,66 +165,75 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     }
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
-      float sc = 0.f;
-      if (ok[u]) {
 #pragma unroll
-        for (int e = 0; e < EL; ++e) sc = fmaf(qv[e], kv[u][e], sc);
-      }
-      sc = row16_sum(sc);
-      if (ok[u]) {
-        const float mn = fmaxf(m, sc);
-        const float corr = __expf(m - mn), pr = __expf(sc - mn);
-        l = l * corr + pr;
+      for (int g = 0; g < GQ; ++g) {
+        float sc = 0.f;
+        if (ok[u]) {
 #pragma unroll
-        for (int e = 0; e < EL; ++e) acc[e] = acc[e] * corr + pr * vv[u][e];
-        m = mn;
+          for (int e = 0; e < EL; ++e) sc = fmaf(qv[g][e], kv[u][e], sc);
+        }
+        sc = row16_sum(sc);
+        if (ok[u]) {
+          const float mn = fmaxf(m[g], sc);
+          const float corr = __expf(m[g] - mn), pr = __expf(sc - mn);
+          l[g] = l[g] * corr + pr;
+#pragma unroll
+          for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * corr + pr * vv[u][e];
+          m[g] = mn;
+        }
       }
     }
   }
   // merge the 4 groups of a wave, then the 4 waves through LDS
-  for (int o = 16; o < 64; o <<= 1) {
-    const float mo = __shfl_xor(m, o, kWave), lo = __shfl_xor(l, o, kWave);
-    const float mn = fmaxf(m, mo);
-    const float ca = (m == -INFINITY) ? 0.f : __expf(m - mn);
-    const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
-    l = l * ca + lo * cb;
 #pragma unroll
-    for (int e = 0; e < EL; ++e) acc[e] = acc[e] * ca + __shfl_xor(acc[e], o, kWave) * cb;
-    m = mn;
-  }
-  if (lane < 16) {
-    red[wv][lane][0] = m;
-    red[wv][lane][1] = l;
+  for (int g = 0; g < GQ; ++g) {
+    for (int o = 16; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
+      const float mn = fmaxf(m[g], mo);
+      const float ca = (m[g] == -INFINITY) ? 0.f : __expf(m[g] - mn);
+      const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
+      l[g] = l[g] * ca + lo * cb;
 #pragma unroll
-    for (int e = 0; e < EL; ++e) red[wv][lane][2 + e] = acc[e];
+      for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], o, kWave) * cb;
+      m[g] = mn;
+    }
+    if (lane < 16) {
+      red[wv][lane][g * PW] = m[g];
+      red[wv][lane][g * PW + 1] = l[g];
+#pragma unroll
+      for (int e = 0; e < EL; ++e) red[wv][lane][g * PW + 2 + e] = acc[g][e];
+    }
   }
   __syncthreads();
-  if (tid < 16) {
+  for (int pi = tid; pi < 16 * GQ; pi += kDecThreads) {
+    const int g = pi >> 4, ln = pi & 15;
     float M = -INFINITY;
-    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[x][tid][0]);
+    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[x][ln][g * PW]);
     float L = 0.f, a[EL];
 #pragma unroll
     for (int e = 0; e < EL; ++e) a[e] = 0.f;
     for (int x = 0; x < kDecThreads / kWave; ++x) {
-      const float mx = red[x][tid][0];
+      const float mx = red[x][ln][g * PW];
       const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
-      L += red[x][tid][1] * cf;
+      L += red[x][ln][g * PW + 1] * cf;
 #pragma unroll
-      for (int e = 0; e < EL; ++e) a[e] += red[x][tid][2 + e] * cf;
+      for (int e = 0; e < EL; ++e) a[e] += red[x][ln][g * PW + 2 + e] * cf;
     }
-    if (tid == 0) { out[0] = M; out[1] = L; }
+    float* og = out + g * out_head;
+    if (ln == 0) { og[0] = M; og[1] = L; }
 #pragma unroll
-    for (int e = 0; e < EL; ++e) out[2 + tid * EL + e] = a[e];
+    for (int e = 0; e < EL; ++e) og[2 + ln * EL + e] = a[e];
   }
 }
 
 // grid (Hq, B); block 256
 template <typename T, int D>
 __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
-    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int b, int n_slots, double scale,
+    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int GS, int w, int b, int n_slots, double scale,
     const T* __restrict__ q, const float* __restrict__ part, T* __restrict__ O) {
   constexpr int EL = D / 16;
   __shared__ double xs[256];
+  __shared__ double gred[kDecThreads / kWave];
   __shared__ int32_t sel[256];
   __shared__ int32_t wave_cnt[kDecThreads / kWave];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -262,27 +286,53 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   // block completed by this token?
   const int64_t Tpos = c.length[s];
   if ((Tpos + 1) % b != 0) return;
+  if (h % GS != 0) return;                             // one workgroup per selection head ranks the block
+  const int hs = h / GS, Hs = Hq / GS;
   const int64_t p0 = Tpos + 1 - b;                     // first position of the block
   const int slot0 = (int)(p0 % w);                     // contiguous in the ring: w is a multiple of b
   const T* kb = (const T*)c.ringK + (((size_t)s * Hkv + kvh) * w + slot0) * D;
   const T* vb = (const T*)c.ringV + (((size_t)s * Hkv + kvh) * w + slot0) * D;
   const int grp = tid >> 4, sub = tid & 15;
-  float qf[EL];
-  load_slice<T, EL>(q + ((size_t)s * Hq + h) * D + sub * EL, qf);
-  for (int r0 = 0; r0 < b; r0 += 16) {
-    const int r = r0 + grp;
-    double a = 0.0;
-    if (r < b) {
-      float kf[EL];
-      load_slice<T, EL>(kb + (size_t)r * D + sub * EL, kf);
+  // score of row i: the logit of the head's query, or, for a shared selection, the sum over the
+  // group's heads of exp(logit - log-sum-exp over the block) (G times the mean score)
+  double score = 0.0;
+  for (int g = 0; g < GS; ++g) {
+    float qf[EL];
+    load_slice<T, EL>(q + ((size_t)s * Hq + h + g) * D + sub * EL, qf);
+    __syncthreads();                                   // xs of the previous head has been consumed
+    for (int r0 = 0; r0 < b; r0 += 16) {
+      const int r = r0 + grp;
+      double a = 0.0;
+      if (r < b) {
+        float kf[EL];
+        load_slice<T, EL>(kb + (size_t)r * D + sub * EL, kf);
 #pragma unroll
-      for (int e = 0; e < EL; ++e) a = fma((double)kf[e], (double)qf[e], a);
+        for (int e = 0; e < EL; ++e) a = fma((double)kf[e], (double)qf[e], a);
+      }
+      a = group_sum(a, 16);
+      if (r < b && sub == 0) xs[r] = a * scale;
     }
-    a = group_sum(a, 16);
-    if (r < b && sub == 0) xs[r] = a * scale;
+    __syncthreads();
+    if (GS == 1) {
+      if (tid < b) score = xs[tid];
+    } else {
+      const double xi = tid < b ? xs[tid] : -INFINITY;
+      double mx = group_max(xi, kWave);
+      if (lane == 0) gred[wv] = mx;
+      __syncthreads();
+      mx = fmax(fmax(gred[0], gred[1]), fmax(gred[2], gred[3]));
+      __syncthreads();
+      const double e = tid < b ? exp(xi - mx) : 0.0;
+      const double zs = group_sum(e, kWave);
+      if (lane == 0) gred[wv] = zs;
+      __syncthreads();
+      score += e / ((gred[0] + gred[1]) + (gred[2] + gred[3]));
+    }
   }
   __syncthreads();
-  const int t = dh.t_dec[h];
+  if (tid < b) xs[tid] = score;
+  __syncthreads();
+  const int t = dh.t_dec[hs];
   bool keep = false;
   if (tid < b) {
     const double xi = xs[tid];
@@ -300,9 +350,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   for (int x = 0; x < wv; ++x) before += wave_cnt[x];
   if (keep) sel[before] = tid;
   __syncthreads();
-  const int64_t cap = dh.offs[h + 1] - dh.offs[h];
-  const int32_t fill = c.n_rows[s * Hq + h];
-  const size_t base = (size_t)s * c.cap_rows + dh.offs[h];
+  const int64_t cap = dh.offs[hs + 1] - dh.offs[hs];
+  const int32_t fill = c.n_rows[s * Hs + hs];
+  const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
   T* Kg = (T*)c.Kg;
   T* Vg = (T*)c.Vg;
   for (int k = grp; k < t; k += 16) {
@@ -318,7 +368,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   __syncthreads();
   if (tid == 0) {
     int64_t nf = (int64_t)fill + t;
-    c.n_rows[s * Hq + h] = (int32_t)(nf > cap ? cap : nf);
+    c.n_rows[s * Hs + hs] = (int32_t)(nf > cap ? cap : nf);
   }
 }
 
@@ -358,13 +408,23 @@ template <typename T, int D>
 static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHeads& dh, int64_t max_rows,
                       const T* q, const T* k_new, const T* v_new, T* O, void* ws, hipStream_t st) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, B = c->batch, w = prm->window;
+  const int Hs = sel_heads(prm), GS = sel_group(prm);
   const int g_slots = global_slots(max_rows), n_slots = g_slots + window_slots(w);
   DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
-  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B), dim3(256), 0, st, *c, dh, Hq, Hkv, D, w, k_new, v_new,
+  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new, v_new,
                      dw.n_vis);
-  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(n_slots, Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq,
-                     Hkv, w, g_slots, n_slots, (float)logit_scale(prm), q, dw.n_vis, dw.part);
-  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq, Hkv, w,
+  const float sc = (float)logit_scale(prm);
+#define TCA_PARTIAL_CASE(GG)                                                                                \
+  case GG:                                                                                                  \
+    hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st, *c, \
+                       dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                         \
+    break;
+  switch (GS) {
+    TCA_PARTIAL_CASE(1) TCA_PARTIAL_CASE(2) TCA_PARTIAL_CASE(3) TCA_PARTIAL_CASE(4)
+    TCA_PARTIAL_CASE(5) TCA_PARTIAL_CASE(6) TCA_PARTIAL_CASE(7) TCA_PARTIAL_CASE(8)
+  }
+#undef TCA_PARTIAL_CASE
+  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq, Hkv, GS, w,
                      prm->block, n_slots, logit_scale(prm), q, dw.part, O);
   hipLaunchKernelGGL(decode_advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, c->length, B);
   return TCA_OK;
@@ -412,12 +472,12 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
   if (rc) return rc;
   if (!offs || !q || !k_new || !v_new || !p || !O || !ws)
     return fail(TCA_ERR_INVALID, "tca_decode: NULL pointer argument");
-  const int Hq = prm->n_q_heads, b = prm->block, nk = block_log2(b) + 1;
-  if (offs[0] != 0 || offs[Hq] != cache->cap_rows)
-    return fail(TCA_ERR_INVALID, "tca_decode: offs[0] must be 0 and offs[Hq] must equal cap_rows");
+  const int Hs = sel_heads(prm), b = prm->block, nk = block_log2(b) + 1;
+  if (offs[0] != 0 || offs[Hs] != cache->cap_rows)
+    return fail(TCA_ERR_INVALID, "tca_decode: offs[0] must be 0 and offs[Hs] must equal cap_rows");
   DecodeHeads dh;
   int64_t max_rows = 0;
-  for (int h = 0; h < Hq; ++h) {
+  for (int h = 0; h < Hs; ++h) {
     if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_decode: offs not ascending at %d", h);
     if (offs[h + 1] - offs[h] > INT32_MAX) return fail(TCA_ERR_UNSUPPORTED, "head region beyond int32 rows");
     if (offs[h + 1] - offs[h] > max_rows) max_rows = offs[h + 1] - offs[h];
@@ -426,7 +486,7 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
     dh.offs[h] = offs[h];
     dh.t_dec[h] = tca_decode_budget(b, p + (size_t)h * nk);
   }
-  dh.offs[Hq] = offs[Hq];
+  dh.offs[Hs] = offs[Hs];
   if (global_slots(max_rows) + window_slots(prm->window) > kMaxSlots)
     return fail(TCA_ERR_UNSUPPORTED, "tca_decode: more than %d split-K slots per head", kMaxSlots);
   const size_t need = tca_decode_workspace_bytes(prm, cache->batch, max_rows);

@@ -56,6 +56,8 @@ int check_params(const tca_params* prm) {
     return fail(TCA_ERR_INVALID, "scale=%g must be finite and >= 0", prm->scale);
   if (prm->metric != TCA_METRIC_HHI && prm->metric != TCA_METRIC_ENTROPY)
     return fail(TCA_ERR_UNSUPPORTED, "metric=%d", prm->metric);
+  if (prm->share != TCA_SHARE_HEAD && prm->share != TCA_SHARE_GROUP)
+    return fail(TCA_ERR_UNSUPPORTED, "share=%d", prm->share);
   return TCA_OK;
 }
 
@@ -107,6 +109,12 @@ void psi_counts(int nk, int64_t m, const double* p, int64_t* c) {
 using namespace tca;
 
 extern "C" {
+
+int tca_selection_heads(const tca_params* prm) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  return sel_heads(prm);
+}
 
 int tca_num_counts(int b) {
   int l = block_log2(b);
@@ -166,7 +174,7 @@ int64_t tca_select_rows(const tca_params* prm, int64_t n_blocks, const double* p
   if (!p || n_blocks < 0) return fail(TCA_ERR_INVALID, "bad select_rows arguments");
   int nk = block_log2(prm->block) + 1;
   int64_t total = 0;
-  for (int h = 0; h < prm->n_q_heads; ++h) {
+  for (int h = 0; h < sel_heads(prm); ++h) {
     const double* ph = p + (size_t)h * nk;
     if (!valid_config(ph, nk)) return fail(TCA_ERR_INVALID, "p[%d] is not a distribution", h);
     int64_t c[TCA_MAX_COUNTS];

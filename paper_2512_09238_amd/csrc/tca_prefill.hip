@@ -26,9 +26,9 @@ extern "C" int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0,
                 (long long)q_pos0, (long long)n_queries, (long long)kv_stride);
   if (q_pos0 + n_queries > INT32_MAX) return fail(TCA_ERR_UNSUPPORTED, "positions beyond int32");
   if (offs[0] != 0) return fail(TCA_ERR_INVALID, "tca_prefill: offs[0] must be 0");
-  for (int h = 0; h < prm->n_q_heads; ++h)
+  for (int h = 0; h < sel_heads(prm); ++h)
     if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_prefill: offs not ascending at %d", h);
-  const size_t need = tca_prefill_workspace_bytes(prm, n_queries, offs[prm->n_q_heads]);
+  const size_t need = tca_prefill_workspace_bytes(prm, n_queries, offs[sel_heads(prm)]);
   if (need && (!ws || ws_bytes < need || ((uintptr_t)ws & 255)))
     return fail(TCA_ERR_WORKSPACE, "tca_prefill: workspace needs %zu bytes, 256-byte aligned", need);
   if (n_queries == 0) return TCA_OK;

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(
     const uint16_t* __restrict__ src, int64_t group_stride_rows, const int32_t* group_valid,
     int64_t valid_all, int64_t first_row, uint16_t* __restrict__ dst, int tiles_per_group,
     PrefillHeads ph, int mode, unsigned long long* clk) {
-  // mode 0: global regions (group = query head; rows from ph.offs, valid rows from group_valid)
+  // mode 0: global regions (group = selection head; rows from ph.offs, valid rows from group_valid)
   // mode 1: dense K/V (group = KV head; absolute rows first_row + 64*tile, valid while < valid_all)
   __shared__ uint16_t tile[kBN][D + 8];
   const int g = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
-    int64_t dense_tile0, int dense_tiles, PrefillHeads ph, int Hq, int G, int w, float scale,
+    int64_t dense_tile0, int dense_tiles, PrefillHeads ph, int Hq, int G, int GS, int w, float scale,
     uint16_t* __restrict__ O, float* __restrict__ lse, unsigned long long* __restrict__ clk) {
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
@@ -210,8 +210,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const float sl2e = scale * 1.4426950408889634f;
 
   // ---- per-lane query state (lane column c = one query)
-  const int64_t base = ph.offs[h];
-  const int nr = n_rows[h];
+  const int hs = h / GS;                           // the selection this query head reads (GS query heads share it)
+  const int64_t base = ph.offs[hs];
+  const int nr = n_rows[hs];
   int64_t qrow_i = r0 + wv * 32 + c;
   if (qrow_i > last_row) qrow_i = last_row;         // clamped rows compute a duplicate; never stored
   const int qpos = (int)(q_pos0 + qrow_i);
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const __amdgpu_buffer_rsrc_t krs_d = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(K + (size_t)kvh * kv_stride * D), 0, (last_pos + 1) * (D * 2), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t vrs_g = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(Vgt + (size_t)ph.tile_off[h] * (D * kBN)), 0, n_gt * VBYTES, kRsrcFlags);
+      (void*)(Vgt + (size_t)ph.tile_off[hs] * (D * kBN)), 0, n_gt * VBYTES, kRsrcFlags);
   const __amdgpu_buffer_rsrc_t vrs_d = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(Vt + (size_t)kvh * dense_tiles * (D * kBN)), 0, dense_tiles * VBYTES, kRsrcFlags);
   const int vdshift = dshift - (int)dense_tile0;   // tile t >= n_gt is tile t + vdshift of the dense V^T buffer
@@ -487,7 +488,7 @@ static MfmaWs carve_mfma_ws(void* ws, const tca_params* prm, int64_t g_tiles, in
 }
 
 size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows) {
-  return carve_mfma_ws(nullptr, prm, max_region_tiles(prm->n_q_heads, cap_rows),
+  return carve_mfma_ws(nullptr, prm, max_region_tiles(sel_heads(prm), cap_rows),
                        max_dense_tiles(n_queries, prm->window)).bytes;
 }
 
@@ -496,26 +497,26 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
                      const uint16_t* K, const uint16_t* V, int64_t kv_stride, const int32_t* idx,
                      const uint16_t* Kg, const uint16_t* Vg, const int64_t* offs, const int32_t* n_rows,
                      uint16_t* O, float* lse, void* ws, hipStream_t st) {
-  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, w = prm->window;
+  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, Hs = sel_heads(prm), w = prm->window;
   PrefillHeads ph;
   int32_t run = 0;
   int max_tiles = 0;
-  for (int h = 0; h < Hq; ++h) {
+  for (int h = 0; h < Hs; ++h) {
     ph.offs[h] = offs[h];
     ph.tile_off[h] = run;
     const int nt = (int)((offs[h + 1] - offs[h] + kBN - 1) / kBN);
     run += nt;
     if (nt > max_tiles) max_tiles = nt;
   }
-  ph.offs[Hq] = offs[Hq];
-  ph.tile_off[Hq] = run;
+  ph.offs[Hs] = offs[Hs];
+  ph.tile_off[Hs] = run;
   const int64_t win_lo = q_pos0 - w + 1 > 0 ? q_pos0 - w + 1 : 0;
   const int64_t dt0 = win_lo / kBN, dt1 = (q_pos0 + n_queries - 1) / kBN;
   const int d_tiles = (int)(dt1 - dt0 + 1);
-  MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hq, offs[Hq]), max_dense_tiles(n_queries, w));
+  MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hs, offs[Hs]), max_dense_tiles(n_queries, w));
 
   if (max_tiles > 0)
-    hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hq), dim3(256), 0, st, Vg, (int64_t)0,
+    hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, Vg, (int64_t)0,
                        n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr);
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
                      (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, mw.clk);
@@ -529,7 +530,7 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
     const int n_qt = (int)((n_queries + NW * 32 - 1) / (NW * 32));
     hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
-                       Hq / Hkv, w, (float)logit_scale(prm), O, lse, mw.clk);
+                       Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, mw.clk);
   };
   if (((n_queries + 255) / 256) * Hq >= 1024) launch(std::integral_constant<int, 8>{});
   else launch(std::integral_constant<int, 4>{});
@@ -542,7 +543,7 @@ int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, 
   // the kernel addresses tiles with 32-bit byte offsets inside each buffer
   const int64_t row_bytes = (int64_t)prm->head_dim * 2;
   int64_t max_rows = q_pos0 + n_queries + prm->window + 2 * kBN;
-  for (int h = 0; h < prm->n_q_heads; ++h)
+  for (int h = 0; h < sel_heads(prm); ++h)
     if (offs[h + 1] - offs[h] + kBN > max_rows) max_rows = offs[h + 1] - offs[h] + kBN;
   if (max_rows * row_bytes > (int64_t)INT32_MAX)
     return fail(TCA_ERR_UNSUPPORTED, "tca_prefill (bf16): %lld rows of %lld bytes exceed 2 GiB per head buffer",

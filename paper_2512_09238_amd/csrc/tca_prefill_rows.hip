@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     const T* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const T* __restrict__ K,
     const T* __restrict__ V, int64_t kv_stride, const int32_t* __restrict__ idx,
     const T* __restrict__ Kg, const T* __restrict__ Vg, HeadOffs ho,
-    const int32_t* __restrict__ n_rows, int G, int w, float scale, T* __restrict__ O,
+    const int32_t* __restrict__ n_rows, int G, int GS, int w, float scale, T* __restrict__ O,
     float* __restrict__ lse) {
   constexpr int EL = D / 16;                       // elements of a row per lane
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -46,8 +46,9 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
 #pragma unroll
   for (int e = 0; e < EL; ++e) q[e] = load_f32(Q + ((size_t)h * n_queries + r) * D + sub * EL + e) * scale;
 
-  const int64_t base = ho.offs[h];
-  const int n_glob = count_le(idx + base, n_rows[h], i - w);
+  const int hs = h / GS;                           // the selection this query head reads
+  const int64_t base = ho.offs[hs];
+  const int n_glob = count_le(idx + base, n_rows[hs], i - w);
   const int64_t win0 = i - w + 1 > 0 ? i - w + 1 : 0;
   const int64_t n_keys = n_glob + (i - win0 + 1);
 
@@ -108,16 +109,17 @@ int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64
                         const T* V, int64_t kv_stride, const int32_t* idx, const T* Kg, const T* Vg,
                         const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st) {
   HeadOffs ho;
-  for (int h = 0; h <= prm->n_q_heads; ++h) ho.offs[h] = offs[h];
+  for (int h = 0; h <= sel_heads(prm); ++h) ho.offs[h] = offs[h];
+  const int GS = sel_group(prm);
   const int G = prm->n_q_heads / prm->n_kv_heads;
   dim3 grid((unsigned)((n_queries + 3) / 4), prm->n_q_heads);
   const float scale = (float)logit_scale(prm);
   if (prm->head_dim == 128)
     hipLaunchKernelGGL((prefill_rows_kernel<T, 128>), grid, dim3(kRowThreads), 0, st, Q, q_pos0, n_queries,
-                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, prm->window, scale, O, lse);
+                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse);
   else
     hipLaunchKernelGGL((prefill_rows_kernel<T, 64>), grid, dim3(kRowThreads), 0, st, Q, q_pos0, n_queries,
-                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, prm->window, scale, O, lse);
+                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse);
   return TCA_OK;
 }
 

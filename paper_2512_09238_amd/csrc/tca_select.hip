@@ -19,6 +19,12 @@
 //                   counting over their keys (skipped when t_j = b), keeps those
 //                   with rank < t_j in position order and copies their K/V rows
 //                   and positions into the head's flat region (App. C).
+// When the query heads of a group share one selection (an extension for GQA), the
+// scores of the group's heads have to be normalised before they can be averaged:
+// score_kernel then leaves the fp64 logits in the workspace, group_lse_kernel turns
+// the per-head block statistics into each head's normaliser, and group_score_kernel
+// merges the G logits of a token into one log-domain score and produces the block
+// statistics and ranking keys of that score; assign and gather run once per KV head.
 #include <hip/hip_runtime.h>
 
 #include "tca_common.h"
@@ -34,16 +40,28 @@ constexpr int kGatherRows = 2;        // rows per thread in flight in the copy l
 constexpr int kHeadsPerLaunch = 32;
 constexpr int kBlockStats = 4;        // doubles per (head, block) in SelectWs::stats
 
-SelectWs carve_select_ws(void* ws, int Hq, int b, int64_t n_tokens) {
+// the group's query heads are merged into one score only when there is more than one of them
+static bool grouped(const tca_params* prm) { return sel_group(prm) > 1; }
+
+SelectWs carve_select_ws(void* ws, const tca_params* prm, int64_t n_tokens) {
+  const int Hq = prm->n_q_heads, Hs = sel_heads(prm), b = prm->block;
   int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
   size_t off = 0;
   SelectWs w;
   char* base = (char*)ws;
-  w.tokrank = (uint8_t*)(base + off); off = align_up(off + (size_t)Hq * nb * b, 256);
-  w.keys = (uint64_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * b * sizeof(uint64_t), 256);
+  w.tokrank = (uint8_t*)(base + off); off = align_up(off + (size_t)Hs * nb * b, 256);
+  w.keys = (uint64_t*)(base + off);   off = align_up(off + (size_t)Hs * nb * b * sizeof(uint64_t), 256);
   w.stats = (double*)(base + off);    off = align_up(off + (size_t)Hq * nbt * kBlockStats * sizeof(double), 256);
-  w.blk_t = (int32_t*)(base + off);   off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
-  w.blk_dst = (int32_t*)(base + off); off = align_up(off + (size_t)Hq * nb * sizeof(int32_t), 256);
+  w.sel_stats = w.stats;
+  w.xlog = nullptr;
+  w.lse = nullptr;
+  if (grouped(prm)) {
+    w.sel_stats = (double*)(base + off); off = align_up(off + (size_t)Hs * nbt * kBlockStats * sizeof(double), 256);
+    w.xlog = (double*)(base + off);      off = align_up(off + (size_t)Hq * nbt * b * sizeof(double), 256);
+    w.lse = (double*)(base + off);       off = align_up(off + (size_t)Hq * sizeof(double), 256);
+  }
+  w.blk_t = (int32_t*)(base + off);   off = align_up(off + (size_t)Hs * nb * sizeof(int32_t), 256);
+  w.blk_dst = (int32_t*)(base + off); off = align_up(off + (size_t)Hs * nb * sizeof(int32_t), 256);
   w.bytes = off;
   return w;
 }
@@ -67,13 +85,27 @@ __device__ __forceinline__ int count_greater(const uint64_t* keys, int o_begin, 
   return cnt;
 }
 
+// What score_kernel leaves behind besides the block statistics.
+constexpr int kEmitKeys = 0;      // ranking keys (selection)
+constexpr int kEmitRanks = 1;     // in-block ranks (calibration: reused by every candidate)
+constexpr int kEmitLogits = 2;    // the fp64 logits, tail block included (shared selection: merged by group_score_kernel)
+
+// Key that orders the tokens of a block: the ordered image of the score with its 8
+// lowest mantissa bits replaced by 255 - position, so that one unsigned compare
+// decides "higher score, or the same score at a lower position".  Scores that agree
+// in all but those bits (relative distance below 2^-44) count as tied.
+__device__ __forceinline__ uint64_t ranking_key(double x, int i) {
+  return (ordered_key(x) & ~0xFFull) | (uint64_t)(255 - i);
+}
+
 // grid (nbt, Hkv); block 256.  T storage type, D head dim, G query heads per KV head.
-// RANK: also rank inside the block and write tokrank (calibration); otherwise only keys_out is written.
-template <typename T, int D, int G, bool RANK>
+template <typename T, int D, int G, int EMIT>
 __global__ __launch_bounds__(kScoreThreads) void score_kernel(
     const T* __restrict__ K, const T* __restrict__ q_last, int64_t kv_stride, int64_t pos0,
     int64_t n_tokens, int b, int64_t n_blocks, int64_t nbt, int Hq, double scale,
-    uint8_t* __restrict__ tokrank, uint64_t* __restrict__ keys_out, double* __restrict__ stats) {
+    uint8_t* __restrict__ tokrank, uint64_t* __restrict__ keys_out, double* __restrict__ stats,
+    double* __restrict__ xlog) {
+  constexpr bool RANK = EMIT == kEmitRanks;
   constexpr int EPL = Vec16<T>::N;            // elements per lane per load
   constexpr int LPR = D / EPL;                // lanes per row
   constexpr int RPW = kWave / LPR;            // rows per wave per load
@@ -156,16 +188,20 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
       st[0] = mx; st[1] = e1; st[2] = e2; st[3] = e3;
     }
   }
+  if constexpr (EMIT == kEmitLogits) {
+    for (int pi = tid; pi < G * b; pi += kScoreThreads) {
+      const int g = pi / b, i = pi - g * b;
+      xlog[((size_t)(kvh * G + g) * nbt + j) * b + i] = xs[g][i];          // -inf past the end of the tail
+    }
+    return;
+  }
   if (j >= n_blocks) return;             // the tail block only feeds the normaliser
 
   // Rank inside the block = number of tokens that beat token i (higher logit, or
-  // the same logit at a lower position).  Both conditions are folded into one
-  // 64-bit key: the ordered image of the logit with its 8 lowest mantissa bits
-  // replaced by 255 - position, so one unsigned compare decides a pair.  Logits
-  // that agree in all but those bits (relative distance below 2^-44) count as tied.
+  // the same logit at a lower position): one unsigned compare of ranking keys per pair.
   for (int pi = tid; pi < G * b; pi += kScoreThreads) {
     const int g = pi / b, i = pi - g * b;
-    const uint64_t key = (ordered_key(xs[g][i]) & ~0xFFull) | (uint64_t)(255 - i);
+    const uint64_t key = ranking_key(xs[g][i], i);
     if constexpr (RANK) keys[g][i] = key;
     else keys_out[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = key;
   }
@@ -175,6 +211,88 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(
       const int g = pi / b, i = pi - g * b;
       tokrank[(size_t)(kvh * G + g) * (n_blocks * b) + j * b + i] = (uint8_t)count_greater(keys[g], 0, b, keys[g][i]);
     }
+  }
+}
+
+// ----------------------------------------------------------- group score --
+// Shared selection: the score of a token is the mean over the group's query heads of their
+// Eq. 5 scores, sbar_i = (1/G) sum_g exp(x_gi - lse_g).  It is carried in the log domain,
+// y_i = ln sum_g exp(x_gi - lse_g) = ln(G sbar_i), so that the block statistics, ranking keys,
+// Eq. 6 and Eq. 7 of the per-head path apply to y unchanged (the factor G cancels in the
+// normalised block mass and in both concentration indices).
+
+// grid (Hq); block 256.  lse[h] = ln sum_i e^{x_hi} from the block statistics (tail included).
+__global__ __launch_bounds__(256) void group_lse_kernel(const double* __restrict__ stats, int nbt,
+                                                        double* __restrict__ lse) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const double* st = stats + (size_t)blockIdx.x * nbt * kBlockStats;
+  double mx = -INFINITY;
+  for (int j = tid; j < nbt; j += 256) mx = fmax(mx, st[(size_t)j * kBlockStats]);
+  mx = group_max(mx, kWave);
+  if (lane == 0) red[wv] = mx;
+  __syncthreads();
+  mx = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+  __syncthreads();
+  double z = 0.0;
+  for (int j = tid; j < nbt; j += 256) z += st[(size_t)j * kBlockStats + 1] * exp(st[(size_t)j * kBlockStats] - mx);
+  z = group_sum(z, kWave);
+  if (lane == 0) red[wv] = z;
+  __syncthreads();
+  if (tid == 0) lse[blockIdx.x] = mx + log((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+// grid (nbt, Hkv); block 256: thread i owns token i of the block.
+template <int G, bool RANK>
+__global__ __launch_bounds__(256) void group_score_kernel(
+    const double* __restrict__ xlog, const double* __restrict__ lse, int b, int64_t n_blocks, int64_t nbt,
+    uint8_t* __restrict__ tokrank, uint64_t* __restrict__ keys_out, double* __restrict__ gstats) {
+  __shared__ double red[4][3];
+  __shared__ __attribute__((aligned(16))) uint64_t keys[256];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t j = blockIdx.x;
+  const int kvh = blockIdx.y;
+  double y = -INFINITY;
+  if (tid < b) {
+    double a[G], top = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      a[g] = xlog[((size_t)(kvh * G + g) * nbt + j) * b + tid] - lse[kvh * G + g];
+      top = fmax(top, a[g]);
+    }
+    if (top > -INFINITY) {                                 // a token past the end of the tail stays at -inf
+      double sum = 0.0;
+#pragma unroll
+      for (int g = 0; g < G; ++g) sum += exp(a[g] - top);
+      y = top + log(sum);
+    }
+  }
+  double mx = group_max(y, kWave);
+  if (lane == 0) red[wv][0] = mx;
+  __syncthreads();
+  mx = fmax(fmax(red[0][0], red[1][0]), fmax(red[2][0], red[3][0]));
+  __syncthreads();
+  const double dx = y - mx;
+  const double e = y > -INFINITY ? exp(dx) : 0.0;
+  const double e1 = group_sum(e, kWave), e2 = group_sum(e * e, kWave);
+  const double e3 = group_sum(e > 0.0 ? e * dx : 0.0, kWave);
+  if (lane == 0) { red[wv][0] = e1; red[wv][1] = e2; red[wv][2] = e3; }
+  __syncthreads();
+  if (tid == 0) {
+    double* st = gstats + ((size_t)kvh * nbt + j) * kBlockStats;
+    st[0] = mx;
+    st[1] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
+    st[2] = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
+    st[3] = (red[0][2] + red[1][2]) + (red[2][2] + red[3][2]);
+  }
+  if (j >= n_blocks) return;
+  const uint64_t key = ranking_key(y, tid);
+  if constexpr (RANK) {
+    if (tid < b) keys[tid] = key;
+    __syncthreads();
+    if (tid < b) tokrank[(size_t)kvh * (n_blocks * b) + j * b + tid] = (uint8_t)count_greater(keys, 0, b, key);
+  } else {
+    if (tid < b) keys_out[(size_t)kvh * (n_blocks * b) + j * b + tid] = key;
   }
 }
 
@@ -333,7 +451,7 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
 // offsets of the heads' regions travel in the kernel's argument block: no copy, no extra launch
 struct OffsArgs { int64_t offs[TCA_MAX_HEADS + 1]; };
 
-// grid (n_blocks, Hq); block 256.
+// grid (n_blocks, selection heads); block 256.  G: selection heads per KV head.
 template <typename T, int D>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const T* __restrict__ K, const T* __restrict__ V, int64_t kv_stride, int64_t pos0, int b,
@@ -412,14 +530,15 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
 }
 
-template <typename T, int D, bool RANK>
+template <typename T, int D, int EMIT>
 static void launch_score(int G, dim3 grid, hipStream_t st, const T* K, const T* q, int64_t kv_stride,
                          int64_t pos0, int64_t n_tokens, int b, int64_t nb, int64_t nbt, int Hq,
-                         double scale, uint8_t* tokrank, uint64_t* keys, double* stats) {
+                         double scale, const SelectWs& w) {
 #define TCA_SCORE_CASE(GG)                                                                           \
   case GG:                                                                                           \
-    hipLaunchKernelGGL((score_kernel<T, D, GG, RANK>), grid, dim3(kScoreThreads), 0, st, K, q,       \
-                       kv_stride, pos0, n_tokens, b, nb, nbt, Hq, scale, tokrank, keys, stats);      \
+    hipLaunchKernelGGL((score_kernel<T, D, GG, EMIT>), grid, dim3(kScoreThreads), 0, st, K, q,       \
+                       kv_stride, pos0, n_tokens, b, nb, nbt, Hq, scale, w.tokrank, w.keys, w.stats, \
+                       w.xlog);                                                                      \
     break;
   switch (G) {
     TCA_SCORE_CASE(1) TCA_SCORE_CASE(2) TCA_SCORE_CASE(3) TCA_SCORE_CASE(4)
@@ -428,34 +547,65 @@ static void launch_score(int G, dim3 grid, hipStream_t st, const T* K, const T* 
 #undef TCA_SCORE_CASE
 }
 
-// Stage 1 of selection for callers outside this file (calibration): logits, block
-// statistics and in-block ranks of tokens [0, n_tokens) of K scored by q_last.
-void select_score_stage(const tca_params* prm, const void* q_last, const void* K, int64_t kv_stride,
+template <bool RANK>
+static void launch_group_score(int G, int Hq, int Hkv, int b, int64_t nb, int64_t nbt, const SelectWs& w,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(group_lse_kernel, dim3(Hq), dim3(256), 0, st, w.stats, (int)nbt, w.lse);
+  const dim3 grid((unsigned)nbt, Hkv);
+#define TCA_GROUP_CASE(GG)                                                                              \
+  case GG:                                                                                              \
+    hipLaunchKernelGGL((group_score_kernel<GG, RANK>), grid, dim3(256), 0, st, w.xlog, w.lse, b, nb, nbt, \
+                       w.tokrank, w.keys, w.sel_stats);                                                 \
+    break;
+  switch (G) {
+    TCA_GROUP_CASE(2) TCA_GROUP_CASE(3) TCA_GROUP_CASE(4) TCA_GROUP_CASE(5)
+    TCA_GROUP_CASE(6) TCA_GROUP_CASE(7) TCA_GROUP_CASE(8)
+  }
+#undef TCA_GROUP_CASE
+}
+
+// Scores tokens [pos0, pos0 + n_tokens) for every selection head: block statistics in
+// w.sel_stats, and in-block ranks in w.tokrank (RANK) or ranking keys in w.keys.
+template <typename T, int D, bool RANK>
+static void score_stage(const tca_params* prm, const T* q_last, const T* K, int64_t kv_stride, int64_t pos0,
                         int64_t n_tokens, const SelectWs& w, hipStream_t st) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
   const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
   const dim3 grid((unsigned)nbt, Hkv);
   const double sc = logit_scale(prm);
-  if (prm->dtype == TCA_BF16) {
-    using T = bf16_t;
-    if (prm->head_dim == 128) launch_score<T, 128, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
-    else launch_score<T, 64, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
+  if (grouped(prm)) {
+    launch_score<T, D, kEmitLogits>(G, grid, st, K, q_last, kv_stride, pos0, n_tokens, b, nb, nbt, Hq, sc, w);
+    launch_group_score<RANK>(G, Hq, Hkv, b, nb, nbt, w, st);
   } else {
-    using T = float;
-    if (prm->head_dim == 128) launch_score<T, 128, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
-    else launch_score<T, 64, true>(G, grid, st, (const T*)K, (const T*)q_last, kv_stride, 0, n_tokens, b, nb, nbt, Hq, sc, w.tokrank, w.keys, w.stats);
+    launch_score<T, D, RANK ? kEmitRanks : kEmitKeys>(G, grid, st, K, q_last, kv_stride, pos0, n_tokens, b, nb,
+                                                      nbt, Hq, sc, w);
   }
 }
 
-// Stage 2: block metric, ranking and budgets for one configuration per head.
-// blk_t / blk_dst: [Hq][nb]; n_rows: [Hq] fill counters (in/out); cap: per-head capacity.
+// Stage 1 of selection for callers outside this file (calibration): block statistics
+// and in-block ranks of tokens [0, n_tokens) of K scored by q_last.
+void select_score_stage(const tca_params* prm, const void* q_last, const void* K, int64_t kv_stride,
+                        int64_t n_tokens, const SelectWs& w, hipStream_t st) {
+  if (prm->dtype == TCA_BF16) {
+    using T = bf16_t;
+    if (prm->head_dim == 128) score_stage<T, 128, true>(prm, (const T*)q_last, (const T*)K, kv_stride, 0, n_tokens, w, st);
+    else score_stage<T, 64, true>(prm, (const T*)q_last, (const T*)K, kv_stride, 0, n_tokens, w, st);
+  } else {
+    using T = float;
+    if (prm->head_dim == 128) score_stage<T, 128, true>(prm, (const T*)q_last, (const T*)K, kv_stride, 0, n_tokens, w, st);
+    else score_stage<T, 64, true>(prm, (const T*)q_last, (const T*)K, kv_stride, 0, n_tokens, w, st);
+  }
+}
+
+// Stage 2: block metric, ranking and budgets for one configuration per selection head.
+// blk_t / blk_dst: [Hs][nb]; n_rows: [Hs] fill counters (in/out); cap: per-head capacity.
 void select_assign_stage(const tca_params* prm, int64_t n_tokens, const double* p, const int64_t* cap,
                          const double* stats, int32_t* n_rows, int32_t* blk_t, int32_t* blk_dst,
                          hipStream_t st) {
-  const int Hq = prm->n_q_heads, b = prm->block, nk = block_log2(b) + 1;
+  const int Hs = sel_heads(prm), b = prm->block, nk = block_log2(b) + 1;
   const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
-  for (int h0 = 0; h0 < Hq; h0 += kHeadsPerLaunch) {
-    const int nh = Hq - h0 < kHeadsPerLaunch ? Hq - h0 : kHeadsPerLaunch;
+  for (int h0 = 0; h0 < Hs; h0 += kHeadsPerLaunch) {
+    const int nh = Hs - h0 < kHeadsPerLaunch ? Hs - h0 : kHeadsPerLaunch;
     AssignArgs aa;
     for (int hl = 0; hl < nh; ++hl) {
       int64_t c[TCA_MAX_COUNTS];
@@ -474,21 +624,20 @@ static int run_select(const tca_params* prm, const T* q_last, const T* K, const 
                       int64_t kv_stride, int64_t pos0, int64_t n_tokens, const double* p,
                       const int64_t* offs, int32_t* n_rows, int32_t* idx, T* Kg, T* Vg, void* ws,
                       hipStream_t st) {
-  const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, G = Hq / Hkv, b = prm->block;
-  const int64_t nb = n_tokens / b, nbt = (n_tokens + b - 1) / b;
-  SelectWs w = carve_select_ws(ws, Hq, b, n_tokens);
+  const int Hs = sel_heads(prm), Hkv = prm->n_kv_heads, b = prm->block;
+  const int64_t nb = n_tokens / b;
+  SelectWs w = carve_select_ws(ws, prm, n_tokens);
   OffsArgs oa;
-  for (int h = 0; h <= Hq; ++h) oa.offs[h] = offs[h];
+  for (int h = 0; h <= Hs; ++h) oa.offs[h] = offs[h];
 
-  launch_score<T, D, false>(G, dim3((unsigned)nbt, Hkv), st, K, q_last, kv_stride, pos0, n_tokens, b, nb, nbt,
-                            Hq, logit_scale(prm), w.tokrank, w.keys, w.stats);
+  score_stage<T, D, false>(prm, q_last, K, kv_stride, pos0, n_tokens, w, st);
   if (nb == 0) return TCA_OK;
 
   int64_t cap[TCA_MAX_HEADS];
-  for (int h = 0; h < Hq; ++h) cap[h] = offs[h + 1] - offs[h];
-  select_assign_stage(prm, n_tokens, p, cap, w.stats, n_rows, w.blk_t, w.blk_dst, st);
-  hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hq), dim3(kGatherThreads), 0, st, K, V,
-                     kv_stride, pos0, b, nb, G, w.keys, w.blk_t, w.blk_dst, oa, idx, Kg, Vg);
+  for (int h = 0; h < Hs; ++h) cap[h] = offs[h + 1] - offs[h];
+  select_assign_stage(prm, n_tokens, p, cap, w.sel_stats, n_rows, w.blk_t, w.blk_dst, st);
+  hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hs), dim3(kGatherThreads), 0, st, K, V,
+                     kv_stride, pos0, b, nb, Hs / Hkv, w.keys, w.blk_t, w.blk_dst, oa, idx, Kg, Vg);
   return TCA_OK;
 }
 
@@ -498,7 +647,7 @@ using namespace tca;
 
 extern "C" size_t tca_select_workspace_bytes(const tca_params* prm, int64_t n_tokens) {
   if (check_params(prm) != TCA_OK || n_tokens < 0) return 0;
-  SelectWs w = carve_select_ws(nullptr, prm->n_q_heads, prm->block, n_tokens);
+  SelectWs w = carve_select_ws(nullptr, prm, n_tokens);
   return w.bytes;
 }
 
@@ -510,7 +659,7 @@ extern "C" int tca_select(const tca_params* prm, const void* q_last, const void*
   if (rc) return rc;
   if (!q_last || !K || !V || !p || !offs || !n_rows || !idx || !Kg || !Vg || !ws)
     return fail(TCA_ERR_INVALID, "tca_select: NULL pointer argument");
-  const int b = prm->block, Hq = prm->n_q_heads;
+  const int b = prm->block, Hs = sel_heads(prm);
   if (n_tokens < 0 || pos0 < 0 || pos0 % b != 0 || pos0 + n_tokens > kv_stride)
     return fail(TCA_ERR_INVALID, "tca_select: pos0=%lld n_tokens=%lld kv_stride=%lld (pos0 must be a "
                 "multiple of b and the range must fit)", (long long)pos0, (long long)n_tokens,
@@ -520,7 +669,7 @@ extern "C" int tca_select(const tca_params* prm, const void* q_last, const void*
     return fail(TCA_ERR_UNSUPPORTED, "tca_select: %lld blocks exceed the limit of %d per call",
                 (long long)(n_tokens / b), TCA_MAX_BLOCKS);
   const int nk = block_log2(b) + 1;
-  for (int h = 0; h < Hq; ++h) {
+  for (int h = 0; h < Hs; ++h) {
     if (!valid_config(p + (size_t)h * nk, nk))
       return fail(TCA_ERR_INVALID, "tca_select: p[%d] is not a distribution", h);
     if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_select: offs not ascending at %d", h);

@@ -24,7 +24,7 @@ def chunk_bounds(L: int, chunk: int):
 
 def chunked_rows(prm, L: int, chunk: int, P) -> np.ndarray:
     """Rows each head's global region receives from a chunked prefill of L tokens."""
-    rows = np.zeros(prm.n_q_heads, np.int64)
+    rows = np.zeros(tb.tca_selection_heads(prm), np.int64)
     for c0, c1 in chunk_bounds(L, chunk):
         rows += tb.tca_select_rows(prm, (c1 - c0) // prm.block, P)[1]
     return rows
@@ -79,7 +79,7 @@ class MixedBatch:
         self.slot_of = {seq: s for s, seq in enumerate(order)}
         self.seq_of_slot = order
         t_dec = np.array([tb.tca_decode_budget(prm.block, p) for p in self.P])
-        cap = np.zeros(prm.n_q_heads, np.int64)
+        cap = np.zeros(tb.tca_selection_heads(prm), np.int64)
         # at most one decode step per chunk event, each can complete at most one block per sequence
         extra = t_dec * (len(events) // prm.block + 2)
         for L in self.lengths:

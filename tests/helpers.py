@@ -13,9 +13,10 @@ MARGIN = 1e-6
 TOL = {"bf16": 2e-2, "f32": 1e-4}      # max-abs output tolerance per storage type
 
 
-def params_for(tb, Hq, Hkv, d, b, w, dtype, alpha=0.5, metric="hhi"):
+def params_for(tb, Hq, Hkv, d, b, w, dtype, alpha=0.5, metric="hhi", share=False):
     return tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16 if dtype == "bf16" else tb.TCA_F32, alpha, 0.0,
-                          tb.TCA_METRIC_ENTROPY if metric == "entropy" else tb.TCA_METRIC_HHI)
+                          tb.TCA_METRIC_ENTROPY if metric == "entropy" else tb.TCA_METRIC_HHI,
+                          tb.TCA_SHARE_GROUP if share else tb.TCA_SHARE_HEAD)
 
 
 def gpu_select(tb, bufs_mod, prm, x, P, L=None, pos0=0, gb=None):
@@ -100,14 +101,16 @@ def assert_selection(sel: orc.Selection, got: np.ndarray, b: int, p, tag=""):
 
 
 def oracle_rows(x, P, prm_dict, S_list, rows, heads=None):
-    """Oracle outputs for the given query rows (positions) of each head, using the index sets S_list."""
+    """Oracle outputs for the given query rows (positions) of each head, using the index sets S_list
+    (one per query head, or one per KV head for a shared selection)."""
     Qf, Kf, Vf = x["Q"], wl.to_f64(x["K"]), wl.to_f64(x["V"])
     Hq, Hkv = Qf.shape[0], Kf.shape[0]
     heads = range(Hq) if heads is None else heads
+    per = Hq // len(S_list)
     out = {}
     for h in heads:
         g = orc.kv_head_of(h, Hq, Hkv)
         q = wl.to_f64(Qf[h][rows])
-        out[h] = np.stack([orc.attention_row(q[n], int(i), Kf[g], Vf[g], S_list[h], prm_dict["w"])
+        out[h] = np.stack([orc.attention_row(q[n], int(i), Kf[g], Vf[g], S_list[h // per], prm_dict["w"])
                            for n, i in enumerate(rows)])
     return out

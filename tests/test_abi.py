@@ -53,6 +53,12 @@ def test_host_counts_rows_and_decode_budget_match_oracle():
         total, rows = tb.tca_select_rows(prm, m, P)
         assert list(rows) == [orc.selected_rows(b, m, p) for p in P] and total == rows.sum()
     assert list(tb.tca_psi_counts(2, 8, [0.25, 0.75])) == [2, 6]
+    # a shared selection has one entry per KV head, and needs room for the logits of every query head
+    shared = tb.make_params(4, 2, 128, b, 512, tb.TCA_BF16, share=tb.TCA_SHARE_GROUP)
+    assert tb.tca_selection_heads(prm) == 4 and tb.tca_selection_heads(shared) == 2
+    total, rows = tb.tca_select_rows(shared, 256, P[:2])
+    assert list(rows) == [orc.selected_rows(b, 256, p) for p in P[:2]]
+    assert tb.tca_select_workspace_bytes(shared, 4096) >= 4 * 4096 * 8
 
 
 def test_argument_errors_are_codes_not_crashes():
@@ -69,6 +75,7 @@ def test_argument_errors_are_codes_not_crashes():
     assert tb.tca_select_workspace_bytes(bad, 1024) == 0
     for prm in (tb.make_params(4, 2, 96, 128, 4096, tb.TCA_BF16), tb.make_params(4, 2, 128, 128, 100, tb.TCA_BF16),
                 tb.make_params(4, 2, 128, 128, 4096, tb.TCA_BF16, 0.5, 0.0, 2),
+                tb.make_params(4, 2, 128, 128, 4096, tb.TCA_BF16, 0.5, 0.0, 0, 2),
                 tb.make_params(4, 2, 128, 128, 4096, 7), tb.make_params(256, 256, 128, 128, 4096, 0)):
         with pytest.raises(tb.TcaError):
             tb.tca_select_rows(prm, 4, np.ones((prm.n_q_heads, 8)) / 8)
