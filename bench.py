@@ -41,19 +41,24 @@ def visible_pairs(idx_host, L, w):
     return int(glob + local)
 
 
-def bench_prefill(args, tb, bufs, wl, torch):
+def bench_prefill(args, tb, bufs, wl, torch, share=False, x=None):
+    """share: one selection per KV head (tca_params.share = TCA_SHARE_GROUP) on the same inputs."""
     cfg = dict(wl.CONFIGS[3])
     if args.L:
         cfg["L"] = args.L
     Hq, Hkv, d, L, b, w = cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["L"], cfg["b"], cfg["w"]
-    log(f"[bench] generating config-3 inputs: Hq={Hq} Hkv={Hkv} d={d} L={L} bf16 ...")
-    t0 = time.time()
-    x = wl.prefill_inputs(cfg["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
-    log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
-    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, cfg["alpha"], 0.0)
+    if x is None:
+        log(f"[bench] generating config-3 inputs: Hq={Hq} Hkv={Hkv} d={d} L={L} bf16 ...")
+        t0 = time.time()
+        x = wl.prefill_inputs(cfg["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+        log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
+    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, cfg["alpha"], 0.0,
+                         share=tb.TCA_SHARE_GROUP if share else tb.TCA_SHARE_HEAD)
+    Hs = tb.tca_selection_heads(prm)
+    GS = Hq // Hs
 
     budget_src = "uniform[0.05,0.5]"
-    budget = ("frac", wl.budget_fractions(wl.budget_seed(3), Hq))
+    budget = ("frac", wl.budget_fractions(wl.budget_seed(3), Hs))
     fr = budget[1]
     P = np.stack([tb.tca_config_from_budget(b, cfg["sigma"], f) for f in fr])
     if args.calibrate:
@@ -76,7 +81,7 @@ def bench_prefill(args, tb, bufs, wl, torch):
     O = torch.empty_like(Qd)
     ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
     ws_pf = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
-    log(f"[bench] realised budget {total / (Hq * L):.4f} of L per head on average; {total} global rows")
+    log(f"[bench] realised budget {total / (Hs * L):.4f} of L per head on average; {total} global rows")
 
     def step(ev=None):
         gb.n_rows.zero_()
@@ -112,16 +117,16 @@ def bench_prefill(args, tb, bufs, wl, torch):
 
     idx_host = gb.idx.cpu().numpy()
     n_rows = gb.n_rows.cpu().numpy()
-    pairs = sum(visible_pairs(idx_host[int(gb.offs[h]):int(gb.offs[h]) + int(n_rows[h])], L, w) for h in range(Hq))
+    pairs = GS * sum(visible_pairs(idx_host[int(gb.offs[h]):int(gb.offs[h]) + int(n_rows[h])], L, w) for h in range(Hs))
     flops = 4.0 * d * pairs
     tflops = flops / (pf_ms * 1e-3) / 1e12
     e = 2
-    sel_bytes = Hkv * L * d * e + Hq * L + 2 * int(n_rows.sum()) * (2 * d * e) + 4 * int(n_rows.sum())
+    sel_bytes = Hkv * L * d * e + Hs * L + 2 * int(n_rows.sum()) * (2 * d * e) + 4 * int(n_rows.sum())
     res = {
         "L": L, "ms_per_step": ms_per_step, "select_ms": sel_ms, "prefill_ms": pf_ms,
         "tokens_per_s": L / (ms_per_step * 1e-3), "pairs": pairs, "flops": flops, "tflops": tflops,
         "select_gbs": sel_bytes / (sel_ms * 1e-3) / 1e9, "select_bytes": sel_bytes,
-        "budget_src": budget_src, "mean_budget": total / (Hq * L), "cfg": cfg,
+        "budget_src": budget_src, "mean_budget": total / (Hs * L), "cfg": cfg, "global_rows": int(total),
         "clock_ghz": clock_ghz, "probe_const": probe_c, "probe_random": probe_r,
     }
     host = {"x": x, "P": P, "idx": idx_host, "offs": gb.offs, "n_rows": n_rows, "O": O, "prm": prm, "budget": budget}
@@ -173,13 +178,15 @@ def cpu_baseline_prefill(host, cfg, wl, bufs, seconds=20.0, seed=5):
     }
 
 
-def bench_decode(args, tb, bufs, wl, torch):
+def bench_decode(args, tb, bufs, wl, torch, share=False):
     cfg = dict(wl.CONFIGS[4])
     Hq, Hkv, d, T0, b, w, B, steps = (cfg[k] for k in ("Hq", "Hkv", "d", "L", "b", "w", "batch", "steps"))
     if args.decode_batch:
         B = args.decode_batch
-    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, cfg["alpha"], 0.0)
-    fr = wl.budget_fractions(wl.budget_seed(4), Hq)
+    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, cfg["alpha"], 0.0,
+                         share=tb.TCA_SHARE_GROUP if share else tb.TCA_SHARE_HEAD)
+    Hs = tb.tca_selection_heads(prm)
+    fr = wl.budget_fractions(wl.budget_seed(4), Hs)
     P = np.stack([tb.tca_config_from_budget(b, cfg["sigma"], f) for f in fr])
     n_glob = np.round(fr * (T0 - w)).astype(np.int64)
     t_dec = np.array([tb.tca_decode_budget(b, p) for p in P])
@@ -192,7 +199,7 @@ def bench_decode(args, tb, bufs, wl, torch):
     for s in range(B):
         cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=g, device="cuda", dtype=torch.float32))
         cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=g, device="cuda", dtype=torch.float32))
-        for h in range(Hq):
+        for h in range(Hs):
             o = int(cache.offs[h])
             pos = np.sort(rng.choice(T0 - w, size=int(n_glob[h]), replace=False)).astype(np.int32)
             cache.idx[s, o:o + len(pos)] = torch.from_numpy(pos).cuda()
@@ -285,6 +292,8 @@ def main():
     ap.add_argument("--calibrate", action="store_true", default=True)
     ap.add_argument("--no-calibrate", dest="calibrate", action="store_false")
     ap.add_argument("--mixed", action="store_true", help="also time the config-5 ragged mixed batch (adds about a minute)")
+    ap.add_argument("--shared", action="store_true",
+                    help="also time both workloads with one selection per KV head (tca_params.share), reported in 'shared_selection'")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build covers one GPU only (no sharding, no collectives); run with --gpus 1")
@@ -315,9 +324,20 @@ def main():
         cpu = cpu_baseline_prefill(host, res["cfg"], wl, bufs, seconds=args.cpu_seconds)
         log(f"[bench] oracle: {cpu['value']:.2f} tokens/s on {cpu['cores']} threads; "
             f"max abs err vs GPU on sampled rows {cpu['max_abs_err_vs_gpu']:.3e}; index sets equal: {cpu['index_sets_equal_gpu']}")
+    shared = None
+    if args.shared:
+        rs, hs_ = bench_prefill(args, tb, bufs, wl, torch, share=True, x=host["x"])
+        del hs_
+        shared = {"what": "the same workloads with tca_params.share = TCA_SHARE_GROUP: one selection per KV head",
+                  "ms_per_step": rs["ms_per_step"], "select_ms": rs["select_ms"], "prefill_ms": rs["prefill_ms"],
+                  "prefill_tflops": rs["tflops"], "global_rows": rs["global_rows"], "mean_budget_frac": rs["mean_budget"],
+                  "select_gbs": rs["select_gbs"], "select_frac": rs["select_gbs"] / PEAK_HBM_GBS,
+                  "per_head_global_rows": res["global_rows"]}
     del host
     torch.cuda.empty_cache()
     dec = None if args.no_decode else bench_decode(args, tb, bufs, wl, torch)
+    if shared is not None and not args.no_decode:
+        shared["decode"] = bench_decode(args, tb, bufs, wl, torch, share=True)
     mixed = bench_mixed(args, tb, bufs, wl, torch) if args.mixed else None
 
     cfg = res["cfg"]
@@ -354,6 +374,8 @@ def main():
     }
     if mixed is not None:
         out["mixed_batch"] = mixed
+    if shared is not None:
+        out["shared_selection"] = shared
     print(json.dumps(out), flush=True)
 
 

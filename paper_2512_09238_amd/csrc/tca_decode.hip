@@ -94,6 +94,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
   constexpr int EL = D / 16;
+  constexpr int CH = kChunk;                          // rows per slot (256 and 2048 measured no better with GQ = 4)
   constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
   __shared__ float red[kDecThreads / kWave][16][GQ * PW];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -106,17 +107,20 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
 
   const T *kbase, *vbase;
   int r_begin, r_end;            // rows of this chunk, relative to kbase
-  bool is_window = slot >= g_slots;
+  const bool is_window = slot >= g_slots;
   if (!is_window) {
     const int nv = n_vis[s * Hs + hs];
-    r_begin = slot * kChunk;
-    r_end = min(nv, r_begin + kChunk);
+    r_begin = slot * CH;
+    r_end = min(nv, r_begin + CH);
     const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
     kbase = (const T*)c.Kg + base * D;
     vbase = (const T*)c.Vg + base * D;
   } else {
-    r_begin = (slot - g_slots) * kChunk;
-    r_end = min(w, r_begin + kChunk);
+    // Slot r of the ring holds the latest position congruent to r mod w that is <= Tpos.  Once
+    // Tpos >= w every slot is filled; before that only slots 0 .. Tpos are.
+    const int filled = Tpos >= w ? w : (int)Tpos + 1;
+    r_begin = (slot - g_slots) * CH;
+    r_end = min(filled, r_begin + CH);
     const size_t base = ((size_t)s * Hkv + kvh) * w;
     kbase = (const T*)c.ringK + base * D;
     vbase = (const T*)c.ringV + base * D;
@@ -126,12 +130,25 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     return;
   }
 
-  float qv[GQ][EL];
+  // logits are carried in base-2 units (scale * log2 e) so that the exponential is one v_exp_f32.
+  // bf16 storage: q.k over a lane's slice is EL/2 two-element bf16 dot products with fp32
+  // accumulation straight from the loaded words, and the factor is applied to the row's sum;
+  // fp32 storage: the factor is folded into the query.
+  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+  constexpr bool kDot2 = sizeof(T) == 2;
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const float qk_factor = kDot2 ? scale * kLog2e : 1.f;
+  float qv[kDot2 ? 1 : GQ][EL];
+  RawSlice<T, EL> qraw[kDot2 ? GQ : 1];
 #pragma unroll
   for (int g = 0; g < GQ; ++g) {
-    load_slice<T, EL>(q + ((size_t)s * Hq + h0 + g) * D + sub * EL, qv[g]);
+    if constexpr (kDot2) {
+      qraw[g].load(q + ((size_t)s * Hq + h0 + g) * D + sub * EL);
+    } else {
+      load_slice<T, EL>(q + ((size_t)s * Hq + h0 + g) * D + sub * EL, qv[g]);
 #pragma unroll
-    for (int e = 0; e < EL; ++e) qv[g][e] *= scale;
+      for (int e = 0; e < EL; ++e) qv[g][e] *= scale * kLog2e;
+    }
   }
 
   float m[GQ], l[GQ], acc[GQ][EL];
@@ -143,50 +160,77 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     for (int e = 0; e < EL; ++e) acc[g][e] = 0.f;
   }
 
-  // kUnr rows per group are loaded (K and V) before any of them is used, so that
-  // each lane keeps 2*kUnr 16-byte loads in flight
+  // Online softmax with a lazy reference: m[g] is raised (and l, acc rescaled) only when a
+  // logit exceeds it by more than kSlack, so the common row costs one subtract, one exp and
+  // the multiply-adds.  Terms are then at most 2^kSlack; the result is exact because l and
+  // acc share the reference, which the merge steps below carry along.
+  constexpr float kSlack = 8.f;
+  // Rows are fetched one iteration ahead of their use (kUnr rows of K and of V per group,
+  // kept as loaded until then), so that a lane has 2*kUnr loads in flight while it computes.
   constexpr int kUnr = 2;
-  for (int r0 = r_begin; r0 < r_end; r0 += 16 * kUnr) {
-    float kv[kUnr][EL], vv[kUnr][EL];
-    bool ok[kUnr];
+  using Raw = RawSlice<T, EL>;
+  Raw kr[kUnr], vr[kUnr];
+  bool ok[kUnr];
+  auto fetch = [&](int r0, Raw (&kk)[kUnr], Raw (&vq)[kUnr], bool (&okk)[kUnr]) {
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
       const int r = r0 + u * 16 + grp;
-      ok[u] = r < r_end;
-      if (ok[u] && is_window) {
-        // slot r of the ring holds position Tpos - ((Tpos - r) mod w); empty while Tpos < w
-        const int64_t back = ((Tpos - r) % w + w) % w;
-        ok[u] = Tpos - back >= 0;
-      }
-      if (ok[u]) {
-        load_slice<T, EL>(kbase + (size_t)r * D + sub * EL, kv[u]);
-        load_slice<T, EL>(vbase + (size_t)r * D + sub * EL, vv[u]);
+      okk[u] = r < r_end;
+      if (okk[u]) {
+        kk[u].load(kbase + (size_t)r * D + sub * EL);
+        vq[u].load(vbase + (size_t)r * D + sub * EL);
       }
     }
+  };
+  fetch(r_begin, kr, vr, ok);
+  for (int r0 = r_begin; r0 < r_end; r0 += 16 * kUnr) {
+    Raw kn[kUnr], vn[kUnr];
+    bool okn[kUnr];
+    fetch(r0 + 16 * kUnr, kn, vn, okn);                    // nothing is loaded past r_end
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
+      float kv[EL], vv[EL];
+      if (ok[u]) {
+        if constexpr (!kDot2) kr[u].widen(kv);
+        vr[u].widen(vv);
+      }
 #pragma unroll
       for (int g = 0; g < GQ; ++g) {
         float sc = 0.f;
         if (ok[u]) {
+          if constexpr (kDot2) {
 #pragma unroll
-          for (int e = 0; e < EL; ++e) sc = fmaf(qv[g][e], kv[u][e], sc);
+            for (int i = 0; i < EL / 2; ++i)
+              sc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kr[u].w[i]),
+                                                   __builtin_bit_cast(bf16x2_t, qraw[g].w[i]), sc, false);
+          } else {
+#pragma unroll
+            for (int e = 0; e < EL; ++e) sc = fmaf(qv[g][e], kv[e], sc);
+          }
         }
-        sc = row16_sum(sc);
+        sc = row16_sum(sc) * qk_factor;
         if (ok[u]) {
-          const float mn = fmaxf(m[g], sc);
-          const float corr = __expf(m[g] - mn), pr = __expf(sc - mn);
-          l[g] = l[g] * corr + pr;
+          if (sc > m[g] + kSlack) {
+            const float corr = __builtin_amdgcn_exp2f(m[g] - sc);       // 0 on the first row (m = -inf)
+            l[g] *= corr;
 #pragma unroll
-          for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * corr + pr * vv[u][e];
-          m[g] = mn;
+            for (int e = 0; e < EL; ++e) acc[g][e] *= corr;
+            m[g] = sc;
+          }
+          const float pr = __builtin_amdgcn_exp2f(sc - m[g]);
+          l[g] += pr;
+#pragma unroll
+          for (int e = 0; e < EL; ++e) acc[g][e] = fmaf(pr, vv[e], acc[g][e]);
         }
       }
     }
+#pragma unroll
+    for (int u = 0; u < kUnr; ++u) { kr[u] = kn[u]; vr[u] = vn[u]; ok[u] = okn[u]; }
   }
-  // merge the 4 groups of a wave, then the 4 waves through LDS
+  // merge the 4 groups of a wave, then the 4 waves through LDS (references back in natural-log units)
 #pragma unroll
   for (int g = 0; g < GQ; ++g) {
+    m[g] *= kLn2;
     for (int o = 16; o < 64; o <<= 1) {
       const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
       const float mn = fmaxf(m[g], mo);

@@ -92,6 +92,38 @@ template <> __device__ __forceinline__ void load_slice<bf16_t, 4>(const bf16_t* 
   out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
 }
 
+// The same slice kept as loaded (N*sizeof(T) bytes) and widened when it is used, so that
+// loads issued ahead of their use cost few registers.
+template <typename T, int N>
+struct RawSlice {
+  static constexpr int W = N * (int)sizeof(T) / 4;       // dwords: 2, 4 or 8
+  uint32_t w[W];
+  __device__ __forceinline__ void load(const T* p) {
+    if constexpr (W == 2) {
+      const uint2 v = *reinterpret_cast<const uint2*>(p);
+      w[0] = v.x; w[1] = v.y;
+    } else {
+#pragma unroll
+      for (int i = 0; i < W / 4; ++i) {
+        const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p) + 16 * i);
+        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+      }
+    }
+  }
+  __device__ __forceinline__ void widen(float (&out)[N]) const {
+    if constexpr (sizeof(T) == 4) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) out[i] = __uint_as_float(w[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < W; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+    }
+  }
+};
+
 // Lane exchanges on the vector ALU (DPP), which are several times cheaper than
 // the LDS-crossbar shuffles.  Patterns (all within a row of 16 lanes):
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
