@@ -242,3 +242,112 @@ def test_shared_chunked_prefill_matches_oracle(mods):
     Og = bufs.to_host_f64(O)
     assert not np.isnan(Og).any()
     assert np.abs(Og - Oref).max() <= H.TOL[dtype]
+
+
+def test_shared_prefill_full_size_sampled_rows(mods):
+    """Config 3 (128K tokens, Hq=32, Hkv=8) with one selection per KV head, as bench.py --shared
+    runs it: index sets compared in full, outputs on sampled rows of every query head."""
+    tb, bufs, _ = mods
+    c = wl.CONFIGS[3]
+    Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
+    G = Hq // Hkv
+    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+    P_gpu, P_orc = configs(tb, b, wl.budget_fractions(wl.budget_seed(3), Hkv))
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16", share=True)
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    O = torch.empty_like(Qd)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+    Kf, Vf = wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    sels = orc.select_all_groups(wl.to_f64(x["Q"][:, L - 1]), Kf, b, P_orc, c["alpha"])
+    S_used = []
+    for g in range(Hkv):
+        got = H.head_indices(gb, g)
+        H.assert_selection(sels[g], got, b, P_orc[g], tag=f"kv head {g}")
+        S_used.append(got)
+    rng = np.random.default_rng(199)
+    pos = np.unique(np.concatenate([[0, b, w - 1, w, w + 1, L // 2, L - 1], rng.integers(0, L, size=8)])).astype(np.int64)
+    Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
+    worst = 0.0
+    for h in range(Hq):
+        qh = wl.to_f64(x["Q"][h][pos])
+        for n, i in enumerate(pos):
+            ref = orc.attention_row(qh[n], int(i), Kf[h // G], Vf[h // G], S_used[h // G], w)
+            worst = max(worst, float(np.abs(ref - Og[h, n]).max()))
+    print("max abs err on", len(pos) * Hq, "rows:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
+
+
+def test_shared_decode_full_size_sampled_heads(mods):
+    """Config 4 (batch 16 at 128K context) with one selection per KV head: sampled (sequence,
+    query head) outputs against the oracle, and the rows appended by a block that completes."""
+    tb, bufs, _ = mods
+    c = wl.CONFIGS[4]
+    Hq, Hkv, d, T0, b, w, B = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"], c["batch"]
+    G = Hq // Hkv
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16", share=True)
+    fr = wl.budget_fractions(wl.budget_seed(4), Hkv)
+    P_gpu, P_orc = configs(tb, b, fr)
+    n_glob = np.round(fr * (T0 - w)).astype(np.int64)
+    t_dec = np.array([tb.tca_decode_budget(b, p) for p in P_gpu])
+    cache = bufs.DecodeCache(prm, B, n_glob + 2 * t_dec)
+    gen = torch.Generator(device="cuda").manual_seed(wl.data_seed(4) + 1)
+    rng = np.random.default_rng(wl.data_seed(4) + 1)
+    pend = rng.integers(0, b, size=B)
+    pend[3] = b - 1                                    # sequence 3 completes a block at this step
+    lengths = T0 + pend
+    for s in range(B):
+        cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=gen, device="cuda", dtype=torch.float32))
+        cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=gen, device="cuda", dtype=torch.float32))
+        for g in range(Hkv):
+            o = int(cache.offs[g])
+            pos = np.sort(rng.choice(T0 - w, size=int(n_glob[g]), replace=False)).astype(np.int32)
+            cache.idx[s, o:o + len(pos)] = torch.from_numpy(pos).cuda()
+    cache.n_rows.copy_(torch.from_numpy(np.tile(n_glob.astype(np.int32), (B, 1))))
+    cache.ringK.copy_(torch.randn(cache.ringK.shape, generator=gen, device="cuda", dtype=torch.float32))
+    cache.ringV.copy_(torch.randn(cache.ringV.shape, generator=gen, device="cuda", dtype=torch.float32))
+    cache.length.copy_(torch.from_numpy(lengths.astype(np.int64)))
+    q = torch.randn(B, Hq, d, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    kn = torch.randn(B, Hkv, d, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    vn = torch.randn(B, Hkv, d, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    O = torch.full((B, Hq, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    ws = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache.max_head_rows))
+    groups = [(0, 0), (3, 1), (3, 7), (9, 4), (15, 7)]           # (sequence, KV head)
+    before = {}
+    for (s, g) in groups:
+        o, n = int(cache.offs[g]), int(n_glob[g])
+        before[(s, g)] = dict(idx=cache.idx[s, o:o + n].cpu().numpy().astype(np.int64),
+                              Kg=cache.Kg[s, o:o + n].double().cpu().numpy(), Vg=cache.Vg[s, o:o + n].double().cpu().numpy(),
+                              ringK=cache.ringK[s, g].double().cpu().numpy(), ringV=cache.ringV[s, g].double().cpu().numpy())
+    tb.tca_decode(prm, cache.view, cache.offs, q, kn, vn, P_gpu, O, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O.float()).any()
+    assert cache.length.cpu().tolist() == (lengths + 1).tolist()
+    worst = 0.0
+    for (s, g) in groups:
+        T = int(lengths[s])
+        bf = before[(s, g)]
+        Kfull = np.zeros((T + 1, d)); Vfull = np.zeros((T + 1, d))
+        Kfull[bf["idx"]] = bf["Kg"]; Vfull[bf["idx"]] = bf["Vg"]
+        for p in range(T - w + 1, T):
+            Kfull[p] = bf["ringK"][p % w]; Vfull[p] = bf["ringV"][p % w]
+        Kfull[T] = kn[s, g].double().cpu().numpy(); Vfull[T] = vn[s, g].double().cpu().numpy()
+        qg = q[s, g * G:(g + 1) * G].double().cpu().numpy()
+        for j in range(G):
+            ref = orc.attention_row(qg[j], T, Kfull, Vfull, bf["idx"], w)
+            worst = max(worst, float(np.abs(ref - O[s, g * G + j].double().cpu().numpy()).max()))
+        o = int(cache.offs[g])
+        n_now = int(cache.n_rows[s, g].item())
+        if (T + 1) % b == 0:
+            blk = T // b
+            X = np.stack([orc.last_query_logits(qg[j], Kfull[blk * b:(blk + 1) * b]) for j in range(G)])
+            keep = blk * b + orc.top_t(orc.group_scores_from_logits(X), orc.decode_budget(b, P_orc[g]))
+            assert n_now == n_glob[g] + len(keep)
+            assert np.array_equal(cache.idx[s, o + int(n_glob[g]):o + n_now].cpu().numpy(), keep)
+            assert np.array_equal(cache.Kg[s, o + int(n_glob[g]):o + n_now].double().cpu().numpy(), Kfull[keep])
+        else:
+            assert n_now == n_glob[g]
+    print("max abs err on sampled (sequence, head) pairs:", worst, flush=True)
+    assert worst <= H.TOL["bf16"]
