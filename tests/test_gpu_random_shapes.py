@@ -1,6 +1,7 @@
 """Seeded sweep over small random shapes: selection sets, prefill outputs and a few decode
 steps of the GPU path against the oracle, every row.  Shapes cover both head dims, every
-group size 1..8, blocks 2..256, windows of 1..8 blocks, ragged lengths, both storage types."""
+group size 1..8, blocks 2..256, windows of 1..8 blocks, ragged lengths, both storage types.
+A second sweep runs other shapes with one selection per KV head (tca_params.share)."""
 import numpy as np
 import pytest
 import torch
@@ -34,17 +35,31 @@ def _draw(rng):
 CASES = [(_draw(np.random.default_rng(900 + i)), 900 + i) for i in range(48)]
 
 
+SHARED_CASES = [(_draw(np.random.default_rng(1900 + i)), 1900 + i) for i in range(32)]
+
+
 @pytest.mark.parametrize("case,seed", CASES, ids=lambda v: str(v).replace(" ", ""))
 def test_random_shape_select_prefill_decode(mods, case, seed):
+    run_case(mods, case, seed, share=False)
+
+
+@pytest.mark.parametrize("case,seed", SHARED_CASES, ids=lambda v: str(v).replace(" ", ""))
+def test_random_shape_shared_selection(mods, case, seed):
+    run_case(mods, case, seed, share=True)
+
+
+def run_case(mods, case, seed, share):
     tb, bufs = mods
     kind, Hq, Hkv, d, L, dtype, b, w = case
-    print("case", case, "seed", seed, flush=True)
+    print("case", case, "seed", seed, "share", share, flush=True)
     rng = np.random.default_rng(seed)
     x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
-    fr = rng.uniform(0.03, 0.97, size=Hq)
+    Hs = Hkv if share else Hq
+    GS = Hq // Hs
+    fr = rng.uniform(0.03, 0.97, size=Hs)
     P_gpu = np.stack([tb.tca_config_from_budget(b, 1.0, f) for f in fr])
     P_orc = np.stack([orc.config_from_budget(b, 1.0, f) for f in fr])
-    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype, share=share)
     steps = int(min(2 * b + 3, 40))
     _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
     extra = np.array([tb.tca_decode_budget(b, p) for p in P_gpu]) * ((L + steps) // b - L // b + 1)
@@ -61,14 +76,15 @@ def test_random_shape_select_prefill_decode(mods, case, seed):
     torch.cuda.synchronize()
 
     Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
-    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5, share=share)
     exact = True
-    for h in range(Hq):
-        o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
+    for n_ in range(Hs):
+        o, n = int(cache.offs[n_]), int(cache.n_rows[0, n_].item())
         got = cache.idx[0, o:o + n].cpu().numpy().astype(np.int64)
-        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+        if not H.assert_selection(sels[n_], got, b, P_orc[n_], tag=f"selection head {n_}"):
             exact = False
-            Oref[h] = orc.tca_attention(Qf[h], Kf[h // (Hq // Hkv)], Vf[h // (Hq // Hkv)], got, w)
+            for h in range(n_ * GS, (n_ + 1) * GS):
+                Oref[h] = orc.tca_attention(Qf[h], Kf[h // (Hq // Hkv)], Vf[h // (Hq // Hkv)], got, w)
     Og = bufs.to_host_f64(O)
     assert not np.isnan(Og).any()
     err = np.abs(Og - Oref).max()
@@ -87,9 +103,9 @@ def test_random_shape_select_prefill_decode(mods, case, seed):
     worst = 0.0
     for s in range(steps):
         ref = orc.decode_step(ocache, wl.to_f64(dec["q"][s, 0]), wl.to_f64(dec["k_new"][s, 0]),
-                              wl.to_f64(dec["v_new"][s, 0]), b, w, P_orc)
+                              wl.to_f64(dec["v_new"][s, 0]), b, w, P_orc, share=share)
         worst = max(worst, np.abs(Odg[s, 0] - ref).max())
     assert worst <= H.TOL[dtype], f"decode max abs err {worst}"
-    for h in range(Hq):
+    for h in range(Hs):
         o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
         assert np.array_equal(cache.idx[0, o:o + n].cpu().numpy(), ocache.S[h]), f"head {h} after decode"

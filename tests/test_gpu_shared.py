@@ -351,3 +351,69 @@ def test_shared_decode_full_size_sampled_heads(mods):
             assert n_now == n_glob[g]
     print("max abs err on sampled (sequence, head) pairs:", worst, flush=True)
     assert worst <= H.TOL["bf16"]
+
+
+def test_shared_mixed_batch_and_graph_replay(mods):
+    """The ragged mixed batch (chunks interleaved with decode steps) with one selection per KV
+    head, each sequence replayed alone by the oracle; then one more decode step of the whole
+    batch captured into a HIP graph and replayed against the eager result."""
+    tb, bufs, sched = mods
+    Hq, Hkv, d, b, w, chunk = 8, 2, 64, 32, 128, 256
+    lengths = [300, 1100, 700]
+    seed = 191
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16", share=True)
+    P_gpu, P_orc = configs(tb, b, wl.budget_fractions(seed, Hkv))
+    xs = [wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "bf16", seed + 1 + i) for i, L in enumerate(lengths)]
+    mb = sched.MixedBatch(prm, lengths, chunk, P_gpu)
+    n_calls = len(mb.events)
+    dec = wl.decode_inputs(Hq, Hkv, d, n_calls + 1, "bf16", seed + 9, batch=len(lengths))
+    seqs = []
+    for x in xs:
+        Qd = bufs.to_device(x["Q"])
+        seqs.append(dict(Q=Qd, K=bufs.to_device(x["K"]), V=bufs.to_device(x["V"]), O=torch.full_like(Qd, float("nan"))))
+    outs = {}
+    mb.run(seqs, lambda step, slots: tuple(bufs.to_device(dec[k][step, :len(slots)]) for k in ("q", "k_new", "v_new")),
+           lambda step, slots, Od: outs.__setitem__(step, (list(slots), Od.clone())))
+    torch.cuda.synchronize()
+    assert mb.n_done == len(lengths)
+    worst_p, worst_d = 0.0, 0.0
+    for i, (x, L) in enumerate(zip(xs, lengths)):
+        Qf, Kf, Vf = (wl.to_f64(x[k]) for k in ("Q", "K", "V"))
+        Oref, S = orc.tca_prefill_chunked(Qf, Kf, Vf, b, w, P_orc, 0.5, chunk, share=True)
+        worst_p = max(worst_p, np.abs(bufs.to_host_f64(seqs[i]["O"]) - Oref).max())
+        slot = mb.slot_of[i]
+        oc = orc.HeadCache(S=[s_.copy() for s_ in S], K=Kf.copy(), V=Vf.copy())
+        for step in sorted(outs):
+            slots, Od = outs[step]
+            if slot in slots:
+                ref = orc.decode_step(oc, wl.to_f64(dec["q"][step, slot]), wl.to_f64(dec["k_new"][step, slot]),
+                                      wl.to_f64(dec["v_new"][step, slot]), b, w, P_orc, share=True)
+                worst_d = max(worst_d, np.abs(Od[slot].double().cpu().numpy() - ref).max())
+        for g in range(Hkv):
+            o, n = int(mb.cache.offs[g]), int(mb.cache.n_rows[slot, g].item())
+            assert np.array_equal(mb.cache.idx[slot, o:o + n].cpu().numpy(), oc.S[g]), (i, g)
+    print("max abs err prefill", worst_p, "decode", worst_d, flush=True)
+    assert worst_p <= H.TOL["bf16"] and worst_d <= H.TOL["bf16"]
+
+    # one more step of the full batch: eager on a copy of the cache state, then from a graph
+    c = mb.cache
+    order = mb.seq_of_slot
+    q1, k1, v1 = (bufs.to_device(np.ascontiguousarray(dec[k][n_calls][order])) for k in ("q", "k_new", "v_new"))
+    state = [t.clone() for t in (c.idx, c.Kg, c.Vg, c.n_rows, c.ringK, c.ringV, c.length)]
+    O_eager = torch.empty_like(q1)
+    tb.tca_decode(prm, c.view, c.offs, q1, k1, v1, P_gpu, O_eager, mb.ws.decode)
+    torch.cuda.synchronize()
+    after = [t.clone() for t in (c.idx, c.n_rows, c.length)]
+    for t, s0 in zip((c.idx, c.Kg, c.Vg, c.n_rows, c.ringK, c.ringV, c.length), state):
+        t.copy_(s0)
+    O_graph = torch.empty_like(q1)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        tb.tca_decode(prm, c.view, c.offs, q1, k1, v1, P_gpu, O_graph, mb.ws.decode)
+    for rep in range(3):
+        for t, s0 in zip((c.idx, c.Kg, c.Vg, c.n_rows, c.ringK, c.ringV, c.length), state):
+            t.copy_(s0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_graph, O_eager), f"replay {rep}"
+        assert all(torch.equal(a, t) for a, t in zip(after, (c.idx, c.n_rows, c.length)))
