@@ -87,46 +87,20 @@ __global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv,
   }
 }
 
-// grid (n_slots, Hs, B); block 256.  Selection head hs = blockIdx.y serves the GQ query
-// heads hs*GQ .. hs*GQ+GQ-1 (GQ = 1: one selection per query head).
-template <typename T, int D, int GQ>
-__global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
-    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
-    const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
+// Split-K attention of NQ queries (consecutive heads, q0 = the first one's row) over rows
+// [r_begin, r_end) of one K/V buffer: every row is read once and scored against all NQ queries.
+// Writes one (max, sum, acc[D]) partial per query at out + g * out_head.  red: LDS scratch of
+// 4 * 16 * NQ * (D/16 + 2) floats.  Called by a whole workgroup of 256 threads.
+template <typename T, int D, int NQ>
+__device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const T* __restrict__ vbase, int r_begin,
+                                             int r_end, const T* __restrict__ q0, float scale,
+                                             float* __restrict__ out, size_t out_head, float* red) {
   constexpr int EL = D / 16;
-  constexpr int CH = kChunk;                          // rows per slot (256 and 2048 measured no better with GQ = 4)
   constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
-  __shared__ float red[kDecThreads / kWave][16][GQ * PW];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int grp = tid >> 4, sub = tid & 15;           // 16 groups of 16 lanes
-  const int slot = blockIdx.x, hs = blockIdx.y, s = blockIdx.z;
-  const int Hs = Hq / GQ, h0 = hs * GQ, kvh = h0 / (Hq / Hkv);
-  float* out = part + (((size_t)s * Hq + h0) * n_slots + slot) * (D + 2);   // head h0 + g: + g * n_slots * (D+2)
-  const size_t out_head = (size_t)n_slots * (D + 2);
-  const int64_t Tpos = c.length[s];
-
-  const T *kbase, *vbase;
-  int r_begin, r_end;            // rows of this chunk, relative to kbase
-  const bool is_window = slot >= g_slots;
-  if (!is_window) {
-    const int nv = n_vis[s * Hs + hs];
-    r_begin = slot * CH;
-    r_end = min(nv, r_begin + CH);
-    const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
-    kbase = (const T*)c.Kg + base * D;
-    vbase = (const T*)c.Vg + base * D;
-  } else {
-    // Slot r of the ring holds the latest position congruent to r mod w that is <= Tpos.  Once
-    // Tpos >= w every slot is filled; before that only slots 0 .. Tpos are.
-    const int filled = Tpos >= w ? w : (int)Tpos + 1;
-    r_begin = (slot - g_slots) * CH;
-    r_end = min(filled, r_begin + CH);
-    const size_t base = ((size_t)s * Hkv + kvh) * w;
-    kbase = (const T*)c.ringK + base * D;
-    vbase = (const T*)c.ringV + base * D;
-  }
   if (r_begin >= r_end) {
-    if (tid < GQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
+    if (tid < NQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
     return;
   }
 
@@ -138,22 +112,22 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   constexpr bool kDot2 = sizeof(T) == 2;
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   const float qk_factor = kDot2 ? scale * kLog2e : 1.f;
-  float qv[kDot2 ? 1 : GQ][EL];
-  RawSlice<T, EL> qraw[kDot2 ? GQ : 1];
+  float qv[kDot2 ? 1 : NQ][EL];
+  RawSlice<T, EL> qraw[kDot2 ? NQ : 1];
 #pragma unroll
-  for (int g = 0; g < GQ; ++g) {
+  for (int g = 0; g < NQ; ++g) {
     if constexpr (kDot2) {
-      qraw[g].load(q + ((size_t)s * Hq + h0 + g) * D + sub * EL);
+      qraw[g].load(q0 + (size_t)g * D + sub * EL);
     } else {
-      load_slice<T, EL>(q + ((size_t)s * Hq + h0 + g) * D + sub * EL, qv[g]);
+      load_slice<T, EL>(q0 + (size_t)g * D + sub * EL, qv[g]);
 #pragma unroll
       for (int e = 0; e < EL; ++e) qv[g][e] *= scale * kLog2e;
     }
   }
 
-  float m[GQ], l[GQ], acc[GQ][EL];
+  float m[NQ], l[NQ], acc[NQ][EL];
 #pragma unroll
-  for (int g = 0; g < GQ; ++g) {
+  for (int g = 0; g < NQ; ++g) {
     m[g] = -INFINITY;
     l[g] = 0.f;
 #pragma unroll
@@ -195,7 +169,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
         vr[u].widen(vv);
       }
 #pragma unroll
-      for (int g = 0; g < GQ; ++g) {
+      for (int g = 0; g < NQ; ++g) {
         float sc = 0.f;
         if (ok[u]) {
           if constexpr (kDot2) {
@@ -229,7 +203,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
   }
   // merge the 4 groups of a wave, then the 4 waves through LDS (references back in natural-log units)
 #pragma unroll
-  for (int g = 0; g < GQ; ++g) {
+  for (int g = 0; g < NQ; ++g) {
     m[g] *= kLn2;
     for (int o = 16; o < 64; o <<= 1) {
       const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
@@ -242,31 +216,72 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
       m[g] = mn;
     }
     if (lane < 16) {
-      red[wv][lane][g * PW] = m[g];
-      red[wv][lane][g * PW + 1] = l[g];
+      red[(wv * 16 + lane) * (NQ * PW) + g * PW] = m[g];
+      red[(wv * 16 + lane) * (NQ * PW) + g * PW + 1] = l[g];
 #pragma unroll
-      for (int e = 0; e < EL; ++e) red[wv][lane][g * PW + 2 + e] = acc[g][e];
+      for (int e = 0; e < EL; ++e) red[(wv * 16 + lane) * (NQ * PW) + g * PW + 2 + e] = acc[g][e];
     }
   }
   __syncthreads();
-  for (int pi = tid; pi < 16 * GQ; pi += kDecThreads) {
+  for (int pi = tid; pi < 16 * NQ; pi += kDecThreads) {
     const int g = pi >> 4, ln = pi & 15;
     float M = -INFINITY;
-    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[x][ln][g * PW]);
+    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[(x * 16 + ln) * (NQ * PW) + g * PW]);
     float L = 0.f, a[EL];
 #pragma unroll
     for (int e = 0; e < EL; ++e) a[e] = 0.f;
     for (int x = 0; x < kDecThreads / kWave; ++x) {
-      const float mx = red[x][ln][g * PW];
+      const float mx = red[(x * 16 + ln) * (NQ * PW) + g * PW];
       const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
-      L += red[x][ln][g * PW + 1] * cf;
+      L += red[(x * 16 + ln) * (NQ * PW) + g * PW + 1] * cf;
 #pragma unroll
-      for (int e = 0; e < EL; ++e) a[e] += red[x][ln][g * PW + 2 + e] * cf;
+      for (int e = 0; e < EL; ++e) a[e] += red[(x * 16 + ln) * (NQ * PW) + g * PW + 2 + e] * cf;
     }
     float* og = out + g * out_head;
     if (ln == 0) { og[0] = M; og[1] = L; }
 #pragma unroll
     for (int e = 0; e < EL; ++e) og[2 + ln * EL + e] = a[e];
+  }
+}
+
+// grid (n_slots, Hs, B); block 256.  Selection head hs = blockIdx.y serves the GQ query
+// heads hs*GQ .. hs*GQ+GQ-1 (GQ = 1: one selection per query head).  Slots below g_slots are
+// chunks of the head's global region, the others chunks of the ring.  The ring belongs to the KV
+// head, so with GW > GQ (one selection per query head, GW = G heads per KV head) the workgroup
+// of the group's first head scores each ring row against all GW queries and the others skip it.
+template <typename T, int D, int GQ, int GW>
+__global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
+    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
+    const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
+  constexpr int EL = D / 16;
+  constexpr int CH = kChunk;                          // rows per slot (256 and 2048 measured no better with GQ = 4)
+  constexpr int NMAX = GQ > GW ? GQ : GW;
+  __shared__ float red[(kDecThreads / kWave) * 16 * NMAX * (EL + 2)];
+  const int tid = threadIdx.x;
+  const int slot = blockIdx.x, hs = blockIdx.y, s = blockIdx.z;
+  const int Hs = Hq / GQ, h0 = hs * GQ, kvh = h0 / (Hq / Hkv);
+  float* out = part + (((size_t)s * Hq + h0) * n_slots + slot) * (D + 2);   // head h0 + g: + g * n_slots * (D+2)
+  const size_t out_head = (size_t)n_slots * (D + 2);
+  const int64_t Tpos = c.length[s];
+  const T* q0 = q + ((size_t)s * Hq + h0) * D;
+
+  if (slot < g_slots) {
+    const int nv = n_vis[s * Hs + hs];
+    const int r_begin = slot * CH;
+    const int r_end = min(nv, r_begin + CH);
+    const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
+    partial_rows<T, D, GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
+                           out_head, red);
+  } else {
+    if (GW != GQ && h0 % GW != 0) return;              // this head's ring partial is written by the group's first head
+    // Slot r of the ring holds the latest position congruent to r mod w that is <= Tpos.  Once
+    // Tpos >= w every slot is filled; before that only slots 0 .. Tpos are.
+    const int filled = Tpos >= w ? w : (int)Tpos + 1;
+    const int r_begin = (slot - g_slots) * CH;
+    const int r_end = min(filled, r_begin + CH);
+    const size_t base = ((size_t)s * Hkv + kvh) * w;
+    partial_rows<T, D, GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale, out,
+                           out_head, red);
   }
 }
 
@@ -458,12 +473,18 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
   hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new, v_new,
                      dw.n_vis);
   const float sc = (float)logit_scale(prm);
-#define TCA_PARTIAL_CASE(GG)                                                                                \
-  case GG:                                                                                                  \
-    hipLaunchKernelGGL((decode_partial_kernel<T, D, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st, *c, \
-                       dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                         \
+  // (queries per region row, queries per ring row): (G, G) for a shared selection, else (1, G)
+  const int G = Hq / Hkv;
+#define TCA_PARTIAL_CASE(GG)                                                                                    \
+  case GG:                                                                                                      \
+    if (GS > 1)                                                                                                 \
+      hipLaunchKernelGGL((decode_partial_kernel<T, D, GG, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st, \
+                         *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
+    else                                                                                                        \
+      hipLaunchKernelGGL((decode_partial_kernel<T, D, 1, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st,  \
+                         *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
     break;
-  switch (GS) {
+  switch (G) {
     TCA_PARTIAL_CASE(1) TCA_PARTIAL_CASE(2) TCA_PARTIAL_CASE(3) TCA_PARTIAL_CASE(4)
     TCA_PARTIAL_CASE(5) TCA_PARTIAL_CASE(6) TCA_PARTIAL_CASE(7) TCA_PARTIAL_CASE(8)
   }
