@@ -26,10 +26,15 @@
 #include "tca_common.h"
 #include "tca_device.h"
 
+#ifndef TCA_PART_THREADS
+#define TCA_PART_THREADS 256
+#endif
 namespace tca {
 
-constexpr int kChunk = 1024;          // rows per split-K slot
-constexpr int kDecThreads = 256;
+constexpr int kPartThreads = TCA_PART_THREADS;   // threads of a split-K workgroup
+constexpr int kPartWaves = kPartThreads / 64;
+constexpr int kChunk = 4 * kPartThreads;          // rows per split-K slot: 64 per 16-lane group
+constexpr int kDecThreads = 256;                  // the other kernels
 constexpr int kMaxSlots = 4096;       // split-K slots per head the merge kernel can weigh (4M rows per head)
 
 struct DecodeHeads {
@@ -87,10 +92,63 @@ __global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv,
   }
 }
 
+// Tail of the split-K kernels: every 16-lane group of the workgroup holds, for each of NQ
+// queries, an online-softmax state (reference m in base-2 units, sum l, acc over the lane's
+// slice of d).  Merges the 4 groups of each wave, then the 4 waves through LDS, and writes one
+// (max, sum, acc[D]) partial per query at out + g * out_head.
+template <int D, int NQ>
+__device__ __forceinline__ void merge_partials(float (&m)[NQ], float (&l)[NQ], float (&acc)[NQ][D / 16],
+                                               float* __restrict__ out, size_t out_head, float* red) {
+  constexpr int EL = D / 16;
+  constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
+  constexpr float kLn2 = 0.6931471805599453f;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    m[g] *= kLn2;
+    for (int o = 16; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
+      const float mn = fmaxf(m[g], mo);
+      const float ca = (m[g] == -INFINITY) ? 0.f : __expf(m[g] - mn);
+      const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
+      l[g] = l[g] * ca + lo * cb;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], o, kWave) * cb;
+      m[g] = mn;
+    }
+    if (lane < 16) {
+      red[(wv * 16 + lane) * (NQ * PW) + g * PW] = m[g];
+      red[(wv * 16 + lane) * (NQ * PW) + g * PW + 1] = l[g];
+#pragma unroll
+      for (int e = 0; e < EL; ++e) red[(wv * 16 + lane) * (NQ * PW) + g * PW + 2 + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  for (int pi = tid; pi < 16 * NQ; pi += kPartThreads) {
+    const int g = pi >> 4, ln = pi & 15;
+    float M = -INFINITY;
+    for (int x = 0; x < kPartWaves; ++x) M = fmaxf(M, red[(x * 16 + ln) * (NQ * PW) + g * PW]);
+    float L = 0.f, a[EL];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) a[e] = 0.f;
+    for (int x = 0; x < kPartWaves; ++x) {
+      const float mx = red[(x * 16 + ln) * (NQ * PW) + g * PW];
+      const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+      L += red[(x * 16 + ln) * (NQ * PW) + g * PW + 1] * cf;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) a[e] += red[(x * 16 + ln) * (NQ * PW) + g * PW + 2 + e] * cf;
+    }
+    float* og = out + g * out_head;
+    if (ln == 0) { og[0] = M; og[1] = L; }
+#pragma unroll
+    for (int e = 0; e < EL; ++e) og[2 + ln * EL + e] = a[e];
+  }
+}
+
 // Split-K attention of NQ queries (consecutive heads, q0 = the first one's row) over rows
 // [r_begin, r_end) of one K/V buffer: every row is read once and scored against all NQ queries.
 // Writes one (max, sum, acc[D]) partial per query at out + g * out_head.  red: LDS scratch of
-// 4 * 16 * NQ * (D/16 + 2) floats.  Called by a whole workgroup of 256 threads.
+// kPartWaves * 16 * NQ * (D/16 + 2) floats.  Called by a whole workgroup.
 template <typename T, int D, int NQ>
 __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const T* __restrict__ vbase, int r_begin,
                                              int r_end, const T* __restrict__ q0, float scale,
@@ -98,7 +156,7 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
   constexpr int EL = D / 16;
   constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int grp = tid >> 4, sub = tid & 15;           // 16 groups of 16 lanes
+  const int grp = tid >> 4, sub = tid & 15;           // groups of 16 lanes
   if (r_begin >= r_end) {
     if (tid < NQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
     return;
@@ -148,7 +206,7 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
   auto fetch = [&](int r0, Raw (&kk)[kUnr], Raw (&vq)[kUnr], bool (&okk)[kUnr]) {
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
-      const int r = r0 + u * 16 + grp;
+      const int r = r0 + u * (kPartThreads / 16) + grp;
       okk[u] = r < r_end;
       if (okk[u]) {
         kk[u].load(kbase + (size_t)r * D + sub * EL);
@@ -157,10 +215,10 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
     }
   };
   fetch(r_begin, kr, vr, ok);
-  for (int r0 = r_begin; r0 < r_end; r0 += 16 * kUnr) {
+  for (int r0 = r_begin; r0 < r_end; r0 += (kPartThreads / 16) * kUnr) {
     Raw kn[kUnr], vn[kUnr];
     bool okn[kUnr];
-    fetch(r0 + 16 * kUnr, kn, vn, okn);                    // nothing is loaded past r_end
+    fetch(r0 + (kPartThreads / 16) * kUnr, kn, vn, okn);                    // nothing is loaded past r_end
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
       float kv[EL], vv[EL];
@@ -201,63 +259,195 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) { kr[u] = kn[u]; vr[u] = vn[u]; ok[u] = okn[u]; }
   }
-  // merge the 4 groups of a wave, then the 4 waves through LDS (references back in natural-log units)
-#pragma unroll
-  for (int g = 0; g < NQ; ++g) {
-    m[g] *= kLn2;
-    for (int o = 16; o < 64; o <<= 1) {
-      const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
-      const float mn = fmaxf(m[g], mo);
-      const float ca = (m[g] == -INFINITY) ? 0.f : __expf(m[g] - mn);
-      const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
-      l[g] = l[g] * ca + lo * cb;
-#pragma unroll
-      for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], o, kWave) * cb;
-      m[g] = mn;
-    }
-    if (lane < 16) {
-      red[(wv * 16 + lane) * (NQ * PW) + g * PW] = m[g];
-      red[(wv * 16 + lane) * (NQ * PW) + g * PW + 1] = l[g];
-#pragma unroll
-      for (int e = 0; e < EL; ++e) red[(wv * 16 + lane) * (NQ * PW) + g * PW + 2 + e] = acc[g][e];
-    }
-  }
-  __syncthreads();
-  for (int pi = tid; pi < 16 * NQ; pi += kDecThreads) {
-    const int g = pi >> 4, ln = pi & 15;
-    float M = -INFINITY;
-    for (int x = 0; x < kDecThreads / kWave; ++x) M = fmaxf(M, red[(x * 16 + ln) * (NQ * PW) + g * PW]);
-    float L = 0.f, a[EL];
-#pragma unroll
-    for (int e = 0; e < EL; ++e) a[e] = 0.f;
-    for (int x = 0; x < kDecThreads / kWave; ++x) {
-      const float mx = red[(x * 16 + ln) * (NQ * PW) + g * PW];
-      const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
-      L += red[(x * 16 + ln) * (NQ * PW) + g * PW + 1] * cf;
-#pragma unroll
-      for (int e = 0; e < EL; ++e) a[e] += red[(x * 16 + ln) * (NQ * PW) + g * PW + 2 + e] * cf;
-    }
-    float* og = out + g * out_head;
-    if (ln == 0) { og[0] = M; og[1] = L; }
-#pragma unroll
-    for (int e = 0; e < EL; ++e) og[2 + ln * EL + e] = a[e];
-  }
+  merge_partials<D, NQ>(m, l, acc, out, out_head, red);
 }
 
-// grid (n_slots, Hs, B); block 256.  Selection head hs = blockIdx.y serves the GQ query
+// The same for bf16 rows of 128 elements and NQ > 1 queries, with q.k on the matrix cores.
+// A wave takes 16 rows per iteration (its 16-lane group kb the rows 4kb .. 4kb+3).  K rows go
+// from registers into a wave-private LDS tile and come back in MFMA operand order (lane
+// (n, kb) = 8 consecutive elements of row n), so that four 16x16x32 MFMAs against the queries
+// (operand B, columns >= NQ zero) leave S[row 4kb+i][query n] in lane (n, kb): the NQ*4 lanes
+// with n < NQ hold every score once, and only they do the softmax arithmetic.  Their terms p
+// return through LDS to the lanes that hold the V rows, which accumulate p.v on the vector ALU
+// as before.  The reference m[g] is common to the wave and lazy (raised only when a score
+// exceeds it by more than kSlack, decided by a wave-wide vote).  Against partial_rows this
+// removes, per (row, query), the dot products, the 16-lane reductions and 15 of the 16 copies
+// of the exponential.  tiles: LDS, kMfmaTileBytes per wave, then 256 bytes per query.
+constexpr int kMfmaTileBytes = 16 * 256 + 16 * 8 * 4;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 dec_bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float dec_f32x4_t;
+
+template <int NQ>
+__device__ __forceinline__ void partial_rows_mfma(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase,
+                                                  int r_begin, int r_end, const bf16_t* __restrict__ q0, float scale,
+                                                  float* __restrict__ out, size_t out_head, float* red,
+                                                  unsigned char* tiles) {
+  constexpr int D = 128, EL = 8;
+  constexpr float kLog2e = 1.4426950408889634f;
+  constexpr float kSlack = 8.f;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int kb = lane >> 4, n = lane & 15;            // group inside the wave; lane inside the group
+  if (r_begin >= r_end) {
+    if (tid < NQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
+    return;
+  }
+  unsigned char* kt = tiles + wv * kMfmaTileBytes;    // [16 rows][16 chunks of 16 B], chunk index xor row
+  float* pt = reinterpret_cast<float*>(kt + 16 * 256); // [16 rows][8 queries]: scores, then terms p
+  const bool holder = n < NQ;                         // this lane owns the scores of query n
+
+  // The queries sit in LDS (chunk index xor query, like the K tile) and are read as operand B
+  // of MFMA j (elements (4j + kb) * 8 .. + 7 of query n) every iteration: 4 registers instead of 16.
+  unsigned char* qt = tiles + kPartWaves * kMfmaTileBytes;       // [NQ][16 chunks of 16 B]
+  for (int ci = tid; ci < NQ * 16; ci += kPartThreads) {
+    const int g = ci >> 4, ch = ci & 15;
+    *reinterpret_cast<uint4*>(qt + g * 256 + ((ch ^ g) & 15) * 16) = *reinterpret_cast<const uint4*>(q0 + (size_t)g * D + ch * 8);
+  }
+  __syncthreads();
+  const float factor = scale * kLog2e;
+
+  float m[NQ], l[NQ], acc[NQ][EL];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    m[g] = -INFINITY;
+    l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EL; ++e) acc[g][e] = 0.f;
+  }
+  float m_mine = -INFINITY, l_mine = 0.f;             // holder lanes: reference and sum of query n over rows 4kb .. 4kb+3
+
+  // K rows are requested one iteration ahead (they are needed first, for the tile); V rows at the
+  // end of the iteration before, so that they travel while the next scores are formed.
+  using Raw = RawSlice<bf16_t, EL>;
+  Raw kn[4], vn[4];
+  bool okk[4], okv[4];
+  auto fetch_k = [&](int r0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = r0 + 16 * wv + 4 * kb + u;
+      okk[u] = r < r_end;                              // nothing is loaded past r_end
+      if (okk[u]) kn[u].load(kbase + (size_t)r * D + n * EL);
+    }
+  };
+  auto fetch_v = [&](int r0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = r0 + 16 * wv + 4 * kb + u;
+      okv[u] = r < r_end;
+      if (okv[u]) vn[u].load(vbase + (size_t)r * D + n * EL);
+    }
+  };
+  fetch_k(r_begin);
+  fetch_v(r_begin);
+  for (int r0 = r_begin; r0 < r_end; r0 += 16 * kPartWaves) {
+    // this iteration's K rows into the tile, the next ones requested
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = 4 * kb + u;
+      if (okk[u])
+        *reinterpret_cast<uint4*>(kt + row * 256 + ((n ^ row) & 15) * 16) = make_uint4(kn[u].w[0], kn[u].w[1], kn[u].w[2], kn[u].w[3]);
+    }
+    fetch_k(r0 + 16 * kPartWaves);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+    // S[row 4kb+i][query n] = sum over d; operand A of MFMA j: chunk 4j + kb of row n
+    dec_f32x4_t sv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4 a = *reinterpret_cast<const uint4*>(kt + n * 256 + (((4 * j + kb) ^ n) & 15) * 16);
+      uint4 bq = make_uint4(0, 0, 0, 0);               // columns >= NQ of operand B are zero
+      if (holder) bq = *reinterpret_cast<const uint4*>(qt + n * 256 + (((4 * j + kb) ^ n) & 15) * 16);
+      sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dec_bf16x8_t, a),
+                                                   __builtin_bit_cast(dec_bf16x8_t, bq), sv, 0, 0, 0);
+    }
+    float s2[4];
+    bool raise = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool valid = r0 + 16 * wv + 4 * kb + i < r_end;      // rows past the end hold stale tile data
+      s2[i] = valid ? sv[i] * factor : -INFINITY;
+      raise |= holder && s2[i] > m_mine + kSlack;
+    }
+    if (__any(raise)) {
+      // raise the references: every lane learns the largest score of each query over the 16 rows
+      if (holder) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pt[(4 * kb + i) * 8 + n] = s2[i];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      float mxs[8];
+#pragma unroll
+      for (int g = 0; g < 8; ++g) mxs[g] = -INFINITY;
+#pragma unroll 2
+      for (int x = 0; x < 16; ++x) {
+        float t[8];
+        *reinterpret_cast<float4*>(&t[0]) = *reinterpret_cast<const float4*>(pt + x * 8);
+        if constexpr (NQ > 4) *reinterpret_cast<float4*>(&t[4]) = *reinterpret_cast<const float4*>(pt + x * 8 + 4);
+#pragma unroll
+        for (int g = 0; g < NQ; ++g) mxs[g] = fmaxf(mxs[g], t[g]);
+      }
+#pragma unroll
+      for (int g = 0; g < NQ; ++g) {
+        const float mx = mxs[g];
+        const float m_new = fmaxf(m[g], mx);
+        const float corr = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m[g] - m_new);   // 0 while m[g] = -inf
+#pragma unroll
+        for (int e = 0; e < EL; ++e) acc[g][e] *= corr;
+        if (n == g) { l_mine *= corr; m_mine = m_new; }
+        m[g] = m_new;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      p[i] = (holder && s2[i] > -INFINITY) ? __builtin_amdgcn_exp2f(s2[i] - m_mine) : 0.f;
+      l_mine += p[i];
+    }
+    if (holder) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pt[(4 * kb + i) * 8 + n] = p[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (okv[u]) {
+        float pr[8];                                   // terms of row 4kb+u for every query
+        *reinterpret_cast<float4*>(&pr[0]) = *reinterpret_cast<const float4*>(pt + (4 * kb + u) * 8);
+        if constexpr (NQ > 4) *reinterpret_cast<float4*>(&pr[4]) = *reinterpret_cast<const float4*>(pt + (4 * kb + u) * 8 + 4);
+        float vv[EL];
+        vn[u].widen(vv);
+#pragma unroll
+        for (int g = 0; g < NQ; ++g) {
+#pragma unroll
+          for (int e = 0; e < EL; ++e) acc[g][e] = fmaf(pr[g], vv[e], acc[g][e]);
+        }
+      }
+    }
+    fetch_v(r0 + 16 * kPartWaves);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the tile and pt are rewritten by the next iteration
+  }
+  // the sum of query g over this group's rows sits in lane g of the group
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) l[g] = __shfl(l_mine, (lane & 48) + g, kWave);
+  merge_partials<D, NQ>(m, l, acc, out, out_head, red);
+}
+
+// grid (n_slots, Hs, B); block kPartThreads.  Selection head hs = blockIdx.y serves the GQ query
 // heads hs*GQ .. hs*GQ+GQ-1 (GQ = 1: one selection per query head).  Slots below g_slots are
 // chunks of the head's global region, the others chunks of the ring.  The ring belongs to the KV
 // head, so with GW > GQ (one selection per query head, GW = G heads per KV head) the workgroup
 // of the group's first head scores each ring row against all GW queries and the others skip it.
 template <typename T, int D, int GQ, int GW>
-__global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
+__global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
   constexpr int EL = D / 16;
   constexpr int CH = kChunk;                          // rows per slot (256 and 2048 measured no better with GQ = 4)
   constexpr int NMAX = GQ > GW ? GQ : GW;
-  __shared__ float red[(kDecThreads / kWave) * 16 * NMAX * (EL + 2)];
-  const int tid = threadIdx.x;
+  __shared__ float red[kPartWaves * 16 * NMAX * (EL + 2)];
+  constexpr bool kMfma = sizeof(T) == 2 && D == 128;   // rows that partial_rows_mfma takes
+  __shared__ __attribute__((aligned(16))) unsigned char tiles[kMfma && NMAX > 1 ? kPartWaves * kMfmaTileBytes + NMAX * 256 : 16];
   const int slot = blockIdx.x, hs = blockIdx.y, s = blockIdx.z;
   const int Hs = Hq / GQ, h0 = hs * GQ, kvh = h0 / (Hq / Hkv);
   float* out = part + (((size_t)s * Hq + h0) * n_slots + slot) * (D + 2);   // head h0 + g: + g * n_slots * (D+2)
@@ -270,8 +460,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const int r_begin = slot * CH;
     const int r_end = min(nv, r_begin + CH);
     const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
-    partial_rows<T, D, GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
-                           out_head, red);
+    if constexpr (kMfma && GQ > 1)
+      partial_rows_mfma<GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
+                            out_head, red, tiles);
+    else
+      partial_rows<T, D, GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
+                             out_head, red);
   } else {
     if (GW != GQ && h0 % GW != 0) return;              // this head's ring partial is written by the group's first head
     // Slot r of the ring holds the latest position congruent to r mod w that is <= Tpos.  Once
@@ -280,8 +474,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(
     const int r_begin = (slot - g_slots) * CH;
     const int r_end = min(filled, r_begin + CH);
     const size_t base = ((size_t)s * Hkv + kvh) * w;
-    partial_rows<T, D, GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale, out,
-                           out_head, red);
+    if constexpr (kMfma && GW > 1)
+      partial_rows_mfma<GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale,
+                            out, out_head, red, tiles);
+    else
+      partial_rows<T, D, GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale,
+                             out, out_head, red);
   }
 }
 
@@ -478,10 +676,10 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
 #define TCA_PARTIAL_CASE(GG)                                                                                    \
   case GG:                                                                                                      \
     if (GS > 1)                                                                                                 \
-      hipLaunchKernelGGL((decode_partial_kernel<T, D, GG, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st, \
+      hipLaunchKernelGGL((decode_partial_kernel<T, D, GG, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
                          *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
     else                                                                                                        \
-      hipLaunchKernelGGL((decode_partial_kernel<T, D, 1, GG>), dim3(n_slots, Hs, B), dim3(kDecThreads), 0, st,  \
+      hipLaunchKernelGGL((decode_partial_kernel<T, D, 1, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
                          *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
     break;
   switch (G) {

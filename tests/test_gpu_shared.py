@@ -417,3 +417,59 @@ def test_shared_mixed_batch_and_graph_replay(mods):
         torch.cuda.synchronize()
         assert torch.equal(O_graph, O_eager), f"replay {rep}"
         assert all(torch.equal(a, t) for a, t in zip(after, (c.idx, c.n_rows, c.length)))
+
+
+@pytest.mark.parametrize("share", [False, True], ids=["per_head", "shared"])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128)])
+def test_decode_with_rising_and_falling_logits(mods, share, dtype, d):
+    """One decode step over a hand-filled cache whose key magnitudes ramp up, then down, along the
+    stored rows, so that the split-K kernels raise their softmax reference many times (and then
+    stop raising it) inside one slot, in several slots and in the ring."""
+    tb, bufs, _ = mods
+    Hq, Hkv, b, w, T0 = 8, 2, 16, 256, 6000
+    G = Hq // Hkv
+    Hs = Hkv if share else Hq
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype, share=share)
+    P_gpu, _ = configs(tb, b, [0.5] * Hs)
+    rng = np.random.default_rng(211)
+    n_glob = rng.integers(1500, 3500, size=Hs)
+    cache = bufs.DecodeCache(prm, 1, n_glob + 64)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    T = T0 + 3                                              # no block completes at this step
+    idx_h, Kg_h, Vg_h = [], [], []
+    for n_ in range(Hs):
+        n = int(n_glob[n_])
+        pos = np.sort(rng.choice(T0 - w, size=n, replace=False)).astype(np.int32)
+        ramp = np.concatenate([np.linspace(0.05, 4.0, n // 2), np.linspace(4.0, 0.05, n - n // 2)])[:, None]
+        Kg = torch.from_numpy(rng.standard_normal((n, d)) * ramp).to(dt)
+        Vg = torch.from_numpy(rng.standard_normal((n, d))).to(dt)
+        o = int(cache.offs[n_])
+        cache.idx[0, o:o + n] = torch.from_numpy(pos).cuda()
+        cache.Kg[0, o:o + n] = Kg.cuda()
+        cache.Vg[0, o:o + n] = Vg.cuda()
+        idx_h.append(pos.astype(np.int64)); Kg_h.append(Kg.double().numpy()); Vg_h.append(Vg.double().numpy())
+    cache.n_rows.copy_(torch.from_numpy(n_glob.astype(np.int32))[None])
+    ramp_w = np.linspace(0.05, 3.0, w)[None, :, None]
+    ringK = torch.from_numpy(rng.standard_normal((Hkv, w, d)) * ramp_w).to(dt)
+    ringV = torch.from_numpy(rng.standard_normal((Hkv, w, d))).to(dt)
+    cache.ringK[0] = ringK.cuda(); cache.ringV[0] = ringV.cuda()
+    cache.length.fill_(T)
+    q = torch.from_numpy(2.0 * rng.standard_normal((1, Hq, d))).to(dt).cuda()
+    kn = torch.from_numpy(rng.standard_normal((1, Hkv, d))).to(dt).cuda()
+    vn = torch.from_numpy(rng.standard_normal((1, Hkv, d))).to(dt).cuda()
+    O = torch.full((1, Hq, d), float("nan"), dtype=dt, device="cuda")
+    ws = bufs.workspace(tb.tca_decode_workspace_bytes(prm, 1, cache.max_head_rows))
+    tb.tca_decode(prm, cache.view, cache.offs, q, kn, vn, P_gpu, O, ws)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for h in range(Hq):
+        g, n_ = h // G, (h // G if share else h)
+        Kfull = np.zeros((T + 1, d)); Vfull = np.zeros((T + 1, d))
+        Kfull[idx_h[n_]] = Kg_h[n_]; Vfull[idx_h[n_]] = Vg_h[n_]
+        for p in range(T - w + 1, T):
+            Kfull[p] = ringK[g, p % w].double().numpy(); Vfull[p] = ringV[g, p % w].double().numpy()
+        Kfull[T] = kn[0, g].double().cpu().numpy(); Vfull[T] = vn[0, g].double().cpu().numpy()
+        ref = orc.attention_row(q[0, h].double().cpu().numpy(), T, Kfull, Vfull, idx_h[n_], w)
+        worst = max(worst, float(np.abs(ref - O[0, h].double().cpu().numpy()).max()))
+    print("max abs err", worst, flush=True)
+    assert worst <= H.TOL[dtype]
