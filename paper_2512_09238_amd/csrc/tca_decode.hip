@@ -4,7 +4,7 @@
 // One step = four launches on the caller's stream:
 //   prep    : write the new K/V row into the ring; per head, count the global
 //             rows that have left the window (idx <= T-w; idx is ascending so
-//             this is a prefix).
+//             this is a prefix, found by a 64-way search of one wave).
 //   partial : split-K attention.  grid (slot, selection head, sequence); a slot is
 //             a chunk of kChunk rows of the head's global region or of the ring.
 //             The 256 threads form sixteen 16-lane groups, each streaming whole
@@ -58,35 +58,56 @@ static DecodeWs carve_decode_ws(void* ws, int B, int Hq, int D, int n_slots) {
 static int window_slots(int w) { return (w + kChunk - 1) / kChunk; }
 static int global_slots(int64_t max_head_rows) { return (int)((max_head_rows + kChunk - 1) / kChunk); }
 
-__device__ __forceinline__ int count_le_dev(const int32_t* idx, int n, int64_t bound) {
-  int lo = 0, hi = n;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if ((int64_t)idx[mid] <= bound) lo = mid + 1; else hi = mid;
+// Number of entries <= bound among the ascending idx[0..n), found by a whole wave: every
+// round probes the last element of up to 64 equal chunks of the open range, so 2^18 rows take
+// three dependent loads instead of eighteen.  Result in every lane.
+__device__ __forceinline__ int count_le_wave(const int32_t* __restrict__ idx, int n, int64_t bound) {
+  const int lane = threadIdx.x & 63;
+  int lo = 0, hi = n;                       // the count lies in [lo, hi]
+  while (hi - lo > 64) {
+    const int len = hi - lo;
+    const int step = (len + 63) / 64;
+    const bool has = lane * step < len;     // lane's chunk: [lo + lane*step, lo + min((lane+1)*step, len))
+    const int last = lo + min((lane + 1) * step, len) - 1;
+    const bool le = has && (int64_t)idx[last] <= bound;
+    const int c = __popcll(__ballot(le));   // chunks that lie entirely at or below the bound (a prefix of them)
+    const int nch = (len + step - 1) / step;
+    if (c == nch) { lo = hi; break; }
+    const int lo2 = lo + c * step;
+    hi = lo + min((c + 1) * step, len) - 1; // the last element of chunk c is above the bound
+    lo = lo2;
+  }
+  if (hi > lo) {
+    const bool le = lane < hi - lo && (int64_t)idx[lo + lane] <= bound;
+    lo += __popcll(__ballot(le));
   }
   return lo;
 }
 
-// grid (B); block 256
+// grid (B, ceil(Hs/4)); block 256: one wave per selection head; the workgroups with blockIdx.y = 0
+// also write the new row into the ring
 template <typename T>
-__global__ void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv, int D, int w,
-                                   const T* __restrict__ k_new, const T* __restrict__ v_new,
-                                   int32_t* __restrict__ n_vis) {
+__global__ __launch_bounds__(256) void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv, int D, int w,
+                                                          const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                                          int32_t* __restrict__ n_vis) {
   const int s = blockIdx.x;
   const int64_t Tpos = c.length[s];
-  const int slot = (int)(Tpos % w);
-  T* rk = (T*)c.ringK;
-  T* rv = (T*)c.ringV;
-  for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
-    const int kvh = e / D, dd = e - kvh * D;
-    const size_t dst = (((size_t)s * Hkv + kvh) * w + slot) * D + dd;
-    rk[dst] = k_new[(size_t)s * Hkv * D + e];
-    rv[dst] = v_new[(size_t)s * Hkv * D + e];
+  if (blockIdx.y == 0) {
+    const int slot = (int)(Tpos % w);
+    T* rk = (T*)c.ringK;
+    T* rv = (T*)c.ringV;
+    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+      const int kvh = e / D, dd = e - kvh * D;
+      const size_t dst = (((size_t)s * Hkv + kvh) * w + slot) * D + dd;
+      rk[dst] = k_new[(size_t)s * Hkv * D + e];
+      rv[dst] = v_new[(size_t)s * Hkv * D + e];
+    }
   }
-  for (int h = threadIdx.x; h < Hs; h += blockDim.x) {
-    const int32_t* ix = c.idx + (size_t)s * c.cap_rows + dh.offs[h];
-    n_vis[s * Hs + h] = count_le_dev(ix, c.n_rows[s * Hs + h], Tpos - w);
-  }
+  const int h = blockIdx.y * 4 + (threadIdx.x >> 6);
+  if (h >= Hs) return;
+  const int32_t* ix = c.idx + (size_t)s * c.cap_rows + dh.offs[h];
+  const int nv = count_le_wave(ix, c.n_rows[s * Hs + h], Tpos - w);
+  if ((threadIdx.x & 63) == 0) n_vis[s * Hs + h] = nv;
 }
 
 // Tail of the split-K kernels: every 16-lane group of the workgroup holds, for each of NQ
@@ -665,8 +686,8 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
   const int Hs = sel_heads(prm), GS = sel_group(prm);
   const int g_slots = global_slots(max_rows), n_slots = g_slots + window_slots(w);
   DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
-  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new, v_new,
-                     dw.n_vis);
+  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B, (Hs + 3) / 4), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new,
+                     v_new, dw.n_vis);
   const float sc = (float)logit_scale(prm);
   // (queries per region row, queries per ring row): (G, G) for a shared selection, else (1, G)
   const int G = Hq / Hkv;
