@@ -172,8 +172,7 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
                                              int r_end, const T* __restrict__ q0, float scale,
                                              float* __restrict__ out, size_t out_head, float* red) {
   constexpr int EL = D / 16;
-  constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x;
   const int grp = tid >> 4, sub = tid & 15;           // groups of 16 lanes
   if (r_begin >= r_end) {
     if (tid < NQ) { out[tid * out_head] = -INFINITY; out[tid * out_head + 1] = 0.f; }
@@ -184,7 +183,7 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
   // bf16 storage: q.k over a lane's slice is EL/2 two-element bf16 dot products with fp32
   // accumulation straight from the loaded words, and the factor is applied to the row's sum;
   // fp32 storage: the factor is folded into the query.
-  constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+  constexpr float kLog2e = 1.4426950408889634f;
   constexpr bool kDot2 = sizeof(T) == 2;
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   const float qk_factor = kDot2 ? scale * kLog2e : 1.f;
