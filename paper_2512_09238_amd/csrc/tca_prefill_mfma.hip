@@ -202,7 +202,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const int hh = lane >> 5, c = lane & 31;
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   const int bid = blockIdx.x;
-  const int h = bid % Hq;
+  // Workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own.  With Hq a multiple
+  // of 8, XCD x is given the heads x*Hq/8 .. (x+1)*Hq/8 - 1, so that the query heads of a KV group
+  // stream their shared dense tiles (and, with a shared selection, all their tiles) through one L2.
+  const int hj = bid % Hq;
+  const int h = (Hq & 7) == 0 ? (hj & 7) * (Hq >> 3) + (hj >> 3) : hj;
   const int qtile = n_qt - 1 - bid / Hq;           // longest tiles first
   const int kvh = h / G;
   const int64_t r0 = (int64_t)qtile * BM;          // first query row of the workgroup
