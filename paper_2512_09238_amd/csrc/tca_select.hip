@@ -451,7 +451,10 @@ __global__ __launch_bounds__(kAssignThreads) void assign_kernel(
 // offsets of the heads' regions travel in the kernel's argument block: no copy, no extra launch
 struct OffsArgs { int64_t offs[TCA_MAX_HEADS + 1]; };
 
-// grid (n_blocks, selection heads); block 256.  G: selection heads per KV head.
+// grid (n_blocks * selection heads); block 256.  G: selection heads per KV head.
+// Workgroup ids go round-robin over the 8 XCDs.  The G selection heads of a KV head keep
+// overlapping subsets of the same block's rows, so their workgroups are given ids 8 apart:
+// same XCD, consecutive in time, and the rows a later one needs are mostly in that L2 already.
 template <typename T, int D>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const T* __restrict__ K, const T* __restrict__ V, int64_t kv_stride, int64_t pos0, int b,
@@ -466,8 +469,22 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   __shared__ __attribute__((aligned(16))) uint64_t bkeys[256];
   __shared__ int32_t rank[256];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int64_t j = blockIdx.x;
-  const int h = blockIdx.y, kvh = h / G;
+  int64_t j;
+  int h, kvh;
+  {
+    const int64_t id = blockIdx.x, pairs = (int64_t)gridDim.x / G;       // pairs = n_blocks * KV heads
+    if ((pairs & 7) == 0) {
+      const int64_t u = id >> 3;                                         // position in the XCD's own sequence
+      const int64_t pair = (u / G) * 8 + (id & 7);
+      kvh = (int)(pair / n_blocks);
+      j = pair - (int64_t)kvh * n_blocks;
+      h = kvh * G + (int)(u % G);
+    } else {
+      h = (int)(id / n_blocks);
+      j = id - (int64_t)h * n_blocks;
+      kvh = h / G;
+    }
+  }
   const int t = blk_t[(size_t)h * n_blocks + j];
   const int64_t base = oa.offs[h], cap = oa.offs[h + 1] - base;
   const int64_t dst0 = blk_dst[(size_t)h * n_blocks + j];
@@ -636,7 +653,7 @@ static int run_select(const tca_params* prm, const T* q_last, const T* K, const 
   int64_t cap[TCA_MAX_HEADS];
   for (int h = 0; h < Hs; ++h) cap[h] = offs[h + 1] - offs[h];
   select_assign_stage(prm, n_tokens, p, cap, w.sel_stats, n_rows, w.blk_t, w.blk_dst, st);
-  hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)nb, Hs), dim3(kGatherThreads), 0, st, K, V,
+  hipLaunchKernelGGL((gather_kernel<T, D>), dim3((unsigned)(nb * Hs)), dim3(kGatherThreads), 0, st, K, V,
                      kv_stride, pos0, b, nb, Hs / Hkv, w.keys, w.blk_t, w.blk_dst, oa, idx, Kg, Vg);
   return TCA_OK;
 }
