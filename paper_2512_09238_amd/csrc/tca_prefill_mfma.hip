@@ -203,11 +203,19 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const int n_qt = (int)((n_queries + BM - 1) / BM);
   const int bid = blockIdx.x;
   // Workgroup ids go round-robin over the 8 XCDs, each with an L2 of its own.  With Hq a multiple
-  // of 8, XCD x is given the heads x*Hq/8 .. (x+1)*Hq/8 - 1, so that the query heads of a KV group
-  // stream their shared dense tiles (and, with a shared selection, all their tiles) through one L2.
-  const int hj = bid % Hq;
-  const int h = (Hq & 7) == 0 ? (hj & 7) * (Hq >> 3) + (hj >> 3) : hj;
-  const int qtile = n_qt - 1 - bid / Hq;           // longest tiles first
+  // of 8, XCD x is given the heads x*Hq/8 .. (x+1)*Hq/8 - 1 and works through them one at a time:
+  // the query tiles in flight on an XCD then belong to one head and stream the same K / V^T tiles
+  // through its L2 (and the heads of a KV group, which share the dense tiles - with a shared
+  // selection all tiles - follow each other on the same XCD).
+  int h, qtile;
+  if ((Hq & 7) == 0) {
+    const int u = bid >> 3;                        // position in the XCD's own sequence
+    h = (bid & 7) * (Hq >> 3) + u / n_qt;          // one head at a time per XCD
+    qtile = n_qt - 1 - u % n_qt;                   // longest tiles first
+  } else {
+    h = bid % Hq;
+    qtile = n_qt - 1 - bid / Hq;
+  }
   const int kvh = h / G;
   const int64_t r0 = (int64_t)qtile * BM;          // first query row of the workgroup
   const int64_t last_row = n_queries - 1;
