@@ -516,9 +516,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   const float* pp = part + ((size_t)s * Hq + h) * n_slots * (D + 2);
 
   // log-sum-exp merge of the head's partials: slot weights first (one thread per
-  // slot), then every thread sums one output column over a share of the slots
+  // slot), then every thread sums four output columns over a share of the slots
   __shared__ float wgt[kMaxSlots];
-  __shared__ float colsum[kDecThreads];
+  __shared__ float colsum[kDecThreads / (D / 4)][D];
   __shared__ float lsum[kDecThreads / kWave];
   {
     float M = -INFINITY;
@@ -540,19 +540,26 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
     if (lane == 0) lsum[wv] = lpart;
     __syncthreads();
     const float L = (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
-    constexpr int SPLIT = kDecThreads / D;               // threads per output column
-    const int col = tid % D, part = tid / D;
-    float a = 0.f;
+    constexpr int CQ = D / 4;                            // column quads of a partial
+    constexpr int SPLIT = kDecThreads / CQ;              // threads per column quad
+    const int cq = tid % CQ, part = tid / CQ;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
     for (int x = part; x < n_slots; x += SPLIT) {
       const float wx = wgt[x];                           // an empty slot's columns were never written
-      if (wx != 0.f) a += pp[(size_t)x * (D + 2) + 2 + col] * wx;
+      if (wx != 0.f) {
+        const float* src = pp + (size_t)x * (D + 2) + 2 + 4 * cq;      // 8-byte aligned
+        const float2 lo = *reinterpret_cast<const float2*>(src), hi = *reinterpret_cast<const float2*>(src + 2);
+        a0 += lo.x * wx; a1 += lo.y * wx; a2 += hi.x * wx; a3 += hi.y * wx;
+      }
     }
-    colsum[tid] = a;
+    colsum[part][4 * cq] = a0; colsum[part][4 * cq + 1] = a1;
+    colsum[part][4 * cq + 2] = a2; colsum[part][4 * cq + 3] = a3;
     __syncthreads();
     if (tid < D) {
       float t = 0.f;
 #pragma unroll
-      for (int q2 = 0; q2 < SPLIT; ++q2) t += colsum[q2 * D + tid];
+      for (int q2 = 0; q2 < SPLIT; ++q2) t += colsum[q2][tid];
       store_f32(O + ((size_t)s * Hq + h) * D + tid, t / L);
     }
   }
