@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per launch of prefill_mfma_kernel on the default workload, from the rocprofv3
 # --pmc runs summarised in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB)
-PROFILED_PREFILL_TRAFFIC_BYTES = (7.0137e6 * 2.0 + 1.0496e6) * 1024
+PROFILED_PREFILL_TRAFFIC_BYTES = (7.0188e6 * 2.0 + 1.0496e6) * 1024
 
 
 def log(*a):
