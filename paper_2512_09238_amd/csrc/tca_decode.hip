@@ -31,6 +31,7 @@ namespace tca {
 constexpr int kPartThreads = 256;                 // threads of a split-K workgroup (64 with 256-row slots measured 8-14 % slower)
 constexpr int kPartWaves = kPartThreads / 64;
 constexpr int kChunk = 4 * kPartThreads;          // rows per split-K slot: 64 per 16-lane group
+constexpr int kChunkShared = 2048;                // the same when every row is scored against a group of queries (1024: 507, 2048: 480, 4096: 540 us per step)
 constexpr int kDecThreads = 256;                  // the other kernels
 constexpr int kMaxSlots = 4096;       // split-K slots per head the merge kernel can weigh (4M rows per head)
 
@@ -55,8 +56,11 @@ static DecodeWs carve_decode_ws(void* ws, int B, int Hq, int D, int n_slots) {
   return w;
 }
 
-static int window_slots(int w) { return (w + kChunk - 1) / kChunk; }
-static int global_slots(int64_t max_head_rows) { return (int)((max_head_rows + kChunk - 1) / kChunk); }
+static int chunk_rows(const tca_params* prm) { return sel_group(prm) > 1 ? kChunkShared : kChunk; }
+static int window_slots(const tca_params* prm) { return (prm->window + chunk_rows(prm) - 1) / chunk_rows(prm); }
+static int global_slots(const tca_params* prm, int64_t max_head_rows) {
+  return (int)((max_head_rows + chunk_rows(prm) - 1) / chunk_rows(prm));
+}
 
 // Number of entries <= bound among the ascending idx[0..n), found by a whole wave: every
 // round probes the last element of up to 64 equal chunks of the open range, so 2^18 rows take
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
   constexpr int EL = D / 16;
-  constexpr int CH = kChunk;                          // rows per slot (256 and 2048 measured no better with GQ = 4)
+  constexpr int CH = GQ > 1 ? kChunkShared : kChunk;  // rows per slot
   constexpr int NMAX = GQ > GW ? GQ : GW;
   __shared__ float red[kPartWaves * 16 * NMAX * (EL + 2)];
   constexpr bool kMfma = sizeof(T) == 2 && D == 128;   // rows that partial_rows_mfma takes
@@ -690,7 +694,7 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
                       const T* q, const T* k_new, const T* v_new, T* O, void* ws, hipStream_t st) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, B = c->batch, w = prm->window;
   const int Hs = sel_heads(prm), GS = sel_group(prm);
-  const int g_slots = global_slots(max_rows), n_slots = g_slots + window_slots(w);
+  const int g_slots = global_slots(prm, max_rows), n_slots = g_slots + window_slots(prm);
   DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
   hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B, (Hs + 3) / 4), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new,
                      v_new, dw.n_vis);
@@ -723,7 +727,7 @@ using namespace tca;
 
 extern "C" size_t tca_decode_workspace_bytes(const tca_params* prm, int batch, int64_t max_head_rows) {
   if (check_params(prm) != TCA_OK || batch < 1 || max_head_rows < 0) return 0;
-  const int n_slots = global_slots(max_head_rows) + window_slots(prm->window);
+  const int n_slots = global_slots(prm, max_head_rows) + window_slots(prm);
   return carve_decode_ws(nullptr, batch, prm->n_q_heads, prm->head_dim, n_slots).bytes;
 }
 
@@ -774,7 +778,7 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
     dh.t_dec[h] = tca_decode_budget(b, p + (size_t)h * nk);
   }
   dh.offs[Hs] = offs[Hs];
-  if (global_slots(max_rows) + window_slots(prm->window) > kMaxSlots)
+  if (global_slots(prm, max_rows) + window_slots(prm) > kMaxSlots)
     return fail(TCA_ERR_UNSUPPORTED, "tca_decode: more than %d split-K slots per head", kMaxSlots);
   const size_t need = tca_decode_workspace_bytes(prm, cache->batch, max_rows);
   if (ws_bytes < need || ((uintptr_t)ws & 255))
