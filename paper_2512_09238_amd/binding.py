@@ -26,6 +26,12 @@ if not os.path.exists(LIB_PATH):
         f"{LIB_PATH} is missing: build it with `python -m paper_2512_09238_amd.build` "
         "(or __graft_entry__.build()).  There is no fallback path."
     )
+# torch is imported before the library is loaded: the process must hold ONE HIP runtime, and
+# torch ships its own copy.  Loaded in this order, libtca.so binds to the runtime torch has
+# already mapped, so that streams and device pointers mean the same thing on both sides;
+# loaded first, it would pull in a second runtime that does not see torch's device context.
+import torch  # noqa: E402,F401
+
 lib = C.CDLL(LIB_PATH)
 
 
@@ -111,7 +117,6 @@ def _host(a, dtype):
 def _stream(stream):
     if stream is not None:
         return C.c_void_p(int(stream))
-    import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
@@ -251,7 +256,6 @@ def tca_probe_mfma(random_operands: bool, iters: int, ws, stream=None):
 def prefill_shader_clock_ghz(ws) -> float:
     """Average shader clock during the last completed bf16 tca_prefill that used `ws`
     (a torch uint8 tensor): its first two uint64 are cycle and 100 MHz tick sums."""
-    import torch
     torch.cuda.synchronize()
     c = ws[:16].view(torch.int64).cpu().numpy()
     return float(c[0]) / (float(c[1]) * 10.0) if c[1] else 0.0

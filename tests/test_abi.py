@@ -102,3 +102,14 @@ def test_probe_rejects_bad_arguments_without_a_gpu():
     assert rc == tb.TCA_ERR_INVALID
     rc = tb.lib.tca_probe_mfma(1, 100, ctypes.byref(tf), ctypes.byref(ghz), ctypes.c_void_p(256), 16, None)
     assert rc == tb.TCA_ERR_WORKSPACE
+
+
+def test_binding_loads_torch_before_the_library():
+    """One HIP runtime per process: the binding imports torch (which ships its own copy) before it
+    loads libtca.so, whatever the caller imported first."""
+    import subprocess
+    import sys
+    code = ("import sys; import paper_2512_09238_amd.binding as tb; "
+            "assert 'torch' in sys.modules; print(tb.tca_num_counts(128))")
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip() == "8", r.stderr[-500:]
