@@ -360,3 +360,35 @@ def test_calibrate_budgets_matches_oracle(tb, bufs, case):
                 assert bool(got["fallback"][h]) == ref[h].fallback
                 np.testing.assert_allclose(got["p_star"][h], ref[h].p, rtol=1e-12, atol=1e-15)
     assert np.all(tb.tca_calibrate_budgets(prm, Qd, Kd, L, M, 1.0, 1e9, ws)["fallback"] == 1)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_large_logits_do_not_overflow(tb, bufs, dtype):
+    """Queries scaled by 40: logits in the hundreds, softmax mass on a few keys, most scores
+    underflow.  Selection, prefill and a decode step still match the oracle (no inf, no NaN)."""
+    Hq, Hkv, d, L, b, w = 4, 2, 128, 900, 32, 128
+    x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, dtype, 301)
+    if dtype == "bf16":
+        q = wl.to_f64(x["Q"]) * 40.0
+        x["Q"] = bufs.to_device(q.astype(np.float32), "cpu").to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    else:
+        x["Q"] = (x["Q"] * 40.0).astype(np.float32)
+    P_gpu, P_orc = budgets_to_configs(tb, b, [0.1, 0.3, 0.5, 0.7])
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    O = torch.full_like(Qd, float("nan"))
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+    torch.cuda.synchronize()
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    assert np.abs(Kf[0] @ Qf[0, L - 1]).max() / np.sqrt(d) > 100.0          # the case is what it claims to be
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    for h in range(Hq):
+        got = H.head_indices(gb, h)
+        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+            Oref[h] = orc.tca_attention(Qf[h], Kf[h // 2], Vf[h // 2], got, w)
+    Og = bufs.to_host_f64(O)
+    assert np.isfinite(Og).all()
+    # with the mass on single keys a one-ulp bf16 difference in a logit moves weight between keys:
+    # the bound stays the storage tolerance, scaled by the value range
+    assert np.abs(Og - Oref).max() <= H.TOL[dtype] * max(1.0, np.abs(Vf).max())
