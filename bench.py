@@ -292,6 +292,8 @@ def main():
     ap.add_argument("--calibrate", action="store_true", default=True)
     ap.add_argument("--no-calibrate", dest="calibrate", action="store_false")
     ap.add_argument("--mixed", action="store_true", help="also time the config-5 ragged mixed batch (adds about a minute)")
+    ap.add_argument("--prefill-variant", type=int, default=0,
+                    help="workgroup shape of the bf16 prefill kernel (tca_diag_prefill_variant): 0 = automatic")
     ap.add_argument("--shared", action="store_true",
                     help="also time both workloads with one selection per KV head (tca_params.share), reported in 'shared_selection'")
     args = ap.parse_args()
@@ -306,6 +308,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
+    tb.tca_diag_prefill_clocks(True)             # the attention kernel's shader clock is part of the report
+    tb.tca_diag_prefill_variant(args.prefill_variant)
     log(f"[bench] device {props.name}: {props.multi_processor_count} CUs")
 
     if args.copy_probe:

@@ -31,8 +31,8 @@
  *     rows_out, the regions of idx / Kg / Vg) has one entry per selection head.
  *   - Compacted global subset: idx / Kg / Vg hold, for selection head n, rows
  *     offs[n] .. offs[n] + n_rows[n] - 1 of a flat buffer (offs = capacity prefix
- *     sums, host array of Hs+1 entries; App. C "flatten all head tokens
- *     into a single contiguous buffer and precompute offsets").  idx is the
+ *     sums, host array of Hs+1 entries; the heads' rows share one flat buffer
+ *     addressed through precomputed offsets, the layout of App. C).  idx is the
  *     absolute token position of each row, ascending within a head.
  *   - Positions are 0-based.  The local subset of the query at position i is the
  *     window (i-w, i]; a global row at position j is visible to it iff j <= i-w,
@@ -257,22 +257,6 @@ int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, const void* K
                           int M, double sigma, double tau,
                           double* p_star, int32_t* cand_idx, double* a_out, int64_t* n_out,
                           int32_t* fallback, void* ws, size_t ws_bytes, void* stream);
-
-/* Diagnostics (not steps of the method).
- *
- * tca_probe_mfma times a register-only loop of bf16 32x32x16 MFMAs that fills every SIMD
- * (`iters` x 16 MFMAs per wave) and reports the rate it reached and the shader clock it ran at
- * (cycle counter over the constant 100 MHz counter).  random_operands != 0 gives the operands
- * random signs and magnitudes, 0 makes them constants; the difference is the board's power
- * limit, which bounds what any MFMA kernel on real data can reach.  ws: device scratch of
- * tca_probe_workspace_bytes() bytes.  Synchronises the stream.
- *
- * After a TCA_BF16 tca_prefill call has completed, the first two uint64 of its workspace hold
- * the sum over workgroups of elapsed shader-clock cycles and of elapsed 100 MHz ticks; their
- * ratio / 10 is the average shader clock in GHz during the attention kernel. */
-size_t tca_probe_workspace_bytes(void);
-int tca_probe_mfma(int random_operands, int iters, double* tflops, double* shader_ghz,
-                   void* ws, size_t ws_bytes, void* stream);
 
 const char* tca_strerror(int code);
 const char* tca_last_error(void);

@@ -1,7 +1,7 @@
 """ctypes binding of libtca.so: argument marshalling only.
 
 Every function has the name and the argument order of its C declaration in
-include/tca.h.  Device arrays are torch CUDA tensors (used for memory and
+include/tca.h (diagnostics: include/tca_diag.h).  Device arrays are torch CUDA tensors (used for memory and
 streams only); host arrays are numpy.  Nothing here computes any step of the
 method, and there is no CPU fallback: if the library is missing, importing
 this module raises.
@@ -81,6 +81,8 @@ EXPORTS = {
     "tca_calibrate_budgets": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                         C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_diag_prefill_clocks": (None, [C.c_int]),
+    "tca_diag_prefill_variant": (C.c_int, [C.c_int]),
     "tca_strerror": (C.c_char_p, [C.c_int]),
     "tca_last_error": (C.c_char_p, []),
 }
@@ -253,9 +255,18 @@ def tca_probe_mfma(random_operands: bool, iters: int, ws, stream=None):
     return tf.value, ghz.value
 
 
+def tca_diag_prefill_clocks(enable: bool) -> None:
+    lib.tca_diag_prefill_clocks(int(bool(enable)))
+
+
+def tca_diag_prefill_variant(variant: int) -> None:
+    _check(lib.tca_diag_prefill_variant(int(variant)))
+
+
 def prefill_shader_clock_ghz(ws) -> float:
     """Average shader clock during the last completed bf16 tca_prefill that used `ws`
-    (a torch uint8 tensor): its first two uint64 are cycle and 100 MHz tick sums."""
+    (a torch uint8 tensor) while tca_diag_prefill_clocks was on: its first two uint64 are
+    cycle and 100 MHz tick sums."""
     torch.cuda.synchronize()
     c = ws[:16].view(torch.int64).cpu().numpy()
     return float(c[0]) / (float(c[1]) * 10.0) if c[1] else 0.0

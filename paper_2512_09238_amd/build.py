@@ -20,7 +20,7 @@ SOURCES = [
     "tca_prefill_mfma.hip",
     "tca_decode.hip",
     "tca_calibrate.hip",
-    "tca_probe.hip",
+    "tca_diag.hip",
 ]
 
 FLAGS = [
@@ -35,7 +35,7 @@ FLAGS = [
 # rows go through -inf, and the one inf - inf is discarded by a select), so its maxima
 # need no quieting moves.
 FILE_FLAGS = {
-    "tca_prefill_mfma.hip": ["-fno-honor-nans"],
+    "tca_prefill_mfma.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -29,6 +29,11 @@ bool valid_config(const double* p, int nk);
 // Eq. 7 counts; the deficit goes to the k=1 group.
 void psi_counts(int nk, int64_t m, const double* p, int64_t* c);
 
+// Diagnostics switches (tca_diag.h): whether tca_prefill records its shader clock, and which
+// workgroup shape the bf16 prefill kernel takes (0 = chosen by the call's size).
+bool diag_prefill_clocks();
+int prefill_variant();
+
 inline double logit_scale(const tca_params* prm) {
   return prm->scale != 0.0 ? prm->scale : 1.0 / __builtin_sqrt((double)prm->head_dim);
 }

@@ -23,6 +23,8 @@
 //   advance : length += 1.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "tca_common.h"
 #include "tca_device.h"
 
@@ -117,22 +119,21 @@ __global__ __launch_bounds__(256) void decode_prep_kernel(tca_cache c, DecodeHea
 // Tail of the split-K kernels: every 16-lane group of the workgroup holds, for each of NQ
 // queries, an online-softmax state (reference m in base-2 units, sum l, acc over the lane's
 // slice of d).  Merges the 4 groups of each wave, then the 4 waves through LDS, and writes one
-// (max, sum, acc[D]) partial per query at out + g * out_head.
+// (reference, sum, acc[D]) partial per query at out + g * out_head, the reference still in
+// base-2 units (integer references, as the fp32 path keeps them, stay exact through every merge).
 template <int D, int NQ>
 __device__ __forceinline__ void merge_partials(float (&m)[NQ], float (&l)[NQ], float (&acc)[NQ][D / 16],
                                                float* __restrict__ out, size_t out_head, float* red) {
   constexpr int EL = D / 16;
   constexpr int PW = EL + 2;                          // floats of one lane's share of a partial
-  constexpr float kLn2 = 0.6931471805599453f;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
-    m[g] *= kLn2;
     for (int o = 16; o < 64; o <<= 1) {
       const float mo = __shfl_xor(m[g], o, kWave), lo = __shfl_xor(l[g], o, kWave);
       const float mn = fmaxf(m[g], mo);
-      const float ca = (m[g] == -INFINITY) ? 0.f : __expf(m[g] - mn);
-      const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
+      const float ca = (m[g] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[g] - mn);
+      const float cb = (mo == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mo - mn);
       l[g] = l[g] * ca + lo * cb;
 #pragma unroll
       for (int e = 0; e < EL; ++e) acc[g][e] = acc[g][e] * ca + __shfl_xor(acc[g][e], o, kWave) * cb;
@@ -155,7 +156,7 @@ __device__ __forceinline__ void merge_partials(float (&m)[NQ], float (&l)[NQ], f
     for (int e = 0; e < EL; ++e) a[e] = 0.f;
     for (int x = 0; x < kPartWaves; ++x) {
       const float mx = red[(x * 16 + ln) * (NQ * PW) + g * PW];
-      const float cf = (mx == -INFINITY) ? 0.f : __expf(mx - M);
+      const float cf = (mx == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mx - M);
       L += red[(x * 16 + ln) * (NQ * PW) + g * PW + 1] * cf;
 #pragma unroll
       for (int e = 0; e < EL; ++e) a[e] += red[(x * 16 + ln) * (NQ * PW) + g * PW + 2 + e] * cf;
@@ -173,7 +174,7 @@ __device__ __forceinline__ void merge_partials(float (&m)[NQ], float (&l)[NQ], f
 // kPartWaves * 16 * NQ * (D/16 + 2) floats.  Called by a whole workgroup.
 template <typename T, int D, int NQ>
 __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const T* __restrict__ vbase, int r_begin,
-                                             int r_end, const T* __restrict__ q0, float scale,
+                                             int r_end, const T* __restrict__ q0, double scale,
                                              float* __restrict__ out, size_t out_head, float* red) {
   constexpr int EL = D / 16;
   const int tid = threadIdx.x;
@@ -185,23 +186,21 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
 
   // logits are carried in base-2 units (scale * log2 e) so that the exponential is one v_exp_f32.
   // bf16 storage: q.k over a lane's slice is EL/2 two-element bf16 dot products with fp32
-  // accumulation straight from the loaded words, and the factor is applied to the row's sum;
-  // fp32 storage: the factor is folded into the query.
-  constexpr float kLog2e = 1.4426950408889634f;
+  // accumulation straight from the loaded words, and the factor is applied to the row's sum.
+  // fp32 storage: q.k is accumulated in fp64 and the reference of the exponentials is kept at an
+  // integer (exact in fp32, and exact through every later merge), so that x - reference is formed
+  // without cancellation error even for logits in the hundreds.
+  constexpr double kLog2e = 1.4426950408889634;
   constexpr bool kDot2 = sizeof(T) == 2;
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-  const float qk_factor = kDot2 ? scale * kLog2e : 1.f;
+  using logit_t = typename std::conditional<kDot2, float, double>::type;
+  const logit_t qk_factor = (logit_t)(scale * kLog2e);
   float qv[kDot2 ? 1 : NQ][EL];
   RawSlice<T, EL> qraw[kDot2 ? NQ : 1];
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
-    if constexpr (kDot2) {
-      qraw[g].load(q0 + (size_t)g * D + sub * EL);
-    } else {
-      load_slice<T, EL>(q0 + (size_t)g * D + sub * EL, qv[g]);
-#pragma unroll
-      for (int e = 0; e < EL; ++e) qv[g][e] *= scale * kLog2e;
-    }
+    if constexpr (kDot2) qraw[g].load(q0 + (size_t)g * D + sub * EL);
+    else load_slice<T, EL>(q0 + (size_t)g * D + sub * EL, qv[g]);
   }
 
   float m[NQ], l[NQ], acc[NQ][EL];
@@ -249,7 +248,7 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
       }
 #pragma unroll
       for (int g = 0; g < NQ; ++g) {
-        float sc = 0.f;
+        logit_t sc = 0;
         if (ok[u]) {
           if constexpr (kDot2) {
 #pragma unroll
@@ -258,19 +257,20 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
                                                    __builtin_bit_cast(bf16x2_t, qraw[g].w[i]), sc, false);
           } else {
 #pragma unroll
-            for (int e = 0; e < EL; ++e) sc = fmaf(qv[g][e], kv[e], sc);
+            for (int e = 0; e < EL; ++e) sc = fma((double)qv[g][e], (double)kv[e], sc);
           }
         }
         sc = row16_sum(sc) * qk_factor;
         if (ok[u]) {
-          if (sc > m[g] + kSlack) {
-            const float corr = __builtin_amdgcn_exp2f(m[g] - sc);       // 0 on the first row (m = -inf)
+          if (sc > (logit_t)m[g] + (logit_t)kSlack) {
+            const float m_new = kDot2 ? (float)sc : ceilf((float)sc);
+            const float corr = __builtin_amdgcn_exp2f(m[g] - m_new);    // 0 on the first row (m = -inf)
             l[g] *= corr;
 #pragma unroll
             for (int e = 0; e < EL; ++e) acc[g][e] *= corr;
-            m[g] = sc;
+            m[g] = m_new;
           }
-          const float pr = __builtin_amdgcn_exp2f(sc - m[g]);
+          const float pr = __builtin_amdgcn_exp2f((float)(sc - (logit_t)m[g]));
           l[g] += pr;
 #pragma unroll
           for (int e = 0; e < EL; ++e) acc[g][e] = fmaf(pr, vv[e], acc[g][e]);
@@ -300,7 +300,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float dec_f32x4_t;
 
 template <int NQ>
 __device__ __forceinline__ void partial_rows_mfma(const bf16_t* __restrict__ kbase, const bf16_t* __restrict__ vbase,
-                                                  int r_begin, int r_end, const bf16_t* __restrict__ q0, float scale,
+                                                  int r_begin, int r_end, const bf16_t* __restrict__ q0, double scale,
                                                   float* __restrict__ out, size_t out_head, float* red,
                                                   unsigned char* tiles) {
   constexpr int D = 128, EL = 8;
@@ -324,7 +324,7 @@ __device__ __forceinline__ void partial_rows_mfma(const bf16_t* __restrict__ kba
     *reinterpret_cast<uint4*>(qt + g * 256 + ((ch ^ g) & 15) * 16) = *reinterpret_cast<const uint4*>(q0 + (size_t)g * D + ch * 8);
   }
   __syncthreads();
-  const float factor = scale * kLog2e;
+  const float factor = (float)(scale * (double)kLog2e);
 
   float m[NQ], l[NQ], acc[NQ][EL];
 #pragma unroll
@@ -461,7 +461,7 @@ __device__ __forceinline__ void partial_rows_mfma(const bf16_t* __restrict__ kba
 // of the group's first head scores each ring row against all GW queries and the others skip it.
 template <typename T, int D, int GQ, int GW>
 __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
-    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, float scale,
+    tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, double scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
   constexpr int EL = D / 16;
   constexpr int CH = GQ > 1 ? kChunkShared : kChunk;  // rows per slot
@@ -536,7 +536,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
     float lpart = 0.f;
     for (int x = tid; x < n_slots; x += kDecThreads) {
       const float lx = pp[(size_t)x * (D + 2) + 1];
-      const float wx = lx > 0.f ? __expf(pp[(size_t)x * (D + 2)] - M) : 0.f;
+      const float wx = lx > 0.f ? __builtin_amdgcn_exp2f(pp[(size_t)x * (D + 2)] - M) : 0.f;   // references are in base-2 units
       wgt[x] = wx;
       lpart += lx * wx;
     }
@@ -698,7 +698,7 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
   DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
   hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B, (Hs + 3) / 4), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new,
                      v_new, dw.n_vis);
-  const float sc = (float)logit_scale(prm);
+  const double sc = logit_scale(prm);
   // (queries per region row, queries per ring row): (G, G) for a shared selection, else (1, G)
   const int G = Hq / Hkv;
 #define TCA_PARTIAL_CASE(GG)                                                                                    \

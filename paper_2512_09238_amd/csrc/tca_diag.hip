@@ -1,4 +1,6 @@
-// Diagnostic: what this board sustains on the matrix pipe.  A register-only loop
+// Diagnostics (declared in tca_diag.h; not part of the method's boundary).
+//
+// What this board sustains on the matrix pipe.  A register-only loop
 // of v_mfma_f32_32x32x16_bf16 (four independent accumulators per wave, four
 // waves per SIMD), timed with events, plus the shader clock it ran at
 // (cycle counter against the constant 100 MHz counter).  With operands of
@@ -6,7 +8,10 @@
 // clock, which is the ceiling the attention kernel works under.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "tca_common.h"
+#include "tca_diag.h"
 
 namespace tca {
 
@@ -45,9 +50,21 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float rnd, u
   }
 }
 
+static std::atomic<int> g_prefill_clocks{0}, g_prefill_variant{0};
+bool diag_prefill_clocks() { return g_prefill_clocks.load(std::memory_order_relaxed) != 0; }
+int prefill_variant() { return g_prefill_variant.load(std::memory_order_relaxed); }
+
 }  // namespace tca
 
 using namespace tca;
+
+extern "C" void tca_diag_prefill_clocks(int enable) { g_prefill_clocks.store(enable ? 1 : 0); }
+
+extern "C" int tca_diag_prefill_variant(int variant) {
+  if (variant < 0 || variant > 3) return fail(TCA_ERR_INVALID, "tca_diag_prefill_variant: %d", variant);
+  g_prefill_variant.store(variant);
+  return TCA_OK;
+}
 
 extern "C" size_t tca_probe_workspace_bytes(void) { return (size_t)kProbeBlocks * 3 * sizeof(unsigned long long); }
 

@@ -1,8 +1,9 @@
 // bf16 MFMA flash-attention prefill over the global and local subsets (Eq. 2;
 // Alg. 2 line 7) for gfx950.
 //
-// Work decomposition.  One workgroup = 4 wavefronts = one tile of BM = 128
-// consecutive queries of one query head; wave v owns 32 of them.  The
+// Work decomposition.  One workgroup = NW wavefronts = one tile of BM = 32 NW
+// consecutive queries of one query head; wave v owns 32 of them (NW = 8, 256
+// queries, for long calls; NW = 4 when a call has few query tiles).  The
 // workgroup walks 64-key tiles: first the head's compacted global rows (tiles
 // of the head's region of Kg), then the dense keys of the sliding window
 // (absolute 64-key tiles of K).  Visibility is a prefix test in both parts:
@@ -27,6 +28,14 @@
 // XOR-swizzled 16-byte chunks (conflict-free b128 reads without padding), filled by
 // direct global -> LDS loads.  The loop is software-pipelined by one tile (see the
 // kernel); one barrier per tile.
+//
+// Softmax bookkeeping.  The reference m of a query's exponentials is lazy: it is not
+// the running maximum but any earlier maximum of visible scores, raised only when a
+// tile's terms would come near the top of the fp32 range (row sum of the tile >=
+// kRaise).  Terms, sum and accumulators share the reference, so the quotient is the
+// same; the common tile then needs no maximum at all.  The sum l is formed from the
+// bf16-rounded terms, the very numbers that enter O^T = V^T P^T, so numerator and
+// denominator carry the same rounding.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -40,6 +49,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 
 constexpr int kBN = 64;              // keys per tile
 constexpr int kFragAhead = 4;        // LDS fragment reads in flight ahead of the MFMA that uses them
+constexpr float kRaise = 0x1p60f;    // a tile whose terms sum to this much raises the softmax reference
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct PrefillHeads {
   int64_t offs[TCA_MAX_HEADS + 1];      // row offsets of the heads' regions
@@ -117,6 +128,57 @@ __device__ __forceinline__ int count_le_i32(const int32_t* idx, int n, int64_t b
   return lo;
 }
 
+// O^T += V^T P^T step.  With two query blocks per wave the O^T accumulators (128 registers for
+// d = 128) are pinned to the accumulation registers, which only the matrix pipe touches, so that
+// the scores and the exponentials' terms keep the vector registers.  The instruction is written
+// out because the register file of an operand cannot be chosen through the builtin; what the
+// compiler then cannot see is that o is being written for 8 passes after issue: every vector
+// ALU read of o goes through settle_acc() first.
+template <bool ACC>
+__device__ __forceinline__ void pv_mfma(f32x16_t& o, const bf16x8_t& a, const bf16x8_t& b) {
+  if constexpr (ACC) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(a), "v"(b));
+  else o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, o, 0, 0, 0);
+}
+// S^T = K Q^T steps for two query blocks per wave: scores in vector registers, Q fragments in
+// accumulation registers.  FIRST starts a chain from zero.
+template <bool FIRST>
+__device__ __forceinline__ void s_mfma(f32x16_t& s, const bf16x8_t& k, const bf16x8_t& q) {
+  if constexpr (FIRST) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(q));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(q));
+}
+// The last step of the four chains of a tile (two blocks x two 32-key sub-tiles), followed by the
+// wait states the vector ALU needs before it may touch their results (19 at most; the compiler
+// inserts them for the builtin, not for a written-out instruction).
+__device__ __forceinline__ void s_mfma_last(f32x16_t& s00, f32x16_t& s10, f32x16_t& s01, f32x16_t& s11,
+                                            const bf16x8_t& k0, const bf16x8_t& k1, const bf16x8_t& q0,
+                                            const bf16x8_t& q1) {
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %0, %4, %6, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %4, %7, %1\n\t"
+      "v_mfma_f32_32x32x16_bf16 %2, %5, %6, %2\n\t"
+      "v_mfma_f32_32x32x16_bf16 %3, %5, %7, %3\n\t"
+      "s_nop 15\n\ts_nop 7"
+      : "+v"(s00), "+v"(s10), "+v"(s01), "+v"(s11)
+      : "v"(k0), "v"(k1), "a"(q0), "a"(q1));
+}
+// Marks the accumulators as living in the accumulation registers at this point (no instruction):
+// placed after every vector-ALU update of o, so that the value the loop carries has one home and
+// is not shuttled between the two register files on every iteration.
+template <int N>
+__device__ __forceinline__ void home_acc(f32x16_t (&o)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+a"(o[i]));
+}
+// Waits out the matrix pipe's pending writes to accumulators before the vector ALU reads them.
+template <int N>
+__device__ __forceinline__ void settle_acc(f32x16_t (&o)[N]) {
+  static_assert(N == 2 || N == 4, "one statement per supported slice count");
+  if constexpr (N == 4)
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]));
+  else
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(o[0]), "+a"(o[1]));
+}
+
 // Cross-half exchange: returns max over the two 32-lane halves, in every lane.
 __device__ __forceinline__ float half_max(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -171,15 +233,24 @@ __device__ __forceinline__ void copy16_to_lds(__amdgpu_buffer_rsrc_t rsrc, int l
 }
 
 // Software pipeline over the tiles of a workgroup (tile t = 0 .. n_tiles-1: first the
-// n_gt tiles of the head's compacted region, then the dense tiles of the window):
-//   iteration t :  S(t+1) = K(t+1) Q^T      (MFMA)     }  one basic block: the MFMAs of the
-//                  P(t)   = softmax step on S(t) (VALU) }  next tile run under this tile's exps
-//                  O     += V(t)^T P(t)     (MFMA)
-// K(t+2) and V^T(t+1) are copied global -> LDS during iteration t.  The K ring and
-// the V^T ring hold two tiles each; one barrier per iteration.
+// n_gt tiles of the head's compacted region, then the dense tiles of the window).  A wave
+// owns QB blocks of 32 queries.  With QB = 1, iteration t is
+//   slot A :  S(t+1) = K(t+1) Q^T          (MFMA)  }  one basic block: the MFMAs of the next
+//             P(t)   = exp step on S(t)    (VALU)  }  tile run under this tile's exponentials
+//   slot B :  O     += V(t)^T P(t)         (MFMA)
+// With QB = 2 every K / V^T fragment read from LDS feeds two MFMAs (one per block; the LDS
+// port moves 128 bytes per clock and CU, which with one fragment per MFMA is as much of a
+// limit as the matrix pipe itself), the wave has a SIMD to itself (512 registers), and the
+// second block's softmax runs half an iteration late so that both slots pair 32 MFMAs with
+// one block's exponentials, neither depending on the other:
+//   slot A :  S_a(t+1), S_b(t+1)           (MFMA)  |  P_a(t)   from S_a(t)     (VALU)
+//   slot B :  O_a += V(t)^T P_a(t), O_b += V(t)^T P_b(t)  |  P_b(t+1) from S_b(t+1)
+// K(t+RING) and V^T(t+RING-1) are copied global -> LDS during iteration t, into the places
+// of K(t) and V^T(t-1); the rings hold RING = 2 or 3 tiles each; one barrier per iteration.
 // Positions and byte offsets are 32-bit here: the host checks (q_pos0 + n_queries) * D * 2 < 2^31.
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
+template <int D, int NW, int QB>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2 / QB, 2 / QB)))
+void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
@@ -187,15 +258,20 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     uint16_t* __restrict__ O, float* __restrict__ lse, unsigned long long* __restrict__ clk) {
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
-  constexpr int BM = NW * 32;            // queries per workgroup, 32 per wave
+  constexpr int WQ = QB * 32;            // queries per wave
+  constexpr int BM = NW * WQ;            // queries per workgroup
   const unsigned long long clk_c0 = __builtin_readcyclecounter(), clk_r0 = __builtin_amdgcn_s_memrealtime();
   constexpr int KBYTES = kBN * D * 2;    // K tile
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
   // Rows are not padded; the 16-byte chunk index is XOR-swizzled with the row so that
   // the b128 reads of 16 consecutive rows at one chunk column fall into distinct banks.
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * KBYTES + 2 * VBYTES];
+  // Tiles in flight: a workgroup that has its CU to itself keeps rings of three K and three V^T
+  // tiles (96 KB for d = 128), so that a copy has a whole iteration and more to arrive; where two
+  // workgroups share a CU the rings hold two.
+  constexpr int RING = (NW * QB >= 8) ? 3 : 2;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[RING * (KBYTES + VBYTES)];
   unsigned char* const kring = lds;
-  unsigned char* const vring = lds + 2 * KBYTES;
+  unsigned char* const vring = lds + RING * KBYTES;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave index, scalar
@@ -221,23 +297,25 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
   const int64_t last_row = n_queries - 1;
   const float sl2e = scale * 1.4426950408889634f;
 
-  // ---- per-lane query state (lane column c = one query)
+  // ---- per-lane query state (lane column c = one query of each block)
   const int hs = h / GS;                           // the selection this query head reads (GS query heads share it)
   const int64_t base = ph.offs[hs];
   const int nr = n_rows[hs];
-  int64_t qrow_i = r0 + wv * 32 + c;
-  if (qrow_i > last_row) qrow_i = last_row;         // clamped rows compute a duplicate; never stored
-  const int qpos = (int)(q_pos0 + qrow_i);
-  const int nvis = count_le_i32(idx + base, nr, (int64_t)qpos - w);
-  bf16x8_t qf[KK];
-  {
+  int qpos[QB], nvis[QB];
+  bf16x8_t qf[QB][KK];
+#pragma unroll
+  for (int blk = 0; blk < QB; ++blk) {
+    int64_t qrow_i = r0 + wv * WQ + blk * 32 + c;
+    if (qrow_i > last_row) qrow_i = last_row;       // clamped rows compute a duplicate; never stored
+    qpos[blk] = (int)(q_pos0 + qrow_i);
+    nvis[blk] = count_le_i32(idx + base, nr, (int64_t)qpos[blk] - w);
     const uint16_t* qrow = Q + ((size_t)h * n_queries + qrow_i) * D;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
+    for (int kk = 0; kk < KK; ++kk) qf[blk][kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
   }
-  // wave-level visibility bounds (queries ascend with the lane index c; clamped rows repeat the last)
-  const int wave_first = (int)(q_pos0 + i64min(r0 + wv * 32, last_row));
-  const int wave_last = (int)(q_pos0 + i64min(r0 + wv * 32 + 31, last_row));
+  // wave-level visibility bounds (queries ascend with block and lane column; clamped rows repeat the last)
+  const int wave_first = (int)(q_pos0 + i64min(r0 + wv * WQ, last_row));
+  const int wave_last = (int)(q_pos0 + i64min(r0 + wv * WQ + WQ - 1, last_row));
   const int wg_last = (int)(q_pos0 + i64min(r0 + BM - 1, last_row));
   const int wg_first = (int)(q_pos0 + r0);
   const int last_pos = (int)(q_pos0 + last_row);
@@ -292,12 +370,18 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     else copy16_to_lds(job.vrs, vlo[j - Copy::NK], job.voff, job.vdst + (j - Copy::NK) * 1024);
   };
 
-  f32x16_t o[DS];
-  float m = -INFINITY, l = 0.f;
+  f32x16_t o[QB][DS];
+  float m[QB], l[QB];
 #pragma unroll
-  for (int sl = 0; sl < DS; ++sl)
+  for (int blk = 0; blk < QB; ++blk) {
+    m[blk] = -INFINITY;
+    l[blk] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[sl][r] = 0.f;
+    for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[blk][sl][r] = 0.f;
+    if constexpr (QB == 2) home_acc(o[blk]);
+  }
 
   // per-lane LDS byte offsets of the MFMA fragments inside a tile (the rest is compile-time constant):
   // K fragment (sub, kk) sits at kfa[kk] + sub * 32 rows, V^T fragment (sl, sg) at vfa[sg] + sl * 32 rows;
@@ -308,26 +392,47 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
 #pragma unroll
   for (int sg = 0; sg < 4; ++sg) vfa[sg] = v_off(c, 2 * sg + hh);
 
-  // S^T = K Q^T for the 64 keys of the tile at kb (two 32-key sub-tiles = two accumulation
-  // chains that alternate; fragments read kFragAhead MFMAs ahead); between_pairs(kk) runs after
-  // the kk-th pair of MFMAs (the place where the tile copies are issued)
-  auto s_tile = [&](const unsigned char* kb, f32x16_t (&s)[2], auto between_pairs) {
+  // S^T = K Q^T for the 64 keys of the tile at kb and every query block of the wave (two 32-key
+  // sub-tiles per block = 2 QB accumulation chains that alternate; fragments read kFragAhead
+  // ahead and used once per block); between_pairs(kk) runs after the kk-th pair of fragments
+  // (the place where the tile copies are issued)
+  auto s_tile = [&](const unsigned char* kb, f32x16_t (&s)[QB][2], auto after_fragment) {
     auto kfrag = [&](int i) {
       return *reinterpret_cast<const bf16x8_t*>(kb + kfa[i >> 1] + (i & 1) * (32 * D * 2));
     };
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
     bf16x8_t fr[kFragAhead];
 #pragma unroll
     for (int i = 0; i < kFragAhead; ++i) fr[i] = kfrag(i);
+    if constexpr (QB == 1) {
 #pragma unroll
-    for (int i = 0; i < 2 * KK; ++i) {
-      const int sub = i & 1, kk = i >> 1;
-      s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[kk], s[sub], 0, 0, 0);
-      if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
-      if (sub == 1) between_pairs(kk);
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[0][sub][r] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 2 * KK; ++i) {
+        const int sub = i & 1, kk = i >> 1;
+        s[0][sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % kFragAhead], qf[0][kk], s[0][sub], 0, 0, 0);
+        if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
+        after_fragment(i);
+      }
+    } else {
+      // the Q fragments (64 registers for d = 128) sit in the accumulation registers as well; the
+      // last MFMA of every chain and the wait for their results share one statement
+#pragma unroll
+      for (int i = 0; i < 2 * KK - 2; ++i) {
+        const int sub = i & 1, kk = i >> 1;
+#pragma unroll
+        for (int blk = 0; blk < QB; ++blk) {
+          if (kk == 0) s_mfma<true>(s[blk][sub], fr[i % kFragAhead], qf[blk][kk]);
+          else s_mfma<false>(s[blk][sub], fr[i % kFragAhead], qf[blk][kk]);
+        }
+        if (i + kFragAhead < 2 * KK) fr[i % kFragAhead] = kfrag(i + kFragAhead);
+        after_fragment(i);
+      }
+      s_mfma_last(s[0][0], s[1][0], s[0][1], s[1][1], fr[(2 * KK - 2) % kFragAhead], fr[(2 * KK - 1) % kFragAhead],
+                  qf[0][KK - 1], qf[1][KK - 1]);
+      after_fragment(2 * KK - 2);
+      after_fragment(2 * KK - 1);
     }
   };
 
@@ -339,65 +444,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
     return half_max(fmaxf(fmaxf(fmaxf(m8[0], m8[1]), fmaxf(m8[2], m8[3])), fmaxf(fmaxf(m8[4], m8[5]), fmaxf(m8[6], m8[7]))));
   };
 
-  // One pipeline step: tile `it` (scores in sc, their unmasked maximum in mx_pre) goes through softmax
-  // and P V; the scores of tile it+1 go to sn, and their maximum is taken under the P V MFMAs.
-  auto step = [&](int it, f32x16_t (&sc)[2], f32x16_t (&sn)[2], float& mx_pre) {
-    // the loads issued during the previous step (K(it+1), V^T(it)) have landed for this wave; after the
-    // barrier for every wave, and every wave is done reading K(it) and V^T(it-1)
-    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
-    __syncthreads();
-    const int tk = it + 2 < last ? it + 2 : last, tv = it + 1 < last ? it + 1 : last;   // past the end: a harmless reload
-    const CopyJob job = copy_job(tk, tv, kring + (it & 1) * KBYTES, vring + ((it + 1) & 1) * VBYTES);
-    const unsigned char* kb = kring + ((it + 1) & 1) * KBYTES;
-    const unsigned char* vb = vring + (it & 1) * VBYTES;
-    const bool is_glob = it < n_gt;
-    const int key0 = (it + (is_glob ? 0 : dshift)) * kBN;
-
-    // ---- mask of tile `it` (boundary tiles only; a tile this wave sees nothing of is fully masked)
-    const bool masked = is_glob ? (key0 + kBN > nv_wave_lo)
-                                : !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w);
-    float mx = mx_pre;
-    if (masked) {
-      // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
-      int lo, hi;
-      if (is_glob) {
-        lo = 0;
-        hi = nvis - key0 < kBN ? nvis - key0 : kBN;
-      } else {
-        const int l32 = qpos - w + 1 - key0, h32 = qpos + 1 - key0;
-        lo = l32 < 0 ? 0 : (l32 > kBN ? kBN : l32);
-        hi = h32 < 0 ? 0 : (h32 > kBN ? kBN : h32);
-      }
-      const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
-      const int rel0 = 4 * hh - lo;
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
-          sc[sub][r] = kr < span ? sc[sub][r] : -INFINITY;
-        }
-      mx = lane_max(sc);
-    }
-
-    // ---- running maximum of the query (lane column); rescale only when some lane's maximum moved
-    const float m_new = fmaxf(m, mx);
-    if (__any(m_new > m)) {
-      const float alpha = (m_new > m) ? __builtin_amdgcn_exp2f((m - m_new) * sl2e) : 1.f;
-      l *= alpha;
-#pragma unroll
-      for (int sl = 0; sl < DS; ++sl)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[sl][r] *= alpha;
-      m = m_new;
-    }
-    const float mb = (m_new == -INFINITY) ? 0.f : m_new * sl2e;
-
-    // ---- scores of the next tile (MFMA) under the exponentials of this one (VALU)
-    s_tile(kb, sn, [&](int kk) {       // copies spread as evenly as the counts allow: load j after pair j * KK / N
-      if ((kk * Copy::N) % KK == 0 && kk * Copy::N / KK < Copy::N) copy_load(job, kk * Copy::N / KK);
-    });
-    bf16x8_t pf[2][2];
+  // exponentials of the scores s against the reference mb (already in base-2 units): bf16 terms in
+  // operand order, and the sum of those rounded terms over the lane's 32 keys
+  auto exp_tile = [&](const f32x16_t (&s)[2], float mb, bf16x8_t (&pf)[2][2]) {
+    const bf16x2_t ones = {(__bf16)1.f, (__bf16)1.f};
     float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
@@ -405,16 +455,158 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
       for (int g = 0; g < 2; ++g) {
         bf16x8_t pk;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[sub][8 * g + e], sl2e, -mb));
-          ls[e & 3] += p;
-          pk[e] = (__bf16)p;
+        for (int e = 0; e < 8; ++e) pk[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[sub][8 * g + e], sl2e, -mb));
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {                // sums the rounded terms: what the P V product sees
+          const bf16x2_t pr = {pk[2 * e2], pk[2 * e2 + 1]};
+          ls[e2] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ls[e2], false);
         }
         pf[sub][g] = pk;
       }
-    l += (ls[0] + ls[1]) + (ls[2] + ls[3]);
+    return (ls[0] + ls[1]) + (ls[2] + ls[3]);
+  };
 
-    // ---- O^T += V^T P^T: the DS accumulation chains alternate; V^T fragments are read ahead
+  // The same work cut into NCH pieces for the two-block schedule, where the written-out MFMAs pin
+  // the instruction order and the pieces are placed between them by hand: piece i forms the
+  // exponentials of elements i*EPC .. i*EPC+EPC-1 and rounds, stores and sums those of piece i-1
+  // (one piece later, so that no instruction waits on the exponential it has just issued);
+  // piece NCH only finishes piece NCH-1.  ls must start at zero; the tile's sum is ls[0..3] added up.
+  constexpr int NCH = 2 * KK;            // = fragments of a K tile = fragments of a V^T tile
+  constexpr int EPC = 32 / NCH;          // elements of a lane's 32 per piece: 2 (d = 128) or 4 (d = 64)
+  auto exp_piece = [&](int i, const f32x16_t (&s)[2], float mb, bf16x8_t (&pf)[2][2], float (&ls)[4], float (&pend)[EPC]) {
+    const bf16x2_t ones = {(__bf16)1.f, (__bf16)1.f};
+    if (i >= 1) {
+#pragma unroll
+      for (int k = 0; k < EPC; k += 2) {
+        const int n = (i - 1) * EPC + k;                 // even element of a pair
+        const bf16x2_t pr = {(__bf16)pend[k], (__bf16)pend[k + 1]};
+        pf[n >> 4][(n >> 3) & 1][n & 7] = pr[0];
+        pf[n >> 4][(n >> 3) & 1][(n & 7) + 1] = pr[1];
+        ls[(n >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ls[(n >> 1) & 3], false);
+      }
+    }
+    if (i < NCH) {
+#pragma unroll
+      for (int k = 0; k < EPC; ++k) {
+        const int n = i * EPC + k;
+        pend[k] = __builtin_amdgcn_exp2f(fmaf(s[n >> 4][n & 15], sl2e, -mb));
+      }
+    }
+  };
+
+  // Mask of tile t on the scores s of block blk (boundary tiles only; a tile this wave sees nothing
+  // of, or past the last one, is fully masked).  Returns whether this lane's query sees any key of it.
+  auto mask_tile = [&](int t, int blk, f32x16_t (&s)[2]) {
+    const bool is_glob = t < n_gt;
+    const int key0 = (t + (is_glob ? 0 : dshift)) * kBN;
+    const bool beyond = t > last;
+    const bool masked = beyond || (is_glob ? (key0 + kBN > nv_wave_lo)
+                                           : !(key0 + kBN - 1 <= wave_first && key0 > wave_last - w));
+    bool sees = true;
+    if (masked) {
+      // visible <=> lo <= key - key0 < hi, with one unsigned compare per element
+      int lo, hi;
+      if (is_glob) {
+        lo = 0;
+        hi = nvis[blk] - key0 < kBN ? nvis[blk] - key0 : kBN;
+      } else {
+        const int l32 = qpos[blk] - w + 1 - key0, h32 = qpos[blk] + 1 - key0;
+        lo = l32 < 0 ? 0 : (l32 > kBN ? kBN : l32);
+        hi = h32 < 0 ? 0 : (h32 > kBN ? kBN : h32);
+      }
+      const unsigned span = (hi > lo && !beyond) ? (unsigned)(hi - lo) : 0u;
+      sees = span != 0u;
+      const int rel0 = 4 * hh - lo;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const unsigned kr = (unsigned)(rel0 + sub * 32 + 8 * (r >> 2) + (r & 3));
+          s[sub][r] = kr < span ? s[sub][r] : -INFINITY;
+        }
+    }
+    return sees;
+  };
+
+  // The uncommon tile: the query's first visible keys, or terms too large for the reference.
+  // The reference becomes the maximum over the visible scores so far (the same in both lanes of
+  // a query), the state is rescaled and the tile's terms are formed again.
+  auto softmax_fixup = [&](int blk, const f32x16_t (&s)[2], bool cold, bool sees, float& lt, bf16x8_t (&pf)[2][2]) {
+    if (__any(lt >= kRaise || (cold && sees))) {
+      const float m_new = fmaxf(m[blk], lane_max(s));
+      const float alpha = (m_new > m[blk]) ? __builtin_amdgcn_exp2f((m[blk] - m_new) * sl2e) : 1.f;   // 0 when m was -inf
+      l[blk] *= alpha;
+      if constexpr (QB == 2) settle_acc(o[blk]);
+#pragma unroll
+      for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[blk][sl][r] *= alpha;
+      if constexpr (QB == 2) home_acc(o[blk]);
+      m[blk] = m_new;
+      lt = exp_tile(s, (m_new == -INFINITY) ? 0.f : m_new * sl2e, pf);
+    }
+  };
+
+  bf16x8_t pf[QB][2][2];                 // P of block 0: formed and used inside a step; of block 1: formed one step ahead
+
+  int rpos = 0;                          // it % RING of the step about to run
+  static_assert((RING - 2) * Copy::N < 16, "the wait below encodes its count in four bits");
+
+  // One pipeline step: tile `it` (scores in sc; with QB = 2 those of block 1 are already in pf[1])
+  // goes through softmax and P V; the scores of tile it+1 go to sn.
+  auto step = [&](int it, f32x16_t (&sc)[QB][2], f32x16_t (&sn)[QB][2]) {
+    // K(it+1) and V^T(it) have landed for this wave (only the copies of the previous step may still
+    // be on their way when the rings hold three tiles); after the barrier for every wave, and every
+    // wave is done reading K(it) and V^T(it-1)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((RING - 2) * Copy::N));     // vmcnt((RING - 2) * N)
+    __syncthreads();
+    const int tk = it + RING < last ? it + RING : last, tv = it + RING - 1 < last ? it + RING - 1 : last;   // past the end: a harmless reload
+    const int r_next = rpos + 1 == RING ? 0 : rpos + 1, r_prev = rpos == 0 ? RING - 1 : rpos - 1;   // (it +- 1) % RING
+    const CopyJob job = copy_job(tk, tv, kring + rpos * KBYTES, vring + r_prev * VBYTES);
+    const unsigned char* kb = kring + r_next * KBYTES;
+    const unsigned char* vb = vring + rpos * VBYTES;
+    rpos = r_next;
+
+    // ---- slot A: scores of the next tile (MFMA) under the exponentials of this one (VALU), taken
+    // against the reference as it stands
+    auto issue_copies = [&](int i) {     // copies spread as evenly as the counts allow: load j after fragment pair j * KK / N
+      const int kk = i >> 1;
+      if ((i & 1) && (kk * Copy::N) % KK == 0 && kk * Copy::N / KK < Copy::N) copy_load(job, kk * Copy::N / KK);
+    };
+    {
+      const bool sees = mask_tile(it, 0, sc[0]);
+      const bool cold = m[0] == -INFINITY;          // no reference yet: no key seen so far
+      const float mb = cold ? 0.f : m[0] * sl2e;
+      float lt;
+      if constexpr (QB == 1) {
+        s_tile(kb, sn, issue_copies);
+        lt = exp_tile(sc[0], mb, pf[0]);
+      } else {
+        float ls[4] = {0.f, 0.f, 0.f, 0.f}, pend[EPC];
+        __builtin_amdgcn_sched_barrier(0);
+        s_tile(kb, sn, [&](int i) {
+          issue_copies(i);
+          exp_piece(i, sc[0], mb, pf[0], ls, pend);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        exp_piece(NCH, sc[0], mb, pf[0], ls, pend);
+        lt = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+      }
+      softmax_fixup(0, sc[0], cold, sees, lt, pf[0]);
+      l[0] += lt;
+    }
+
+    // ---- slot B: O^T += V^T P^T for every block (the accumulation chains alternate; V^T fragments
+    // are read ahead and used once per block), under the exponentials of block 1's next tile
+    bool sees1 = true, cold1 = false;
+    float mb1 = 0.f, ls1[4] = {0.f, 0.f, 0.f, 0.f}, pend1[EPC];
+    bf16x8_t pn[2][2];
+    if constexpr (QB == 2) {
+      sees1 = mask_tile(it + 1, 1, sn[1]);
+      cold1 = m[1] == -INFINITY;
+      mb1 = cold1 ? 0.f : m[1] * sl2e;
+      __builtin_amdgcn_sched_barrier(0);
+    }
     auto vfrag = [&](int j) {
       return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
     };
@@ -424,41 +616,68 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
 #pragma unroll
     for (int j = 0; j < 4 * DS; ++j) {
       const int sl = j % DS, sg = j / DS;           // sg = sub*2 + g: 16 keys
-      o[sl] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[j % kFragAhead], pf[sg >> 1][sg & 1], o[sl], 0, 0, 0);
+#pragma unroll
+      for (int blk = 0; blk < QB; ++blk) pv_mfma<QB == 2>(o[blk][sl], vfr[j % kFragAhead], pf[blk][sg >> 1][sg & 1]);
       if (j + kFragAhead < 4 * DS) vfr[j % kFragAhead] = vfrag(j + kFragAhead);
+      if constexpr (QB == 2) {
+        exp_piece(j, sn[1], mb1, pn, ls1, pend1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    mx_pre = lane_max(sn);              // vector ALU work for the shadow of the MFMAs above
+    if constexpr (QB == 2) {
+      exp_piece(NCH, sn[1], mb1, pn, ls1, pend1);
+      float lt = (ls1[0] + ls1[1]) + (ls1[2] + ls1[3]);
+      softmax_fixup(1, sn[1], cold1, sees1, lt, pn);
+      l[1] += lt;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) pf[1][a][g] = pn[a][g];
+    }
   };
 
-  // ---- prologue: K(0), V^T(0) in; S(0) computed while K(1) comes in
-  f32x16_t sa[2], sb[2];
+  // ---- prologue: everything the steps do not copy themselves - K(0) .. K(RING-1), V^T(0) ..
+  // V^T(RING-2) - is requested here, oldest first; S(0) is formed as soon as K(0) is in
+  f32x16_t sa[QB][2], sb[QB][2];
   {
+    auto tile_or_last = [&](int t) { return t < last ? t : last; };
     const CopyJob first = copy_job(0, 0, kring, vring);
 #pragma unroll
     for (int j = 0; j < Copy::N; ++j) copy_load(first, j);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+    const CopyJob second = copy_job(tile_or_last(1), 0, kring + KBYTES, vring);
+#pragma unroll
+    for (int j = 0; j < Copy::NK; ++j) copy_load(second, j);
+    if constexpr (RING == 3) {
+      const CopyJob third = copy_job(tile_or_last(2), tile_or_last(1), kring + 2 * KBYTES, vring + VBYTES);
+#pragma unroll
+      for (int j = 0; j < Copy::N; ++j) copy_load(third, j);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (Copy::NK + (RING - 2) * Copy::N));   // K(0), V^T(0) are in
     __syncthreads();
-    const int t1 = last < 1 ? last : 1;
-    const CopyJob second = copy_job(t1, t1, kring + KBYTES, vring + VBYTES);
-    s_tile(kring, sa, [&](int kk) {     // K(1) only; V^T(1) is step 0's load
-      if (kk < Copy::NK) copy_load(second, kk);
-    });
+    s_tile(kring, sa, [&](int) {});
+    if constexpr (QB == 2) {            // block 1 runs half a step ahead with its exponentials
+      const bool sees = mask_tile(0, 1, sa[1]);
+      float lt = exp_tile(sa[1], 0.f, pf[1]);
+      softmax_fixup(1, sa[1], true, sees, lt, pf[1]);
+      l[1] += lt;
+    }
   }
-  float mx_pre = lane_max(sa);
   for (int it = 0; it < n_tiles; it += 2) {
-    step(it, sa, sb, mx_pre);
-    if (it + 1 < n_tiles) step(it + 1, sb, sa, mx_pre);
+    step(it, sa, sb);
+    if (it + 1 < n_tiles) step(it + 1, sb, sa);
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);             // no copy into this workgroup's LDS may outlive it
-  if (tid == 0) {                                 // elapsed shader-clock cycles and 100 MHz ticks of this workgroup
+  if (clk && tid == 0) {                          // diagnostics only: elapsed shader-clock cycles and 100 MHz ticks of this workgroup
     atomicAdd(clk, (unsigned long long)__builtin_readcyclecounter() - clk_c0);
     atomicAdd(clk + 1, (unsigned long long)__builtin_amdgcn_s_memrealtime() - clk_r0);
   }
 
   // ---- normalise and store
-  {
-    const int64_t r = r0 + wv * 32 + c;
-    const float lt = half_sum(l);
+#pragma unroll
+  for (int blk = 0; blk < QB; ++blk) {
+    const int64_t r = r0 + wv * WQ + blk * 32 + c;
+    const float lt = half_sum(l[blk]);
+    if constexpr (QB == 2) settle_acc(o[blk]);
     if (r <= last_row) {
       const float inv = 1.f / lt;
       uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
@@ -468,10 +687,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_mfma_kernel(
         for (int q4 = 0; q4 < 4; ++q4) {
           bf16x4_t pk;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[sl][4 * q4 + j] * inv);
+          for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[blk][sl][4 * q4 + j] * inv);
           *reinterpret_cast<bf16x4_t*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
         }
-      if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m * scale + __logf(lt);
+      if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m[blk] * scale + __logf(lt);
     }
   }
 }
@@ -526,26 +745,32 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   const int64_t dt0 = win_lo / kBN, dt1 = (q_pos0 + n_queries - 1) / kBN;
   const int d_tiles = (int)(dt1 - dt0 + 1);
   MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hs, offs[Hs]), max_dense_tiles(n_queries, w));
+  unsigned long long* clk = diag_prefill_clocks() ? mw.clk : nullptr;   // cycle counters only when asked for
 
   if (max_tiles > 0)
     hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, Vg, (int64_t)0,
                        n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr);
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
-                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, mw.clk);
+                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, clk);
 
-  // Wavefronts per workgroup.  Eight (256 queries, one workgroup per CU) halve the tile copies per
-  // query; the board is power-limited under this kernel and the lighter L2 -> LDS traffic lets it
-  // clock about 10 % higher.  Four (128 queries, two workgroups per CU) keep the chip full when
-  // there are few query tiles.
-  auto launch = [&](auto nw_tag) {
-    constexpr int NW = decltype(nw_tag)::value;
-    const int n_qt = (int)((n_queries + NW * 32 - 1) / (NW * 32));
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
+  // Shape of a workgroup.  Long calls: eight waves of 32 queries (256 queries, one workgroup per CU,
+  // two waves per SIMD, rings of three tiles).  Calls with few query tiles: four waves of 32 queries
+  // (128 queries, two workgroups per CU), which keeps more of the chip busy.  Four waves of 64
+  // queries (one wave per SIMD, every LDS fragment feeds two MFMAs, half the LDS reads) stay
+  // selectable through the diagnostics switch: measured 5-8 % slower on 128K tokens, because a
+  // lone wave cannot issue its vector, LDS and scalar instructions fast enough beside the MFMAs.
+  auto launch = [&](auto nw_tag, auto qb_tag) {
+    constexpr int NW = decltype(nw_tag)::value, QB = decltype(qb_tag)::value;
+    const int n_qt = (int)((n_queries + NW * QB * 32 - 1) / (NW * QB * 32));
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
-                       Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, mw.clk);
+                       Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, clk);
   };
-  if (((n_queries + 255) / 256) * Hq >= 1024) launch(std::integral_constant<int, 8>{});
-  else launch(std::integral_constant<int, 4>{});
+  const int variant = prefill_variant();
+  const bool many = ((n_queries + 255) / 256) * Hq >= 1024;
+  if (variant == 3 || (variant == 0 && many)) launch(std::integral_constant<int, 8>{}, std::integral_constant<int, 1>{});
+  else if (variant == 2) launch(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
+  else launch(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
 }
 
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,

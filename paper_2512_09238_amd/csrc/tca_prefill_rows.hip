@@ -6,6 +6,9 @@
 // wave is split into four 16-lane groups; a group owns every fourth key, each
 // lane a D/16 slice of the row, so the q.k reduction is a 4-step butterfly and
 // the P.V accumulation needs no communication.  Groups are merged at the end.
+// Logits and the running maximum are fp64 (the products of fp32 or bf16 inputs are
+// exact in it), so that the exponent x - max carries no cancellation error even
+// when the logits are in the hundreds; exponentials, sums and P.V are fp32.
 #include <hip/hip_runtime.h>
 
 #include "tca_common.h"
@@ -32,7 +35,7 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     const T* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const T* __restrict__ K,
     const T* __restrict__ V, int64_t kv_stride, const int32_t* __restrict__ idx,
     const T* __restrict__ Kg, const T* __restrict__ Vg, HeadOffs ho,
-    const int32_t* __restrict__ n_rows, int G, int GS, int w, float scale, T* __restrict__ O,
+    const int32_t* __restrict__ n_rows, int G, int GS, int w, double scale, T* __restrict__ O,
     float* __restrict__ lse) {
   constexpr int EL = D / 16;                       // elements of a row per lane
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -42,9 +45,9 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
   if (r >= n_queries) return;
   const int64_t i = q_pos0 + r;                    // position of this query
 
-  float q[EL];
+  double q[EL];
 #pragma unroll
-  for (int e = 0; e < EL; ++e) q[e] = load_f32(Q + ((size_t)h * n_queries + r) * D + sub * EL + e) * scale;
+  for (int e = 0; e < EL; ++e) q[e] = (double)load_f32(Q + ((size_t)h * n_queries + r) * D + sub * EL + e);
 
   const int hs = h / GS;                           // the selection this query head reads
   const int64_t base = ho.offs[hs];
@@ -52,7 +55,8 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
   const int64_t win0 = i - w + 1 > 0 ? i - w + 1 : 0;
   const int64_t n_keys = n_glob + (i - win0 + 1);
 
-  float m = -INFINITY, l = 0.f, acc[EL];
+  double m = -INFINITY;
+  float l = 0.f, acc[EL];
 #pragma unroll
   for (int e = 0; e < EL; ++e) acc[e] = 0.f;
 
@@ -70,15 +74,15 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
         vr = V + row * D;
       }
     }
-    float s = 0.f;
+    double s = 0.0;
     if (ok) {
 #pragma unroll
-      for (int e = 0; e < EL; ++e) s = fmaf(q[e], load_f32(kr + sub * EL + e), s);
+      for (int e = 0; e < EL; ++e) s = fma(q[e], (double)load_f32(kr + sub * EL + e), s);
     }
-    s = group_sum(s, 16);
+    s = row16_sum(s) * scale;
     if (ok) {
-      const float mn = fmaxf(m, s);
-      const float corr = __expf(m - mn), pr = __expf(s - mn);
+      const double mn = fmax(m, s);
+      const float corr = expf((float)(m - mn)), pr = expf((float)(s - mn));   // m = -inf: corr = 0
       l = l * corr + pr;
 #pragma unroll
       for (int e = 0; e < EL; ++e) acc[e] = acc[e] * corr + pr * load_f32(vr + sub * EL + e);
@@ -87,10 +91,11 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
   }
   // merge the four groups (lanes with equal `sub`)
   for (int o = 16; o < 64; o <<= 1) {
-    const float mo = __shfl_xor(m, o, kWave), lo = __shfl_xor(l, o, kWave);
-    const float mn = fmaxf(m, mo);
-    const float ca = (m == -INFINITY) ? 0.f : __expf(m - mn);
-    const float cb = (mo == -INFINITY) ? 0.f : __expf(mo - mn);
+    const double mo = __shfl_xor(m, o, kWave);
+    const float lo = __shfl_xor(l, o, kWave);
+    const double mn = fmax(m, mo);
+    const float ca = (m == -INFINITY) ? 0.f : expf((float)(m - mn));
+    const float cb = (mo == -INFINITY) ? 0.f : expf((float)(mo - mn));
     l = l * ca + lo * cb;
 #pragma unroll
     for (int e = 0; e < EL; ++e) acc[e] = acc[e] * ca + __shfl_xor(acc[e], o, kWave) * cb;
@@ -100,7 +105,7 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     const float inv = 1.f / l;
 #pragma unroll
     for (int e = 0; e < EL; ++e) store_f32(O + ((size_t)h * n_queries + r) * D + sub * EL + e, acc[e] * inv);
-    if (lse && sub == 0) lse[(size_t)h * n_queries + r] = m + __logf(l);
+    if (lse && sub == 0) lse[(size_t)h * n_queries + r] = (float)(m + log((double)l));
   }
 }
 
@@ -113,7 +118,7 @@ int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64
   const int GS = sel_group(prm);
   const int G = prm->n_q_heads / prm->n_kv_heads;
   dim3 grid((unsigned)((n_queries + 3) / 4), prm->n_q_heads);
-  const float scale = (float)logit_scale(prm);
+  const double scale = logit_scale(prm);
   if (prm->head_dim == 128)
     hipLaunchKernelGGL((prefill_rows_kernel<T, 128>), grid, dim3(kRowThreads), 0, st, Q, q_pos0, n_queries,
                        K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse);

@@ -1,4 +1,4 @@
-"""The C-ABI library loads, exports every symbol include/tca.h declares, and
+"""The C-ABI library loads, exports every symbol include/*.h declares, and
 its host-side routines (no GPU) agree with the oracle and reject bad input."""
 import ctypes
 import os
@@ -13,9 +13,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
+    names = set()
+    for header in ("tca.h", "tca_diag.h"):       # the method's boundary, and the diagnostics beside it
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tca_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_the_boundary_header_holds_no_diagnostics():
     text = open(os.path.join(ROOT, "include", "tca.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tca_[a-z_0-9]+)\s*\(", text)))
+    assert "tca_probe" not in text and "tca_diag" not in text
 
 
 def test_library_exports_every_declared_symbol():
