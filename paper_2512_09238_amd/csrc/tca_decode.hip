@@ -754,35 +754,37 @@ extern "C" int tca_cache_load_window(const tca_params* prm, const tca_cache* cac
   return TCA_OK;
 }
 
-extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs, const void* q,
-                          const void* k_new, const void* v_new, const double* p, void* O, void* ws,
-                          size_t ws_bytes, void* stream) {
+// Argument checks and the four launches of a step, on a caller-visible scratch buffer.
+static int decode_step(const tca_params* prm, const tca_cache* cache, const int64_t* offs, const void* q,
+                       const void* k_new, const void* v_new, const double* p, void* O, void* ws, size_t ws_bytes,
+                       void* stream, const char* who) {
   int rc = check_params(prm);
   if (rc) return rc;
   rc = check_cache(prm, cache);
   if (rc) return rc;
   if (!offs || !q || !k_new || !v_new || !p || !O || !ws)
-    return fail(TCA_ERR_INVALID, "tca_decode: NULL pointer argument");
+    return fail(TCA_ERR_INVALID, "%s: NULL pointer argument", who);
   const int Hs = sel_heads(prm), b = prm->block, nk = block_log2(b) + 1;
   if (offs[0] != 0 || offs[Hs] != cache->cap_rows)
-    return fail(TCA_ERR_INVALID, "tca_decode: offs[0] must be 0 and offs[Hs] must equal cap_rows");
+    return fail(TCA_ERR_INVALID, "%s: offs[0] must be 0 and offs[Hs] must equal cap_rows", who);
   DecodeHeads dh;
   int64_t max_rows = 0;
   for (int h = 0; h < Hs; ++h) {
-    if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_decode: offs not ascending at %d", h);
+    if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "%s: offs not ascending at %d", who, h);
     if (offs[h + 1] - offs[h] > INT32_MAX) return fail(TCA_ERR_UNSUPPORTED, "head region beyond int32 rows");
     if (offs[h + 1] - offs[h] > max_rows) max_rows = offs[h + 1] - offs[h];
     if (!valid_config(p + (size_t)h * nk, nk))
-      return fail(TCA_ERR_INVALID, "tca_decode: p[%d] is not a distribution", h);
+      return fail(TCA_ERR_INVALID, "%s: p[%d] is not a distribution", who, h);
     dh.offs[h] = offs[h];
     dh.t_dec[h] = tca_decode_budget(b, p + (size_t)h * nk);
   }
   dh.offs[Hs] = offs[Hs];
   if (global_slots(prm, max_rows) + window_slots(prm) > kMaxSlots)
-    return fail(TCA_ERR_UNSUPPORTED, "tca_decode: more than %d split-K slots per head", kMaxSlots);
+    return fail(TCA_ERR_UNSUPPORTED, "%s: more than %d split-K slots per head", who, kMaxSlots);
   const size_t need = tca_decode_workspace_bytes(prm, cache->batch, max_rows);
   if (ws_bytes < need || ((uintptr_t)ws & 255))
-    return fail(TCA_ERR_WORKSPACE, "tca_decode: workspace needs %zu bytes, 256-byte aligned", need);
+    return fail(TCA_ERR_WORKSPACE, "%s: scratch needs %zu bytes, 256-byte aligned; %zu available", who, need,
+                ws_bytes);
   hipStream_t st = (hipStream_t)stream;
   if (prm->dtype == TCA_BF16) {
     using T = bf16_t;
@@ -798,4 +800,10 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
   if (rc) return rc;
   TCA_HIP_CHECK(hipGetLastError());
   return TCA_OK;
+}
+
+extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs, const void* q,
+                          const void* k_new, const void* v_new, const double* p, void* O, void* ws,
+                          size_t ws_bytes, void* stream) {
+  return decode_step(prm, cache, offs, q, k_new, v_new, p, O, ws, ws_bytes, stream, "tca_decode");
 }
