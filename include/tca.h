@@ -235,6 +235,21 @@ int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* off
                const void* q, const void* k_new, const void* v_new, const double* p,
                void* O, void* ws, size_t ws_bytes, void* stream);
 
+/* tca_decode for callers that cannot allocate or hand over scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels
+ * and results as tca_decode, minus (ws, ws_bytes): the split-K partials go to an array of
+ * TCA_DECODE_STATIC_BYTES bytes that is part of the library itself (each GPU the library runs on
+ * holds it until the process ends).  The call allocates and frees nothing.  A step whose
+ * tca_decode_workspace_bytes() exceeds TCA_DECODE_STATIC_BYTES is rejected with
+ * TCA_ERR_WORKSPACE and nothing is launched (32 MiB covers batch 16 x 32 query heads x 128K
+ * tokens at budgets up to 50 %).  Every call on one GPU uses the same array: nothing in it has
+ * to be cleared between calls (each step writes what it reads), but calls that overlap in time
+ * on one GPU - different streams, or a graph replay beside an eager call - race on it. */
+#define TCA_DECODE_STATIC_BYTES (32u << 20)
+int tca_decode_static(const tca_params* prm, const tca_cache* cache, const int64_t* offs,
+                      const void* q, const void* k_new, const void* v_new, const double* p,
+                      void* O, void* stream);
+
 /* Offline head-specific sparsity determination (Alg. 1) on one calibration sequence.
  *
  * For every query head: column means of the dense causal attention matrix

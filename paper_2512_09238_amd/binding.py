@@ -78,6 +78,8 @@ EXPORTS = {
                                         C.c_int64, C.c_int64, C.c_void_p]),
     "tca_decode": (C.c_int, [_P(tca_params), _P(tca_cache), _i64_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              _dbl_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_decode_static": (C.c_int, [_P(tca_params), _P(tca_cache), _i64_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    _dbl_p, C.c_void_p, C.c_void_p]),
     "tca_calibrate_budgets": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
                                         C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -223,6 +225,16 @@ def tca_decode(prm, cache, offs, q, k_new, v_new, p, O, ws, stream=None):
     wsp, wsb = _ws_args(ws)
     _check(lib.tca_decode(C.byref(prm), C.byref(cache), offs.ctypes.data_as(_i64_p), _dp(q), _dp(k_new),
                           _dp(v_new), p.ctypes.data_as(_dbl_p), _dp(O), wsp, wsb, _stream(stream)))
+
+
+TCA_DECODE_STATIC_BYTES = 32 << 20
+
+
+def tca_decode_static(prm, cache, offs, q, k_new, v_new, p, O, stream=None):
+    p = _host(p, np.float64)
+    offs = _host(offs, np.int64)
+    _check(lib.tca_decode_static(C.byref(prm), C.byref(cache), offs.ctypes.data_as(_i64_p), _dp(q), _dp(k_new),
+                                 _dp(v_new), p.ctypes.data_as(_dbl_p), _dp(O), _stream(stream)))
 
 
 def tca_calibrate_budgets(prm, Qcal, Kcal, L_cal, M, sigma, tau, ws, stream=None):

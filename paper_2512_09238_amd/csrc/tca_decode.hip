@@ -23,6 +23,7 @@
 //   advance : length += 1.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "tca_common.h"
@@ -806,4 +807,31 @@ extern "C" int tca_decode(const tca_params* prm, const tca_cache* cache, const i
                           const void* k_new, const void* v_new, const double* p, void* O, void* ws,
                           size_t ws_bytes, void* stream) {
   return decode_step(prm, cache, offs, q, k_new, v_new, p, O, ws, ws_bytes, stream, "tca_decode");
+}
+
+// ---- tca_decode_static: the same step for callers that cannot provide scratch memory.
+// The split-K partials live in an array that is part of the library's code object: every GPU the
+// library runs on holds its own copy, at its own address, from the moment the code object is
+// loaded until the process ends.  `scratch` below is only a host-side handle of that array; the
+// device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[TCA_DECODE_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];
+}  // namespace
+
+extern "C" int tca_decode_static(const tca_params* prm, const tca_cache* cache, const int64_t* offs, const void* q,
+                                 const void* k_new, const void* v_new, const double* p, void* O, void* stream) {
+  int dev = -1;
+  TCA_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(TCA_ERR_UNSUPPORTED, "tca_decode_static: device %d", dev);
+  void* ptr = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!ptr) {                                          // first call on this device (it is the current one)
+    TCA_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(TCA_ERR_HIP, "tca_decode_static: no device address for the scratch array");
+    g_scratch_addr[dev].store(ptr, std::memory_order_release);   // racing first calls store the same address
+  }
+  return decode_step(prm, cache, offs, q, k_new, v_new, p, O, ptr, (size_t)TCA_DECODE_STATIC_BYTES, stream,
+                     "tca_decode_static");
 }

@@ -339,8 +339,9 @@ def test_longest_single_call_4096_blocks_512k_tokens(tb, bufs):
 
 
 def test_diagnostics_clock_and_mfma_probe(tb, bufs):
-    """The MFMA probe returns plausible figures, and a bf16 prefill leaves the cycle / tick
-    sums of its attention kernel at the head of its workspace."""
+    """The MFMA probe returns plausible figures; a bf16 prefill leaves the cycle / tick sums of its
+    attention kernel at the head of its workspace when tca_diag_prefill_clocks is on, and does
+    not touch that place when it is off (the default)."""
     wsp = bufs.workspace(tb.tca_probe_workspace_bytes())
     tf_c, ghz_c = tb.tca_probe_mfma(False, 2000, wsp)
     tf_r, ghz_r = tb.tca_probe_mfma(True, 2000, wsp)
@@ -359,6 +360,13 @@ def test_diagnostics_clock_and_mfma_probe(tb, bufs):
     O = torch.empty_like(Qd)
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
-    ghz = tb.prefill_shader_clock_ghz(ws)
+    torch.cuda.synchronize()
+    assert bool((ws[:16] == 0xFF).all()), "clock counters written although the diagnostics switch is off"
+    try:
+        tb.tca_diag_prefill_clocks(True)
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+        ghz = tb.prefill_shader_clock_ghz(ws)
+    finally:
+        tb.tca_diag_prefill_clocks(False)
     print("prefill shader clock %.3f GHz" % ghz, flush=True)
     assert 0.3 < ghz < 2.6
