@@ -98,13 +98,16 @@ def test_calibration_full_length_two_heads(tb, bufs):
             assert got["cand_idx"][h] == ref[h].index and bool(got["fallback"][h]) == ref[h].fallback
 
 
-def test_decode_full_size_sampled_heads(tb, bufs):
-    """Config 4: batch 16 at 128K context.  Cache contents are drawn on the
-    device with a seeded torch generator; sampled (sequence, head) pairs are
-    copied to the host and checked against the oracle, including a sequence
-    whose block completes at the first step."""
+def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
+    """Config 4: batch 16 at 128K context, all 64 steps queued back to back.  Cache contents are
+    drawn on the device with a seeded torch generator; for sampled (sequence, head) pairs the host
+    keeps what the query can see (global rows, window, appended rows) and replays the steps with
+    the oracle's routines: outputs at the first step, at every step that completes a block of the
+    pair's sequence, at the step after it and at the last step; the global subsets (positions and
+    K rows) after the 64 steps bit for bit, which covers every block completed on the way."""
     c = wl.CONFIGS[4]
-    Hq, Hkv, d, T0, b, w, B = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"], c["batch"]
+    Hq, Hkv, d, T0, b, w, B, steps = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"], c["batch"], c["steps"]
+    G = Hq // Hkv
     prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
     fr = wl.budget_fractions(wl.budget_seed(4), Hq)
     P_gpu = np.stack([tb.tca_config_from_budget(b, c["sigma"], f) for f in fr])
@@ -116,7 +119,11 @@ def test_decode_full_size_sampled_heads(tb, bufs):
     rng = np.random.default_rng(wl.data_seed(4))
     pend = rng.integers(0, b, size=B)
     pend[3] = b - 1                                    # sequence 3 completes a block at step 0
+    pend[7] = b - 1 - 20                               # sequence 7 at step 20
+    pend[9] = b - steps                                # sequence 9 at the last step
     lengths = T0 + pend
+    done_at = {s: int(b - 1 - pend[s]) for s in range(B) if b - 1 - pend[s] < steps}
+    print("blocks complete at steps", done_at, flush=True)
     for s in range(B):
         cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=g, device="cuda", dtype=torch.float32))
         cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=g, device="cuda", dtype=torch.float32))
@@ -128,51 +135,61 @@ def test_decode_full_size_sampled_heads(tb, bufs):
     cache.ringK.copy_(torch.randn(cache.ringK.shape, generator=g, device="cuda", dtype=torch.float32))
     cache.ringV.copy_(torch.randn(cache.ringV.shape, generator=g, device="cuda", dtype=torch.float32))
     cache.length.copy_(torch.from_numpy(lengths.astype(np.int64)))
-    q = torch.randn(B, Hq, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    kn = torch.randn(B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    vn = torch.randn(B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    O = torch.full((B, Hq, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    q = torch.randn(steps, B, Hq, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    kn = torch.randn(steps, B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    vn = torch.randn(steps, B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    O = torch.full((steps, B, Hq, d), float("nan"), device="cuda", dtype=torch.bfloat16)
     ws = bufs.workspace(tb.tca_decode_workspace_bytes(prm, B, cache.max_head_rows))
-    # host copies of what the sampled pairs need, taken before the step
-    pairs = [(0, 0), (3, 5), (3, 31), (7, 13), (15, 31), (9, 18)]
+    # host copies of what the sampled pairs need, taken before the first step
+    pairs = [(0, 0), (3, 5), (3, 31), (7, 13), (7, 28), (9, 18), (15, 31)]
     before = {}
     for (s, h) in pairs:
         o, n = int(cache.offs[h]), int(n_glob[h])
-        kvh = h // (Hq // Hkv)
+        kvh = h // G
         before[(s, h)] = dict(idx=cache.idx[s, o:o + n].cpu().numpy().astype(np.int64),
                               Kg=cache.Kg[s, o:o + n].double().cpu().numpy(), Vg=cache.Vg[s, o:o + n].double().cpu().numpy(),
                               ringK=cache.ringK[s, kvh].double().cpu().numpy(), ringV=cache.ringV[s, kvh].double().cpu().numpy())
-    tb.tca_decode(prm, cache.view, cache.offs, q, kn, vn, P_gpu, O, ws)
+    for st in range(steps):                            # no host sync between the steps
+        tb.tca_decode(prm, cache.view, cache.offs, q[st], kn[st], vn[st], P_gpu, O[st], ws)
     torch.cuda.synchronize()
+    print("gpu done", flush=True)
     assert not torch.isnan(O.float()).any()
-    assert cache.length.cpu().tolist() == (lengths + 1).tolist()
-    worst = 0.0
+    assert cache.length.cpu().tolist() == (lengths + steps).tolist()
+    qh, knh, vnh, Oh = q.double().cpu().numpy(), kn.double().cpu().numpy(), vn.double().cpu().numpy(), O.double().cpu().numpy()
+    worst, n_checked, n_completed = 0.0, 0, 0
     for (s, h) in pairs:
-        kvh = h // (Hq // Hkv)
-        T = int(lengths[s])
+        kvh = h // G
+        T_first = int(lengths[s])
         bf = before[(s, h)]
-        # dense arrays holding only what the query can see: global rows and the window
-        Kfull = np.zeros((T + 1, d)); Vfull = np.zeros((T + 1, d))
+        # dense arrays holding only what the queries can see: global rows, the window, the new rows
+        Kfull = np.zeros((T_first + steps, d)); Vfull = np.zeros((T_first + steps, d))
         Kfull[bf["idx"]] = bf["Kg"]; Vfull[bf["idx"]] = bf["Vg"]
-        for p in range(T - w + 1, T):
+        for p in range(T_first - w + 1, T_first):
             Kfull[p] = bf["ringK"][p % w]; Vfull[p] = bf["ringV"][p % w]
-        Kfull[T] = kn[s, kvh].double().cpu().numpy(); Vfull[T] = vn[s, kvh].double().cpu().numpy()
-        qv = q[s, h].double().cpu().numpy()
-        ref = orc.attention_row(qv, T, Kfull, Vfull, bf["idx"], w)
-        worst = max(worst, float(np.abs(ref - O[s, h].double().cpu().numpy()).max()))
-        o = int(cache.offs[h])
-        n_now = int(cache.n_rows[s, h].item())
-        if (T + 1) % b == 0:
-            blk = T // b
-            x = orc.last_query_logits(qv, Kfull[blk * b:(blk + 1) * b])
-            keep = blk * b + orc.top_t(x, orc.decode_budget(b, P_orc[h]))
-            assert n_now == n_glob[h] + len(keep)
-            assert np.array_equal(cache.idx[s, o + int(n_glob[h]):o + n_now].cpu().numpy(), keep)
-            kg_new = cache.Kg[s, o + int(n_glob[h]):o + n_now].double().cpu().numpy()
-            assert np.array_equal(kg_new, Kfull[keep])
-        else:
-            assert n_now == n_glob[h]
-    print("max abs err on sampled (sequence, head) pairs:", worst, flush=True)
+        S = bf["idx"].copy()
+        check = {0, steps - 1}
+        if s in done_at:
+            check |= {done_at[s], min(done_at[s] + 1, steps - 1)}
+        for st in range(steps):
+            T = T_first + st
+            Kfull[T] = knh[st, s, kvh]; Vfull[T] = vnh[st, s, kvh]
+            if st in check:
+                ref = orc.attention_row(qh[st, s, h], T, Kfull[:T + 1], Vfull[:T + 1], S, w)
+                worst = max(worst, float(np.abs(ref - Oh[st, s, h]).max()))
+                n_checked += 1
+            if (T + 1) % b == 0:                       # the block completed by this token (Sec. IV-B, decoding stage)
+                blk = T // b
+                x = orc.last_query_logits(qh[st, s, h], Kfull[blk * b:(blk + 1) * b])
+                S = np.concatenate([S, blk * b + orc.top_t(x, orc.decode_budget(b, P_orc[h]))])
+                n_completed += 1
+        o, n_now = int(cache.offs[h]), int(cache.n_rows[s, h].item())
+        assert n_now == len(S), (s, h)
+        assert np.array_equal(cache.idx[s, o:o + n_now].cpu().numpy(), S), (s, h)
+        new_rows = S[len(bf["idx"]):]
+        assert np.array_equal(cache.Kg[s, o + len(bf["idx"]):o + n_now].double().cpu().numpy(), Kfull[new_rows]), (s, h)
+        assert np.array_equal(cache.Vg[s, o + len(bf["idx"]):o + n_now].double().cpu().numpy(), Vfull[new_rows]), (s, h)
+    assert n_completed >= 5
+    print("max abs err on", n_checked, "sampled (step, sequence, head) outputs:", worst, "; blocks completed:", n_completed, flush=True)
     assert worst <= H.TOL["bf16"]
 
 
@@ -272,11 +289,11 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     cal = tb.tca_calibrate_budgets(prm, bufs.to_device(xc["Q"]), bufs.to_device(xc["K"]), c["L_cal"], c["M"],
                                    c["sigma"], c["tau"], wsc)
     print("candidates", cal["cand_idx"].tolist(), flush=True)
-    heads = [0, 13, Hq - 1]
-    P_orc = {}
+    heads = [0, 13, Hq - 1]                              # calibrated by the oracle itself, and attended on sampled rows
+    cands_orc = orc.candidates(b, c["M"], c["sigma"])
+    P_orc = {h: cands_orc[int(cal["cand_idx"][h])] for h in range(Hq)}   # the other heads: the oracle's own candidate of that index
     for h in heads:
-        ch = orc.calibrate_head(wl.to_f64(xc["Q"][h]), wl.to_f64(xc["K"][h // G]), b,
-                                orc.candidates(b, c["M"], c["sigma"]), c["tau"], c["alpha"])
+        ch = orc.calibrate_head(wl.to_f64(xc["Q"][h]), wl.to_f64(xc["K"][h // G]), b, cands_orc, c["tau"], c["alpha"])
         assert ch.index == cal["cand_idx"][h], f"calibration of head {h}"
         P_orc[h] = ch.p
     del xc, wsc
@@ -290,11 +307,12 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     pos = _sample_positions(L, w, b, 10, 7)
     Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
     worst = 0.0
+    for h in range(Hq):                                  # the index sets of all heads, in full
+        sel = orc.select(wl.to_f64(x["Q"][h, L - 1]), wl.to_f64(x["K"][h // G]), b, P_orc[h], c["alpha"])
+        H.assert_selection(sel, H.head_indices(gb, h), b, P_orc[h], tag=f"cfg3 calibrated head {h}")
     for h in heads:
         Kf, Vf = wl.to_f64(x["K"][h // G]), wl.to_f64(x["V"][h // G])
-        sel = orc.select(wl.to_f64(x["Q"][h, L - 1]), Kf, b, P_orc[h], c["alpha"])
         got = H.head_indices(gb, h)
-        H.assert_selection(sel, got, b, P_orc[h], tag=f"cfg3 calibrated head {h}")
         qh = wl.to_f64(x["Q"][h][pos])
         for n, i in enumerate(pos):
             ref = orc.attention_row(qh[n], int(i), Kf, Vf, got, w)
