@@ -41,6 +41,12 @@ here and the only behaviour the GPU path implements):
     query head of the group attends to the shared set.  See the section
     "Group-shared selection" below.
 
+  * layer integration around the path (extensions, not in the paper, which takes Q, K, V as
+    given, post position encoding): rotary position embedding of Q and K (`rope_rotate`, the
+    published RoFormer rotation), an FP8 E4M3 decode cache with one scale per row
+    (`quantize_rows_fp8`; `kv_quant="fp8"` in the cache routines), and calibration of several
+    layers (`calibrate_layers`: Alg. 1 once per layer).  See "Layer integration" below.
+
 Functions pinned by tests/test_oracle_pins.py; none is "parity unpinned"
 except the readings listed above, which are choices rather than facts.
 """
@@ -443,13 +449,21 @@ class HeadCache:
         return 0 if self.K is None else self.K.shape[1]
 
 
-def cache_after_prefill(K, V, sels: list[Selection]) -> HeadCache:
-    """State after Alg. 2: global = S (all of it), local = the dense rows."""
-    return HeadCache(S=[s.S.copy() for s in sels], K=np.asarray(K, F64).copy(), V=np.asarray(V, F64).copy())
+def cache_after_prefill(K, V, sels: list[Selection], kv_quant: str | None = None) -> HeadCache:
+    """State after Alg. 2: global = S (all of it), local = the dense rows.
+    kv_quant="fp8": the cache stores every row as FP8 E4M3 codes with one scale per row; what the
+    decode steps read is the dequantised row (quantisation is per row, so quantising all rows and
+    reading those in S or in the window is the same as quantising only what the cache keeps)."""
+    K, V = np.asarray(K, F64), np.asarray(V, F64)
+    if kv_quant == "fp8":
+        K, V = roundtrip_rows_fp8(K), roundtrip_rows_fp8(V)
+    elif kv_quant is not None:
+        raise ValueError(kv_quant)
+    return HeadCache(S=[s.S.copy() for s in sels], K=K.copy(), V=V.copy())
 
 
 def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: float | None = None,
-                share: bool = False) -> np.ndarray:
+                share: bool = False, kv_quant: str | None = None) -> np.ndarray:
     """One generated token.  q [Hq,d]; k_new, v_new [Hkv,d] are the rows of the
     token at position T = cache.length, appended before attending.
 
@@ -459,6 +473,8 @@ def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: flo
     t = floor(sum_k k p_k) positions are appended to the head's global subset.
     share: cache.S and p are per KV head; the block's rows are ranked by the group
     mean of the heads' scores, each normalised over the block.
+    kv_quant="fp8": the new rows enter the cache as FP8 codes with a scale per row; attention and
+    the scoring of a completed block read the dequantised rows.
     """
     q = np.asarray(q, F64)
     Hq, d = q.shape
@@ -466,6 +482,10 @@ def decode_step(cache: HeadCache, q, k_new, v_new, b: int, w: int, p, scale: flo
     T = cache.length
     k_new = np.asarray(k_new, F64)[:, None, :]
     v_new = np.asarray(v_new, F64)[:, None, :]
+    if kv_quant == "fp8":
+        k_new, v_new = roundtrip_rows_fp8(k_new), roundtrip_rows_fp8(v_new)
+    elif kv_quant is not None:
+        raise ValueError(kv_quant)
     cache.K = k_new if cache.K is None else np.concatenate([cache.K, k_new], axis=1)
     cache.V = v_new if cache.V is None else np.concatenate([cache.V, v_new], axis=1)
     out = np.empty((Hq, cache.V.shape[2]), F64)
@@ -593,3 +613,98 @@ def theorem_quantities(q_i, i: int, K, V, S, w: int, scale: float | None = None)
     s_sparse[T] = softmax(K[T] @ q_i * sc)
     l1 = float(np.abs(s_full - s_sparse).sum())
     return gamma, l1, s_full @ V[: i + 1], s_sparse @ V[: i + 1]
+
+
+# --------------------------------------------------------------------------
+# Layer integration (extensions around the path; none of this is in the paper)
+# --------------------------------------------------------------------------
+# FP8 E4M3 (OCP 8-bit floating point, "E4M3": 1 sign, 4 exponent bits with bias 7, 3 mantissa
+# bits; no infinities; S.1111.111 is NaN; largest finite value 448 = 1.75 * 2^8; subnormals
+# m/8 * 2^-6).  A cache row x of d numbers is stored as d codes and one float32 scale:
+#     amax = max_i |x_i|,  scale = amax / 448 (1 if amax = 0),  code_i = RNE_e4m3(x_i / scale)
+# with the two divisions in float32 (the decision of a code is taken in the precision the
+# kernel takes it in); the row read back is code_i * scale, exact in float64.
+FP8_MAX = 448.0
+
+
+def fp8_e4m3_values() -> np.ndarray:
+    """The 256 codes' values in float64, written out from the format definition (NaN for 0x7f, 0xff)."""
+    out = np.empty(256, F64)
+    for code in range(256):
+        sign = -1.0 if code & 0x80 else 1.0
+        e, m = (code >> 3) & 0xF, code & 0x7
+        if e == 0xF and m == 0x7:
+            out[code] = np.nan
+        elif e == 0:
+            out[code] = sign * (m / 8.0) * 2.0 ** -6
+        else:
+            out[code] = sign * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return out
+
+
+def fp8_e4m3_encode(y) -> np.ndarray:
+    """Round-to-nearest-even of float32 numbers to E4M3 codes, saturating at +-448.  Done by
+    search over the table of values, not by bit manipulation: the nearest representable value
+    wins, a tie goes to the code with an even mantissa field."""
+    y = np.asarray(y, np.float32).astype(F64)
+    vals = fp8_e4m3_values()
+    pos_codes = np.arange(0, 0x7F)                       # 0 .. 448, ascending in value
+    pos_vals = vals[pos_codes]
+    a = np.minimum(np.abs(y), FP8_MAX)
+    hi = np.searchsorted(pos_vals, a, side="left")       # first value >= a
+    hi = np.minimum(hi, len(pos_vals) - 1)
+    lo = np.maximum(hi - 1, 0)
+    d_lo, d_hi = a - pos_vals[lo], pos_vals[hi] - a
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (pos_codes[hi] % 2 == 0))
+    code = np.where(take_hi, pos_codes[hi], pos_codes[lo]).astype(np.uint8)
+    return np.where(np.signbit(y), code | 0x80, code).astype(np.uint8)
+
+
+def quantize_rows_fp8(X):
+    """Rows along the last axis -> (codes uint8, same shape; scales float32, one per row)."""
+    X32 = np.asarray(X, np.float32)
+    amax = np.max(np.abs(X32), axis=-1)
+    scale = np.where(amax > 0, amax / np.float32(FP8_MAX), np.float32(1.0)).astype(np.float32)
+    y = (X32 / scale[..., None]).astype(np.float32)
+    return fp8_e4m3_encode(y), scale
+
+
+def dequantize_rows_fp8(codes, scales) -> np.ndarray:
+    return fp8_e4m3_values()[np.asarray(codes, np.uint8)] * np.asarray(scales, F64)[..., None]
+
+
+def roundtrip_rows_fp8(X) -> np.ndarray:
+    """What an FP8 cache returns for the rows X."""
+    return dequantize_rows_fp8(*quantize_rows_fp8(X))
+
+
+def rope_rotate(X, positions, base: float = 10000.0, pairing: str = "half") -> np.ndarray:
+    """Rotary position embedding (the RoFormer rotation) of the rows of X [..., n, d] at the given
+    positions [n]: the pair (x_a, x_b) of a row at position t is turned by the angle
+    t * base^(-2 i / d), i = 0 .. d/2-1.  pairing="half": pair i is (i, i + d/2) (the layout of
+    Llama-family checkpoints); "interleaved": pair i is (2i, 2i+1) (the original paper's)."""
+    X = np.asarray(X, F64)
+    d = X.shape[-1]
+    t = np.asarray(positions, F64)
+    inv_freq = base ** (-2.0 * np.arange(d // 2, dtype=F64) / d)
+    ang = t[:, None] * inv_freq[None, :]                 # [n, d/2]
+    c, s = np.cos(ang), np.sin(ang)
+    out = np.empty_like(X)
+    if pairing == "half":
+        a, b = X[..., : d // 2], X[..., d // 2:]
+        out[..., : d // 2] = a * c - b * s
+        out[..., d // 2:] = b * c + a * s
+    elif pairing == "interleaved":
+        a, b = X[..., 0::2], X[..., 1::2]
+        out[..., 0::2] = a * c - b * s
+        out[..., 1::2] = b * c + a * s
+    else:
+        raise ValueError(pairing)
+    return out
+
+
+def calibrate_layers(Qs, Ks, b: int, M: int, sigma: float, tau: float, alpha: float, share: bool = False):
+    """Alg. 1 applied to every layer of a model in turn (Sec. IV-A: the determination is made
+    once per model, for all heads of all layers): Qs[l] [Hq, L, d], Ks[l] [Hkv, L, d] are the
+    calibration sample's queries and keys at layer l.  Returns one list of Calibration per layer."""
+    return [calibrate(Qs[l], Ks[l], b, M, sigma, tau, alpha, share=share) for l in range(len(Qs))]

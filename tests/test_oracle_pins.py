@@ -608,3 +608,141 @@ def test_group_shared_attention_decode_and_calibration():
     S2 = orc.select_shared(Q[:2, L - 1], K[0], b, cands[2], 0.5).S
     cm = 0.5 * (orc.column_means(orc.dense_causal_probs(Q[0], K[0])) + orc.column_means(orc.dense_causal_probs(Q[1], K[0])))
     assert abs(cal.a[2] - cm[S2].sum()) < 1e-13
+
+
+# --------------------------------------------------------------------------
+# Layer integration (extensions): FP8 cache rows, rotary embedding, several layers
+# --------------------------------------------------------------------------
+def _fp8_fixture():
+    vals, rounds, row = [], [], {}
+    for line in open(os.path.join(GOLD, "fp8_e4m3_codes.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "round":
+            rounds.append((float(t[1]), int(t[2], 16)))
+        elif t[0] in ("row", "scale", "codes"):
+            row[t[0]] = [int(v, 16) if t[0] == "codes" else float(v) for v in t[1:]]
+        else:
+            vals.append((int(t[0], 16), float(t[1])))
+    return vals, rounds, row
+
+
+def test_fp8_format_against_hand_values_and_the_library_type():
+    import torch
+    vals, rounds, row = _fp8_fixture()
+    table = orc.fp8_e4m3_values()
+    for code, v in vals:
+        assert table[code] == v, hex(code)
+    assert np.isnan(table[0x7F]) and np.isnan(table[0xFF]) and np.nanmax(table) == 448.0
+    # the whole table against the library's float8 type
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.nan_to_num(table, nan=-1.0), np.nan_to_num(lib, nan=-1.0))
+    for y, code in rounds:
+        assert int(orc.fp8_e4m3_encode(np.float32(y))) == code, y
+    # rounding of many numbers against the library's conversion (which does not saturate: clip first)
+    rng = np.random.default_rng(5)
+    y = np.concatenate([(rng.standard_normal(50000) * s).astype(np.float32) for s in (1e-3, 0.05, 1.0, 30.0, 200.0)])
+    ref = torch.from_numpy(np.clip(y, -448, 448)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = orc.fp8_e4m3_encode(y)
+    nz = y != 0                                           # the sign of a zero is not a matter of rounding
+    assert np.array_equal(got[nz], ref[nz])
+    # every representable value encodes to itself
+    finite = ~np.isnan(table)
+    assert np.array_equal(orc.fp8_e4m3_encode(table[finite].astype(np.float32))[1:], np.arange(256)[finite][1:])
+    # a planted mistake (ties rounded away from zero instead of to even) fails the fixture
+    away = lambda y: int(orc.fp8_e4m3_encode(np.float32(np.nextafter(np.float32(y), np.float32(1e9)))))
+    assert away(1.0625) != dict(rounds)[1.0625]
+
+
+def test_fp8_rows_scale_rule_and_error_bound():
+    _, _, row = _fp8_fixture()
+    codes, scale = orc.quantize_rows_fp8(np.array([row["row"]]))
+    assert codes[0].tolist() == row["codes"] and float(scale[0]) == row["scale"][0]
+    assert np.array_equal(orc.roundtrip_rows_fp8(np.array([row["row"]]))[0], np.array(row["row"]))
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((200, 128)) * rng.uniform(0.01, 50, size=(200, 1))
+    X[7] = 0.0
+    codes, scale = orc.quantize_rows_fp8(X)
+    assert codes.dtype == np.uint8 and scale.dtype == np.float32 and scale[7] == 1.0 and not codes[7].any()
+    amax = np.abs(X.astype(np.float32)).max(axis=1)
+    big = np.abs(X.astype(np.float32)) == amax[:, None]
+    assert np.all((codes[big & (amax[:, None] > 0)] & 0x7F) == 0x7E)        # the row's largest entry sits at +-448
+    R = orc.dequantize_rows_fp8(codes, scale)
+    # normal range: half a unit of a 3-bit mantissa (2^-4 relative); below 2^-6 * scale: half a subnormal step
+    err = np.abs(R - X.astype(np.float32))
+    bound = np.maximum(np.abs(X) * 2.0 ** -4, scale[:, None] * 2.0 ** -10) * (1 + 1e-6)
+    assert np.all(err <= bound)
+    assert np.all(np.sign(R) * np.sign(X) >= 0)
+
+
+def test_decode_step_with_an_fp8_cache_reads_dequantised_rows():
+    """The cache mode is Eq. 2 over rows that went through the FP8 store: checked against the plain
+    attention routine fed rows converted by the library's float8 type with the row scales."""
+    import torch
+    rng = np.random.default_rng(8)
+    Hq, Hkv, d, L, b, w = 2, 1, 16, 40, 4, 8
+    Q, K, V = rng.standard_normal((Hq, L, d)), rng.standard_normal((Hkv, L, d)) * 3, rng.standard_normal((Hkv, L, d))
+    P = np.stack([orc.config_from_budget(b, 1.0, 0.5)] * Hq)
+    sels = orc.select_all_heads(Q[:, L - 1], K, b, P, 0.5)
+    cache = orc.cache_after_prefill(K, V, sels, kv_quant="fp8")
+    q, kn, vn = rng.standard_normal((Hq, d)), rng.standard_normal((Hkv, d)), rng.standard_normal((Hkv, d))
+    out = orc.decode_step(cache, q, kn, vn, b, w, P, kv_quant="fp8")
+
+    def lib_roundtrip(X):
+        X32 = torch.from_numpy(np.asarray(X, np.float32))
+        amax = X32.abs().amax(dim=-1, keepdim=True)
+        scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+        return ((X32 / scale).clamp(-448, 448).to(torch.float8_e4m3fn).to(torch.float64) * scale.to(torch.float64)).numpy()
+
+    Kq = np.concatenate([lib_roundtrip(K), lib_roundtrip(kn)[:, None]], axis=1)
+    Vq = np.concatenate([lib_roundtrip(V), lib_roundtrip(vn)[:, None]], axis=1)
+    for h in range(Hq):
+        ref = orc.attention_row(q[h], L, Kq[0], Vq[0], sels[h].S, w)
+        np.testing.assert_allclose(out[h], ref, rtol=1e-12, atol=1e-14)
+    assert cache.length == L + 1 and np.array_equal(cache.K[0, L], Kq[0, L])
+    # and it differs from the unquantised step by no more than the rows' rounding allows
+    plain = orc.decode_step(orc.cache_after_prefill(K, V, sels), q, kn, vn, b, w, P)
+    assert 0 < np.abs(plain - out).max() < 0.5
+
+
+def test_rope_hand_example_complex_rotation_and_invariants():
+    rows = [list(map(float, l.split())) for l in open(os.path.join(GOLD, "rope_d4.txt")) if l.strip() and not l.startswith("#")]
+    x = np.array([[1.0, 2.0, 3.0, 4.0]])
+    np.testing.assert_allclose(orc.rope_rotate(x, [2], pairing="half")[0], rows[0], atol=5e-10)
+    np.testing.assert_allclose(orc.rope_rotate(x, [2], pairing="interleaved")[0], rows[1], atol=5e-10)
+    rng = np.random.default_rng(9)
+    n, d = 7, 16
+    X, pos = rng.standard_normal((3, n, d)), rng.integers(0, 5000, size=n)
+    R = orc.rope_rotate(X, pos)
+    # the rotation written with complex numbers: (a + ib) e^{i t f}
+    f = 10000.0 ** (-2.0 * np.arange(d // 2) / d)
+    z = (X[..., : d // 2] + 1j * X[..., d // 2:]) * np.exp(1j * pos[:, None] * f[None, :])
+    np.testing.assert_allclose(R[..., : d // 2], z.real, atol=1e-12)
+    np.testing.assert_allclose(R[..., d // 2:], z.imag, atol=1e-12)
+    np.testing.assert_allclose(np.linalg.norm(R, axis=-1), np.linalg.norm(X, axis=-1), rtol=1e-13)
+    assert np.array_equal(orc.rope_rotate(X, np.zeros(n)), X)
+    # q_m . k_n depends on m - n only; rotating by a then by b is rotating by a + b
+    q, k = rng.standard_normal((1, d)), rng.standard_normal((1, d))
+    d1 = orc.rope_rotate(q, [37]) @ orc.rope_rotate(k, [30]).T
+    d2 = orc.rope_rotate(q, [1007]) @ orc.rope_rotate(k, [1000]).T
+    np.testing.assert_allclose(d1, d2, rtol=1e-10)
+    np.testing.assert_allclose(orc.rope_rotate(orc.rope_rotate(q, [11]), [31]), orc.rope_rotate(q, [42]), atol=1e-12)
+    # the two pairings are one rotation seen through a permutation of the coordinates
+    perm = np.concatenate([np.arange(0, d, 2), np.arange(1, d, 2)])
+    np.testing.assert_allclose(orc.rope_rotate(X, pos, pairing="interleaved")[..., perm], orc.rope_rotate(X[..., perm], pos), atol=1e-12)
+
+
+def test_calibrate_layers_is_alg1_layer_by_layer():
+    rng = np.random.default_rng(10)
+    Hq, Hkv, d, L, b, M = 2, 1, 8, 64, 4, 5
+    Qs = [rng.standard_normal((Hq, L, d)) * g for g in (0.5, 3.0, 8.0)]
+    Ks = [rng.standard_normal((Hkv, L, d)) for _ in range(3)]
+    out = orc.calibrate_layers(Qs, Ks, b, M, 1.0, 0.9, 0.5)
+    assert len(out) == 3 and all(len(layer) == Hq for layer in out)
+    for l in range(3):
+        for h in range(Hq):
+            one = orc.calibrate_head(Qs[l][h], Ks[l][0], b, orc.candidates(b, M, 1.0), 0.9, 0.5)
+            assert out[l][h].index == one.index and np.array_equal(out[l][h].p, one.p)
+    # sharper queries concentrate attention: the peaked layer never needs a larger candidate than the flat one
+    assert max(c.index for c in out[2]) <= max(c.index for c in out[0])
