@@ -178,7 +178,8 @@ def cpu_baseline_prefill(host, cfg, wl, bufs, seconds=20.0, seed=5):
     }
 
 
-def bench_decode(args, tb, bufs, wl, torch, share=False):
+def bench_decode(args, tb, bufs, wl, torch, share=False, fp8=False):
+    """fp8: the cache rows are FP8 E4M3 codes with one scale per row (TCA_KV_FP8)."""
     cfg = dict(wl.CONFIGS[4])
     Hq, Hkv, d, T0, b, w, B, steps = (cfg[k] for k in ("Hq", "Hkv", "d", "L", "b", "w", "batch", "steps"))
     if args.decode_batch:
@@ -191,21 +192,31 @@ def bench_decode(args, tb, bufs, wl, torch, share=False):
     n_glob = np.round(fr * (T0 - w)).astype(np.int64)
     t_dec = np.array([tb.tca_decode_budget(b, p) for p in P])
     cap = n_glob + t_dec * (steps // b + 2)
-    cache = bufs.DecodeCache(prm, B, cap)
+    cache = bufs.DecodeCache(prm, B, cap, kv_format=tb.TCA_KV_FP8 if fp8 else tb.TCA_KV_NATIVE)
     g = torch.Generator(device="cuda").manual_seed(wl.data_seed(4))
     rng = np.random.default_rng(wl.data_seed(4))
     pend = rng.integers(0, b, size=B)                     # pending tokens of the open block
     lengths = T0 + pend
+
+    def fill(rows, scales):
+        if not fp8:
+            rows.copy_(torch.randn(rows.shape, generator=g, device="cuda", dtype=torch.float32))
+            return
+        codes = torch.randint(0, 256, rows.shape, generator=g, device="cuda", dtype=torch.uint8)
+        codes[(codes & 0x7F) == 0x7F] = 0                 # the two NaN codes
+        rows.copy_(codes)
+        scales.copy_(torch.rand(scales.shape, generator=g, device="cuda") * 0.015 + 0.005)
+
     for s in range(B):
-        cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=g, device="cuda", dtype=torch.float32))
-        cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=g, device="cuda", dtype=torch.float32))
+        fill(cache.Kg[s], cache.Kg_scale[s] if fp8 else None)
+        fill(cache.Vg[s], cache.Vg_scale[s] if fp8 else None)
         for h in range(Hs):
             o = int(cache.offs[h])
             pos = np.sort(rng.choice(T0 - w, size=int(n_glob[h]), replace=False)).astype(np.int32)
             cache.idx[s, o:o + len(pos)] = torch.from_numpy(pos).cuda()
     cache.n_rows.copy_(torch.from_numpy(np.tile(n_glob.astype(np.int32), (B, 1))))
-    cache.ringK.copy_(torch.randn(cache.ringK.shape, generator=g, device="cuda", dtype=torch.float32))
-    cache.ringV.copy_(torch.randn(cache.ringV.shape, generator=g, device="cuda", dtype=torch.float32))
+    fill(cache.ringK, cache.ringK_scale)
+    fill(cache.ringV, cache.ringV_scale)
     cache.length.copy_(torch.from_numpy(lengths.astype(np.int64)))
     q = torch.randn(steps, B, Hq, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     kn = torch.randn(steps, B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
@@ -222,9 +233,10 @@ def bench_decode(args, tb, bufs, wl, torch, share=False):
         ev[s + 1].record()
     torch.cuda.synchronize()
     us = np.array([ev[s].elapsed_time(ev[s + 1]) * 1e3 for s in range(steps)])
-    e = 2
-    bytes_step = B * (int(n_glob.sum()) * 2 * d * e + Hkv * w * 2 * d * e)
+    row_bytes = (d + 4) if fp8 else 2 * d                 # a cache row: codes and a float scale, or bf16 elements
+    bytes_step = B * (int(n_glob.sum()) * 2 * row_bytes + Hkv * w * 2 * row_bytes)
     res = {
+        "kv_format": "fp8 e4m3 + scale per row" if fp8 else "bf16",
         "batch": B, "context": T0, "steps": steps, "us_per_step_mean": float(us.mean()),
         "us_per_step_p50": float(np.percentile(us, 50)), "us_per_step_p99": float(np.percentile(us, 99)),
         "algorithmic_bytes_per_step": bytes_step,
@@ -232,7 +244,7 @@ def bench_decode(args, tb, bufs, wl, torch, share=False):
         "frac": bytes_step / (us.mean() * 1e-6) / 1e9 / PEAK_HBM_GBS,
         "mean_budget": float(fr.mean()),
     }
-    log(f"[bench] decode: {res['us_per_step_mean']:.1f} us/step, {res['achieved_gbs']:.0f} GB/s")
+    log(f"[bench] decode ({res['kv_format']}{', shared selection' if share else ''}): {res['us_per_step_mean']:.1f} us/step, {res['achieved_gbs']:.0f} GB/s")
     return res
 
 
@@ -340,6 +352,7 @@ def main():
     del host
     torch.cuda.empty_cache()
     dec = None if args.no_decode else bench_decode(args, tb, bufs, wl, torch)
+    dec_fp8 = None if args.no_decode else bench_decode(args, tb, bufs, wl, torch, fp8=True)
     if shared is not None and not args.no_decode:
         shared["decode"] = bench_decode(args, tb, bufs, wl, torch, share=True)
     mixed = bench_mixed(args, tb, bufs, wl, torch) if args.mixed else None
@@ -375,6 +388,7 @@ def main():
         },
         "cpu_baseline": cpu,
         "decode": dec,
+        "decode_fp8_cache": dec_fp8,
     }
     if mixed is not None:
         out["mixed_batch"] = mixed

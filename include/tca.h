@@ -190,27 +190,54 @@ int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_
                 const int64_t* offs, const int32_t* n_rows,
                 void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/* Storage of the rows of the decode cache.  TCA_KV_NATIVE: rows of tca_params.dtype.
+ * TCA_KV_FP8 (an extension, not in the paper; requires dtype TCA_BF16): a row x of d numbers is
+ * kept as d FP8 E4M3 codes (OCP 8-bit floating point: bias 7, largest finite value 448, no
+ * infinities) and one float scale:
+ *     amax = max_i |x_i|,   scale = amax / 448  (1 if amax = 0),   code_i = RNE_e4m3(x_i / scale)
+ * with both divisions in float32; what decode reads back is code_i * scale.  The cache then
+ * takes 1 + 4/d bytes per element instead of 2. */
+#define TCA_KV_NATIVE 0
+#define TCA_KV_FP8    1
+
 /* KV cache of a batch of sequences that share one set of per-head budgets
  * (budgets belong to the model, Sec. IV-A).  All pointers are device memory. */
 typedef struct tca_cache {
   int32_t  batch;      /* B                                                            */
   int64_t  cap_rows;   /* rows of the flat global buffer per sequence (= offs[Hs])      */
   int32_t* idx;        /* [B, cap_rows]     positions of the global rows                */
-  void*    Kg;         /* [B, cap_rows, d]                                              */
+  void*    Kg;         /* [B, cap_rows, d]  (TCA_KV_FP8: one byte per element)          */
   void*    Vg;         /* [B, cap_rows, d]                                              */
   int32_t* n_rows;     /* [B, Hs]           rows filled per head (updated by the library) */
   void*    ringK;      /* [B, Hkv, w, d]    last w dense rows, position P at slot P mod w */
   void*    ringV;      /* [B, Hkv, w, d]                                                */
   int64_t* length;     /* [B]               tokens seen so far (updated by the library)  */
+  int32_t  kv_format;  /* TCA_KV_NATIVE or TCA_KV_FP8                                    */
+  float*   Kg_scale;   /* [B, cap_rows]     TCA_KV_FP8 only (else ignored, may be NULL)  */
+  float*   Vg_scale;   /* [B, cap_rows]                                                  */
+  float*   ringK_scale;/* [B, Hkv, w]                                                    */
+  float*   ringV_scale;/* [B, Hkv, w]                                                    */
 } tca_cache;
 
 /* Hand a prefilled sequence over to the decode cache: copies dense rows
- * [max(0,L-w), L) of K and V into sequence `seq`'s ring (slot = position mod w)
- * and sets length[seq] = L.  The global region of that sequence is whatever
- * tca_select wrote there (pass idx + seq*cap_rows etc. to tca_select).
+ * [max(0,L-w), L) of K and V into sequence `seq`'s ring (slot = position mod w;
+ * TCA_KV_FP8: as codes and scales) and sets length[seq] = L.  With TCA_KV_NATIVE
+ * the global region of that sequence is whatever tca_select wrote there (pass
+ * idx + seq*cap_rows etc. to tca_select); with TCA_KV_FP8 see tca_cache_load_global.
  * K, V: device [Hkv, kv_stride, d].  Does not synchronise. */
 int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq,
                           const void* K, const void* V, int64_t kv_stride, int64_t L, void* stream);
+
+/* Copies the global subset of one prefilled sequence, as tca_select left it in buffers of
+ * tca_params.dtype, into sequence `seq` of the cache in the cache's storage format (the way
+ * into a TCA_KV_FP8 cache; a plain copy with TCA_KV_NATIVE): rows offs[n] .. offs[n] +
+ * n_rows[n] - 1 of every selection head n, their positions, and n_rows.
+ *   idx, Kg, Vg : device, [offs[Hs]] / [offs[Hs], d], as written by tca_select
+ *   offs        : host [Hs+1], offs[Hs] == cache->cap_rows;  n_rows: device int32 [Hs]
+ * Does not synchronise. */
+int tca_cache_load_global(const tca_params* prm, const tca_cache* cache, int seq,
+                          const int32_t* idx, const void* Kg, const void* Vg,
+                          const int64_t* offs, const int32_t* n_rows, void* stream);
 
 /* One decode step for every sequence of the batch (Sec. IV-B, last paragraph).
  *
@@ -230,7 +257,10 @@ int tca_cache_load_window(const tca_params* prm, const tca_cache* cache, int seq
  *   p      : host [Hs][nk]
  * Does not synchronise; lengths live on the device, so steps can be queued back to back.
  * The call only launches kernels on `stream` (no memset, no allocation, no read-back), so a
- * step may be captured into a HIP graph and replayed. */
+ * step may be captured into a HIP graph and replayed.
+ * TCA_KV_FP8: the new rows are stored as codes and scales first; attention and the scoring of
+ * a completed block read the rows back as code * scale; rows kept from a completed block are
+ * copied as stored. */
 int tca_decode(const tca_params* prm, const tca_cache* cache, const int64_t* offs,
                const void* q, const void* k_new, const void* v_new, const double* p,
                void* O, void* ws, size_t ws_bytes, void* stream);

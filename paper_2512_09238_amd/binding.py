@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libtca.so")
 TCA_BF16, TCA_F32 = 0, 1
 TCA_METRIC_HHI, TCA_METRIC_ENTROPY = 0, 1
 TCA_SHARE_HEAD, TCA_SHARE_GROUP = 0, 1
+TCA_KV_NATIVE, TCA_KV_FP8 = 0, 1
 TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
 
 if not os.path.exists(LIB_PATH):
@@ -48,6 +49,8 @@ class tca_cache(C.Structure):
         ("batch", C.c_int32), ("cap_rows", C.c_int64),
         ("idx", C.c_void_p), ("Kg", C.c_void_p), ("Vg", C.c_void_p), ("n_rows", C.c_void_p),
         ("ringK", C.c_void_p), ("ringV", C.c_void_p), ("length", C.c_void_p),
+        ("kv_format", C.c_int32), ("Kg_scale", C.c_void_p), ("Vg_scale", C.c_void_p),
+        ("ringK_scale", C.c_void_p), ("ringV_scale", C.c_void_p),
     ]
 
 
@@ -76,6 +79,8 @@ EXPORTS = {
                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_cache_load_window": (C.c_int, [_P(tca_params), _P(tca_cache), C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_int64, C.c_void_p]),
+    "tca_cache_load_global": (C.c_int, [_P(tca_params), _P(tca_cache), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        _i64_p, C.c_void_p, C.c_void_p]),
     "tca_decode": (C.c_int, [_P(tca_params), _P(tca_cache), _i64_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              _dbl_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_decode_static": (C.c_int, [_P(tca_params), _P(tca_cache), _i64_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -209,14 +214,23 @@ def tca_prefill(prm, Q, q_pos0, n_queries, K, V, kv_stride, idx, Kg, Vg, offs, n
                            wsp, wsb, _stream(stream)))
 
 
-def make_cache(batch, cap_rows, idx, Kg, Vg, n_rows, ringK, ringV, length) -> tca_cache:
+def make_cache(batch, cap_rows, idx, Kg, Vg, n_rows, ringK, ringV, length, kv_format=TCA_KV_NATIVE,
+               Kg_scale=None, Vg_scale=None, ringK_scale=None, ringV_scale=None) -> tca_cache:
+    ptr = lambda t: None if t is None else t.data_ptr()
     return tca_cache(batch, cap_rows, idx.data_ptr(), Kg.data_ptr(), Vg.data_ptr(), n_rows.data_ptr(),
-                     ringK.data_ptr(), ringV.data_ptr(), length.data_ptr())
+                     ringK.data_ptr(), ringV.data_ptr(), length.data_ptr(), kv_format,
+                     ptr(Kg_scale), ptr(Vg_scale), ptr(ringK_scale), ptr(ringV_scale))
 
 
 def tca_cache_load_window(prm, cache, seq, K, V, kv_stride, L, stream=None):
     _check(lib.tca_cache_load_window(C.byref(prm), C.byref(cache), seq, _dp(K), _dp(V), kv_stride, L,
                                      _stream(stream)))
+
+
+def tca_cache_load_global(prm, cache, seq, idx, Kg, Vg, offs, n_rows, stream=None):
+    offs = _host(offs, np.int64)
+    _check(lib.tca_cache_load_global(C.byref(prm), C.byref(cache), seq, _dp(idx), _dp(Kg), _dp(Vg),
+                                     offs.ctypes.data_as(_i64_p), _dp(n_rows), _stream(stream)))
 
 
 def tca_decode(prm, cache, offs, q, k_new, v_new, p, O, ws, stream=None):

@@ -44,14 +44,16 @@ class GlobalBuffers:
 class DecodeCache:
     """Batch of per-sequence caches sharing one capacity layout."""
 
-    def __init__(self, prm, batch, cap, device="cuda:0"):
+    def __init__(self, prm, batch, cap, device="cuda:0", kv_format=tb.TCA_KV_NATIVE):
         cap = np.asarray(cap, np.int64)
         self.offs = np.concatenate([[0], np.cumsum(cap)]).astype(np.int64)
         self.cap_rows = int(self.offs[-1])
         self.max_head_rows = int(cap.max()) if len(cap) else 0
         rows = max(self.cap_rows, 1)
         d, w, Hkv, Hq = prm.head_dim, prm.window, prm.n_kv_heads, tb.tca_selection_heads(prm)
-        dt = torch_dtype(prm)
+        fp8 = kv_format == tb.TCA_KV_FP8
+        dt = torch.uint8 if fp8 else torch_dtype(prm)       # FP8 rows: one code byte per element, scales beside them
+        self.kv_format = kv_format
         self.idx = torch.zeros(batch, rows, dtype=torch.int32, device=device)
         self.Kg = torch.zeros(batch, rows, d, dtype=dt, device=device)
         self.Vg = torch.zeros(batch, rows, d, dtype=dt, device=device)
@@ -60,5 +62,12 @@ class DecodeCache:
         self.ringV = torch.zeros(batch, Hkv, w, d, dtype=dt, device=device)
         self.length = torch.zeros(batch, dtype=torch.int64, device=device)
         self.batch = batch
+        self.Kg_scale = self.Vg_scale = self.ringK_scale = self.ringV_scale = None
+        if fp8:
+            self.Kg_scale = torch.zeros(batch, rows, dtype=torch.float32, device=device)
+            self.Vg_scale = torch.zeros(batch, rows, dtype=torch.float32, device=device)
+            self.ringK_scale = torch.zeros(batch, Hkv, w, dtype=torch.float32, device=device)
+            self.ringV_scale = torch.zeros(batch, Hkv, w, dtype=torch.float32, device=device)
         self.view = tb.make_cache(batch, self.cap_rows, self.idx, self.Kg, self.Vg, self.n_rows,
-                                  self.ringK, self.ringV, self.length)
+                                  self.ringK, self.ringV, self.length, kv_format, self.Kg_scale, self.Vg_scale,
+                                  self.ringK_scale, self.ringV_scale)

@@ -91,23 +91,66 @@ __device__ __forceinline__ int count_le_wave(const int32_t* __restrict__ idx, in
   return lo;
 }
 
+// max over the 16 lanes of a row, result in every lane
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f32<kDppXor1>(v));
+  v = fmaxf(v, dpp_f32<kDppXor2>(v));
+  v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppMirror>(v));
+  return v;
+}
+
+// Scale of an FP8 row from the largest magnitude of its elements, and its reciprocal use: the codes are
+// RNE_e4m3(x / scale) with both divisions in float32 (the rule stated with TCA_KV_FP8).
+__device__ __forceinline__ float fp8_row_scale(float amax) { return amax > 0.f ? amax / 448.f : 1.f; }
+
+// One 16-lane group stores one row of D elements (a lane's slice: D/16 consecutive elements, 4 or 8)
+// into a cache row of storage type KV: a plain conversion-free copy for the native types, codes and a
+// scale for FP8.  x: the lane's slice widened to float.  Called by all 16 lanes of the group.
+template <typename KV, int EL>
+__device__ __forceinline__ void store_cache_slice(const float (&x)[EL], KV* dst_row, float* scale_slot, int sub) {
+  static_assert(sizeof(KV) == 1, "native rows are copied as stored");
+  float amax = 0.f;
+#pragma unroll
+  for (int e = 0; e < EL; ++e) amax = fmaxf(amax, fabsf(x[e]));
+  amax = row16_max(amax);
+  const float scale = fp8_row_scale(amax);
+  uint32_t* out = reinterpret_cast<uint32_t*>(dst_row + sub * EL);
+#pragma unroll
+  for (int e = 0; e < EL; e += 4) out[e / 4] = f32x4_to_fp8(x[e] / scale, x[e + 1] / scale, x[e + 2] / scale, x[e + 3] / scale);
+  if (sub == 0) *scale_slot = scale;
+}
+
 // grid (B, ceil(Hs/4)); block 256: one wave per selection head; the workgroups with blockIdx.y = 0
-// also write the new row into the ring
-template <typename T>
-__global__ __launch_bounds__(256) void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv, int D, int w,
+// also write the new row into the ring (KV = T: as it is; KV = fp8_t: as codes and a scale)
+template <typename T, typename KV, int D>
+__global__ __launch_bounds__(256) void decode_prep_kernel(tca_cache c, DecodeHeads dh, int Hs, int Hkv, int w,
                                                           const T* __restrict__ k_new, const T* __restrict__ v_new,
                                                           int32_t* __restrict__ n_vis) {
   const int s = blockIdx.x;
   const int64_t Tpos = c.length[s];
   if (blockIdx.y == 0) {
     const int slot = (int)(Tpos % w);
-    T* rk = (T*)c.ringK;
-    T* rv = (T*)c.ringV;
-    for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
-      const int kvh = e / D, dd = e - kvh * D;
-      const size_t dst = (((size_t)s * Hkv + kvh) * w + slot) * D + dd;
-      rk[dst] = k_new[(size_t)s * Hkv * D + e];
-      rv[dst] = v_new[(size_t)s * Hkv * D + e];
+    KV* rk = (KV*)c.ringK;
+    KV* rv = (KV*)c.ringV;
+    if constexpr (std::is_same<T, KV>::value) {
+      for (int e = threadIdx.x; e < Hkv * D; e += blockDim.x) {
+        const int kvh = e / D, dd = e - kvh * D;
+        const size_t dst = (((size_t)s * Hkv + kvh) * w + slot) * D + dd;
+        rk[dst] = k_new[(size_t)s * Hkv * D + e];
+        rv[dst] = v_new[(size_t)s * Hkv * D + e];
+      }
+    } else {
+      constexpr int EL = D / 16;
+      const int grp = threadIdx.x >> 4, sub = threadIdx.x & 15;       // one 16-lane group per (KV head, K or V)
+      for (int job = grp; job < 2 * Hkv; job += 16) {
+        const int kvh = job >> 1;
+        const T* src = ((job & 1) ? v_new : k_new) + ((size_t)s * Hkv + kvh) * D + sub * EL;
+        float x[EL];
+        load_slice<T, EL>(src, x);
+        const size_t row = ((size_t)s * Hkv + kvh) * w + slot;
+        store_cache_slice<KV, EL>(x, ((job & 1) ? rv : rk) + row * D, ((job & 1) ? c.ringV_scale : c.ringK_scale) + row, sub);
+      }
     }
   }
   const int h = blockIdx.y * 4 + (threadIdx.x >> 6);
@@ -173,9 +216,12 @@ __device__ __forceinline__ void merge_partials(float (&m)[NQ], float (&l)[NQ], f
 // [r_begin, r_end) of one K/V buffer: every row is read once and scored against all NQ queries.
 // Writes one (max, sum, acc[D]) partial per query at out + g * out_head.  red: LDS scratch of
 // kPartWaves * 16 * NQ * (D/16 + 2) floats.  Called by a whole workgroup.
-template <typename T, int D, int NQ>
-__device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const T* __restrict__ vbase, int r_begin,
-                                             int r_end, const T* __restrict__ q0, double scale,
+// T: type of the queries; KV: storage type of the rows (T itself, or fp8_t with one float scale per
+// row in kscale / vscale, indexed like the rows).
+template <typename T, typename KV, int D, int NQ>
+__device__ __forceinline__ void partial_rows(const KV* __restrict__ kbase, const KV* __restrict__ vbase,
+                                             const float* __restrict__ kscale, const float* __restrict__ vscale,
+                                             int r_begin, int r_end, const T* __restrict__ q0, double scale,
                                              float* __restrict__ out, size_t out_head, float* red) {
   constexpr int EL = D / 16;
   const int tid = threadIdx.x;
@@ -191,10 +237,13 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
   // fp32 storage: q.k is accumulated in fp64 and the reference of the exponentials is kept at an
   // integer (exact in fp32, and exact through every later merge), so that x - reference is formed
   // without cancellation error even for logits in the hundreds.
+  // FP8 storage: the codes are widened to float, q.k is the fp32 dot product with the codes times the
+  // row's scale, and p.v takes the V row's scale into the weight.
   constexpr double kLog2e = 1.4426950408889634;
-  constexpr bool kDot2 = sizeof(T) == 2;
+  constexpr bool kDot2 = sizeof(KV) == 2;
+  constexpr bool kFp8 = sizeof(KV) == 1;
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-  using logit_t = typename std::conditional<kDot2, float, double>::type;
+  using logit_t = typename std::conditional<sizeof(KV) == 4, double, float>::type;
   const logit_t qk_factor = (logit_t)(scale * kLog2e);
   float qv[kDot2 ? 1 : NQ][EL];
   RawSlice<T, EL> qraw[kDot2 ? NQ : 1];
@@ -221,25 +270,29 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
   // Rows are fetched one iteration ahead of their use (kUnr rows of K and of V per group,
   // kept as loaded until then), so that a lane has 2*kUnr loads in flight while it computes.
   constexpr int kUnr = 2;
-  using Raw = RawSlice<T, EL>;
+  using Raw = RawSlice<KV, EL>;
   Raw kr[kUnr], vr[kUnr];
+  float ksc[kUnr], vsc[kUnr];                          // row scales (FP8 rows only)
   bool ok[kUnr];
-  auto fetch = [&](int r0, Raw (&kk)[kUnr], Raw (&vq)[kUnr], bool (&okk)[kUnr]) {
+  auto fetch = [&](int r0, Raw (&kk)[kUnr], Raw (&vq)[kUnr], float (&ks)[kUnr], float (&vs)[kUnr], bool (&okk)[kUnr]) {
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
       const int r = r0 + u * (kPartThreads / 16) + grp;
       okk[u] = r < r_end;
+      ks[u] = vs[u] = 1.f;
       if (okk[u]) {
         kk[u].load(kbase + (size_t)r * D + sub * EL);
         vq[u].load(vbase + (size_t)r * D + sub * EL);
+        if constexpr (kFp8) { ks[u] = kscale[r]; vs[u] = vscale[r]; }
       }
     }
   };
-  fetch(r_begin, kr, vr, ok);
+  fetch(r_begin, kr, vr, ksc, vsc, ok);
   for (int r0 = r_begin; r0 < r_end; r0 += (kPartThreads / 16) * kUnr) {
     Raw kn[kUnr], vn[kUnr];
+    float ksn[kUnr], vsn[kUnr];
     bool okn[kUnr];
-    fetch(r0 + (kPartThreads / 16) * kUnr, kn, vn, okn);                    // nothing is loaded past r_end
+    fetch(r0 + (kPartThreads / 16) * kUnr, kn, vn, ksn, vsn, okn);          // nothing is loaded past r_end
 #pragma unroll
     for (int u = 0; u < kUnr; ++u) {
       float kv[EL], vv[EL];
@@ -258,13 +311,17 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
                                                    __builtin_bit_cast(bf16x2_t, qraw[g].w[i]), sc, false);
           } else {
 #pragma unroll
-            for (int e = 0; e < EL; ++e) sc = fma((double)qv[g][e], (double)kv[e], sc);
+            for (int e = 0; e < EL; ++e) {
+              if constexpr (sizeof(logit_t) == 4) sc = fmaf(qv[g][e], kv[e], sc);
+              else sc = fma((double)qv[g][e], (double)kv[e], sc);
+            }
           }
         }
         sc = row16_sum(sc) * qk_factor;
+        if constexpr (kFp8) sc *= ksc[u];
         if (ok[u]) {
           if (sc > (logit_t)m[g] + (logit_t)kSlack) {
-            const float m_new = kDot2 ? (float)sc : ceilf((float)sc);
+            const float m_new = sizeof(KV) == 4 ? ceilf((float)sc) : (float)sc;
             const float corr = __builtin_amdgcn_exp2f(m[g] - m_new);    // 0 on the first row (m = -inf)
             l[g] *= corr;
 #pragma unroll
@@ -273,13 +330,14 @@ __device__ __forceinline__ void partial_rows(const T* __restrict__ kbase, const 
           }
           const float pr = __builtin_amdgcn_exp2f((float)(sc - (logit_t)m[g]));
           l[g] += pr;
+          const float pw = kFp8 ? pr * vsc[u] : pr;                   // the V row's scale rides on the weight
 #pragma unroll
-          for (int e = 0; e < EL; ++e) acc[g][e] = fmaf(pr, vv[e], acc[g][e]);
+          for (int e = 0; e < EL; ++e) acc[g][e] = fmaf(pw, vv[e], acc[g][e]);
         }
       }
     }
 #pragma unroll
-    for (int u = 0; u < kUnr; ++u) { kr[u] = kn[u]; vr[u] = vn[u]; ok[u] = okn[u]; }
+    for (int u = 0; u < kUnr; ++u) { kr[u] = kn[u]; vr[u] = vn[u]; ksc[u] = ksn[u]; vsc[u] = vsn[u]; ok[u] = okn[u]; }
   }
   merge_partials<D, NQ>(m, l, acc, out, out_head, red);
 }
@@ -460,7 +518,7 @@ __device__ __forceinline__ void partial_rows_mfma(const bf16_t* __restrict__ kba
 // chunks of the head's global region, the others chunks of the ring.  The ring belongs to the KV
 // head, so with GW > GQ (one selection per query head, GW = G heads per KV head) the workgroup
 // of the group's first head scores each ring row against all GW queries and the others skip it.
-template <typename T, int D, int GQ, int GW>
+template <typename T, typename KV, int D, int GQ, int GW>
 __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int w, int g_slots, int n_slots, double scale,
     const T* __restrict__ q, const int32_t* __restrict__ n_vis, float* __restrict__ part) {
@@ -468,7 +526,7 @@ __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
   constexpr int CH = GQ > 1 ? kChunkShared : kChunk;  // rows per slot
   constexpr int NMAX = GQ > GW ? GQ : GW;
   __shared__ float red[kPartWaves * 16 * NMAX * (EL + 2)];
-  constexpr bool kMfma = sizeof(T) == 2 && D == 128;   // rows that partial_rows_mfma takes
+  constexpr bool kMfma = sizeof(KV) == 2 && D == 128;  // rows that partial_rows_mfma takes
   __shared__ __attribute__((aligned(16))) unsigned char tiles[kMfma && NMAX > 1 ? kPartWaves * kMfmaTileBytes + NMAX * 256 : 16];
   const int slot = blockIdx.x, hs = blockIdx.y, s = blockIdx.z;
   const int Hs = Hq / GQ, h0 = hs * GQ, kvh = h0 / (Hq / Hkv);
@@ -486,8 +544,8 @@ __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
       partial_rows_mfma<GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
                             out_head, red, tiles);
     else
-      partial_rows<T, D, GQ>((const T*)c.Kg + base * D, (const T*)c.Vg + base * D, r_begin, r_end, q0, scale, out,
-                             out_head, red);
+      partial_rows<T, KV, D, GQ>((const KV*)c.Kg + base * D, (const KV*)c.Vg + base * D, c.Kg_scale + base,
+                                 c.Vg_scale + base, r_begin, r_end, q0, scale, out, out_head, red);
   } else {
     if (GW != GQ && h0 % GW != 0) return;              // this head's ring partial is written by the group's first head
     // Slot r of the ring holds the latest position congruent to r mod w that is <= Tpos.  Once
@@ -500,13 +558,13 @@ __global__ __launch_bounds__(kPartThreads) void decode_partial_kernel(
       partial_rows_mfma<GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale,
                             out, out_head, red, tiles);
     else
-      partial_rows<T, D, GW>((const T*)c.ringK + base * D, (const T*)c.ringV + base * D, r_begin, r_end, q0, scale,
-                             out, out_head, red);
+      partial_rows<T, KV, D, GW>((const KV*)c.ringK + base * D, (const KV*)c.ringV + base * D, c.ringK_scale + base,
+                                 c.ringV_scale + base, r_begin, r_end, q0, scale, out, out_head, red);
   }
 }
 
 // grid (Hq, B); block 256
-template <typename T, int D>
+template <typename T, typename KV, int D>
 __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
     tca_cache c, DecodeHeads dh, int Hq, int Hkv, int GS, int w, int b, int n_slots, double scale,
     const T* __restrict__ q, const float* __restrict__ part, T* __restrict__ O) {
@@ -576,8 +634,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   const int hs = h / GS, Hs = Hq / GS;
   const int64_t p0 = Tpos + 1 - b;                     // first position of the block
   const int slot0 = (int)(p0 % w);                     // contiguous in the ring: w is a multiple of b
-  const T* kb = (const T*)c.ringK + (((size_t)s * Hkv + kvh) * w + slot0) * D;
-  const T* vb = (const T*)c.ringV + (((size_t)s * Hkv + kvh) * w + slot0) * D;
+  const size_t ring_row0 = ((size_t)s * Hkv + kvh) * w + slot0;
+  const KV* kb = (const KV*)c.ringK + ring_row0 * D;
+  const KV* vb = (const KV*)c.ringV + ring_row0 * D;
   const int grp = tid >> 4, sub = tid & 15;
   // score of row i: the logit of the head's query, or, for a shared selection, the sum over the
   // group's heads of exp(logit - log-sum-exp over the block) (G times the mean score)
@@ -591,9 +650,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
       double a = 0.0;
       if (r < b) {
         float kf[EL];
-        load_slice<T, EL>(kb + (size_t)r * D + sub * EL, kf);
+        RawSlice<KV, EL> raw;
+        raw.load(kb + (size_t)r * D + sub * EL);
+        raw.widen(kf);
 #pragma unroll
         for (int e = 0; e < EL; ++e) a = fma((double)kf[e], (double)qf[e], a);
+        if constexpr (sizeof(KV) == 1) a *= (double)c.ringK_scale[ring_row0 + r];   // the row read back: code * scale
       }
       a = group_sum(a, 16);
       if (r < b && sub == 0) xs[r] = a * scale;
@@ -639,17 +701,23 @@ __global__ __launch_bounds__(kDecThreads) void decode_merge_kernel(
   const int64_t cap = dh.offs[hs + 1] - dh.offs[hs];
   const int32_t fill = c.n_rows[s * Hs + hs];
   const size_t base = (size_t)s * c.cap_rows + dh.offs[hs];
-  T* Kg = (T*)c.Kg;
-  T* Vg = (T*)c.Vg;
+  KV* Kg = (KV*)c.Kg;
+  KV* Vg = (KV*)c.Vg;
   for (int k = grp; k < t; k += 16) {
     const int64_t row = (int64_t)fill + k;
     if (row >= cap) break;
     const int src = sel[k];
-    for (int e = 0; e < EL; ++e) {
+    for (int e = 0; e < EL; ++e) {                     // rows are copied as stored
       Kg[(base + row) * D + sub * EL + e] = kb[(size_t)src * D + sub * EL + e];
       Vg[(base + row) * D + sub * EL + e] = vb[(size_t)src * D + sub * EL + e];
     }
-    if (sub == 0) c.idx[base + row] = (int32_t)(p0 + src);
+    if (sub == 0) {
+      c.idx[base + row] = (int32_t)(p0 + src);
+      if constexpr (sizeof(KV) == 1) {
+        c.Kg_scale[base + row] = c.ringK_scale[ring_row0 + src];
+        c.Vg_scale[base + row] = c.ringV_scale[ring_row0 + src];
+      }
+    }
   }
   __syncthreads();
   if (tid == 0) {
@@ -663,11 +731,12 @@ __global__ void decode_advance_kernel(int64_t* length, int B) {
   if (s < B) length[s] += 1;
 }
 
-// grid (ceil(rows/16), Hkv); block 256: 16 rows per iteration
-template <typename T>
-__global__ void load_window_kernel(tca_cache c, int seq, int Hkv, int D, int w, const T* __restrict__ K,
-                                   const T* __restrict__ V, int64_t kv_stride, int64_t L) {
-  const int kvh = blockIdx.y;
+// grid (ceil(rows/16), Hkv); block 256: one 16-lane group per row
+template <typename T, typename KV, int D>
+__global__ __launch_bounds__(256) void load_window_kernel(tca_cache c, int seq, int Hkv, int w, const T* __restrict__ K,
+                                                          const T* __restrict__ V, int64_t kv_stride, int64_t L) {
+  constexpr int EL = D / 16;
+  const int kvh = blockIdx.y, sub = threadIdx.x & 15;
   const int64_t first = L - w > 0 ? L - w : 0;
   const int64_t pos = first + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) c.length[seq] = L;
@@ -675,9 +744,46 @@ __global__ void load_window_kernel(tca_cache c, int seq, int Hkv, int D, int w, 
   const int slot = (int)(pos % w);
   const T* ks = K + ((size_t)kvh * kv_stride + pos) * D;
   const T* vs = V + ((size_t)kvh * kv_stride + pos) * D;
-  T* kd = (T*)c.ringK + (((size_t)seq * Hkv + kvh) * w + slot) * D;
-  T* vd = (T*)c.ringV + (((size_t)seq * Hkv + kvh) * w + slot) * D;
-  for (int e = threadIdx.x & 15; e < D; e += 16) { kd[e] = ks[e]; vd[e] = vs[e]; }
+  const size_t row = ((size_t)seq * Hkv + kvh) * w + slot;
+  KV* kd = (KV*)c.ringK + row * D;
+  KV* vd = (KV*)c.ringV + row * D;
+  if constexpr (std::is_same<T, KV>::value) {
+    for (int e = sub; e < D; e += 16) { kd[e] = ks[e]; vd[e] = vs[e]; }
+  } else {
+    float x[EL];
+    load_slice<T, EL>(ks + sub * EL, x);
+    store_cache_slice<KV, EL>(x, kd, c.ringK_scale + row, sub);
+    load_slice<T, EL>(vs + sub * EL, x);
+    store_cache_slice<KV, EL>(x, vd, c.ringV_scale + row, sub);
+  }
+}
+
+// grid (ceil(cap_rows/16)); block 256: one 16-lane group per row of the flat global buffer
+template <typename T, typename KV, int D>
+__global__ __launch_bounds__(256) void load_global_kernel(tca_cache c, int seq, DecodeHeads dh, int Hs,
+                                                          const int32_t* __restrict__ idx, const T* __restrict__ Kg,
+                                                          const T* __restrict__ Vg, const int32_t* __restrict__ n_rows) {
+  constexpr int EL = D / 16;
+  const int sub = threadIdx.x & 15;
+  const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (blockIdx.x == 0 && threadIdx.x < Hs) c.n_rows[(size_t)seq * Hs + threadIdx.x] = n_rows[threadIdx.x];
+  if (r >= c.cap_rows) return;
+  int h = 0;
+  while (h + 1 < Hs && dh.offs[h + 1] <= r) ++h;                 // the head whose region holds row r
+  if (r - dh.offs[h] >= n_rows[h]) return;                      // capacity beyond the filled rows
+  const size_t dst = (size_t)seq * c.cap_rows + r;
+  if (sub == 0) c.idx[dst] = idx[r];
+  KV* kd = (KV*)c.Kg + dst * D;
+  KV* vd = (KV*)c.Vg + dst * D;
+  if constexpr (std::is_same<T, KV>::value) {
+    for (int e = sub; e < D; e += 16) { kd[e] = Kg[(size_t)r * D + e]; vd[e] = Vg[(size_t)r * D + e]; }
+  } else {
+    float x[EL];
+    load_slice<T, EL>(Kg + (size_t)r * D + sub * EL, x);
+    store_cache_slice<KV, EL>(x, kd, c.Kg_scale + dst, sub);
+    load_slice<T, EL>(Vg + (size_t)r * D + sub * EL, x);
+    store_cache_slice<KV, EL>(x, vd, c.Vg_scale + dst, sub);
+  }
 }
 
 static int check_cache(const tca_params* prm, const tca_cache* c) {
@@ -686,18 +792,24 @@ static int check_cache(const tca_params* prm, const tca_cache* c) {
                                                    (long long)c->cap_rows);
   if (!c->idx || !c->Kg || !c->Vg || !c->n_rows || !c->ringK || !c->ringV || !c->length)
     return fail(TCA_ERR_INVALID, "cache: NULL pointer member");
-  (void)prm;
+  if (c->kv_format != TCA_KV_NATIVE && c->kv_format != TCA_KV_FP8)
+    return fail(TCA_ERR_UNSUPPORTED, "cache: kv_format=%d", c->kv_format);
+  if (c->kv_format == TCA_KV_FP8) {
+    if (prm->dtype != TCA_BF16) return fail(TCA_ERR_UNSUPPORTED, "cache: TCA_KV_FP8 requires dtype TCA_BF16");
+    if (!c->Kg_scale || !c->Vg_scale || !c->ringK_scale || !c->ringV_scale)
+      return fail(TCA_ERR_INVALID, "cache: NULL scale pointer with TCA_KV_FP8");
+  }
   return TCA_OK;
 }
 
-template <typename T, int D>
+template <typename T, typename KV, int D>
 static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHeads& dh, int64_t max_rows,
                       const T* q, const T* k_new, const T* v_new, T* O, void* ws, hipStream_t st) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, B = c->batch, w = prm->window;
   const int Hs = sel_heads(prm), GS = sel_group(prm);
   const int g_slots = global_slots(prm, max_rows), n_slots = g_slots + window_slots(prm);
   DecodeWs dw = carve_decode_ws(ws, B, Hq, D, n_slots);
-  hipLaunchKernelGGL((decode_prep_kernel<T>), dim3(B, (Hs + 3) / 4), dim3(256), 0, st, *c, dh, Hs, Hkv, D, w, k_new,
+  hipLaunchKernelGGL((decode_prep_kernel<T, KV, D>), dim3(B, (Hs + 3) / 4), dim3(256), 0, st, *c, dh, Hs, Hkv, w, k_new,
                      v_new, dw.n_vis);
   const double sc = logit_scale(prm);
   // (queries per region row, queries per ring row): (G, G) for a shared selection, else (1, G)
@@ -705,10 +817,10 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
 #define TCA_PARTIAL_CASE(GG)                                                                                    \
   case GG:                                                                                                      \
     if (GS > 1)                                                                                                 \
-      hipLaunchKernelGGL((decode_partial_kernel<T, D, GG, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
+      hipLaunchKernelGGL((decode_partial_kernel<T, KV, D, GG, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
                          *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
     else                                                                                                        \
-      hipLaunchKernelGGL((decode_partial_kernel<T, D, 1, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
+      hipLaunchKernelGGL((decode_partial_kernel<T, KV, D, 1, GG>), dim3(n_slots, Hs, B), dim3(kPartThreads), 0, st, \
                          *c, dh, Hq, Hkv, w, g_slots, n_slots, sc, q, dw.n_vis, dw.part);                       \
     break;
   switch (G) {
@@ -716,7 +828,7 @@ static int run_decode(const tca_params* prm, const tca_cache* c, const DecodeHea
     TCA_PARTIAL_CASE(5) TCA_PARTIAL_CASE(6) TCA_PARTIAL_CASE(7) TCA_PARTIAL_CASE(8)
   }
 #undef TCA_PARTIAL_CASE
-  hipLaunchKernelGGL((decode_merge_kernel<T, D>), dim3(Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq, Hkv, GS, w,
+  hipLaunchKernelGGL((decode_merge_kernel<T, KV, D>), dim3(Hq, B), dim3(kDecThreads), 0, st, *c, dh, Hq, Hkv, GS, w,
                      prm->block, n_slots, logit_scale(prm), q, dw.part, O);
   hipLaunchKernelGGL(decode_advance_kernel, dim3((B + 63) / 64), dim3(64), 0, st, c->length, B);
   return TCA_OK;
@@ -745,12 +857,48 @@ extern "C" int tca_cache_load_window(const tca_params* prm, const tca_cache* cac
   const int64_t rows = L < w ? L : w;
   dim3 grid((unsigned)((rows + 15) / 16 > 0 ? (rows + 15) / 16 : 1), prm->n_kv_heads);
   hipStream_t st = (hipStream_t)stream;
-  if (prm->dtype == TCA_BF16)
-    hipLaunchKernelGGL((load_window_kernel<bf16_t>), grid, dim3(256), 0, st, *cache, seq, prm->n_kv_heads,
-                       prm->head_dim, w, (const bf16_t*)K, (const bf16_t*)V, kv_stride, L);
-  else
-    hipLaunchKernelGGL((load_window_kernel<float>), grid, dim3(256), 0, st, *cache, seq, prm->n_kv_heads,
-                       prm->head_dim, w, (const float*)K, (const float*)V, kv_stride, L);
+  const bool d128 = prm->head_dim == 128;
+#define TCA_LOAD_WINDOW(TT, KK, DD)                                                                            \
+  hipLaunchKernelGGL((load_window_kernel<TT, KK, DD>), grid, dim3(256), 0, st, *cache, seq, prm->n_kv_heads, w, \
+                     (const TT*)K, (const TT*)V, kv_stride, L)
+  if (cache->kv_format == TCA_KV_FP8) { if (d128) TCA_LOAD_WINDOW(bf16_t, fp8_t, 128); else TCA_LOAD_WINDOW(bf16_t, fp8_t, 64); }
+  else if (prm->dtype == TCA_BF16) { if (d128) TCA_LOAD_WINDOW(bf16_t, bf16_t, 128); else TCA_LOAD_WINDOW(bf16_t, bf16_t, 64); }
+  else { if (d128) TCA_LOAD_WINDOW(float, float, 128); else TCA_LOAD_WINDOW(float, float, 64); }
+#undef TCA_LOAD_WINDOW
+  TCA_HIP_CHECK(hipGetLastError());
+  return TCA_OK;
+}
+
+extern "C" int tca_cache_load_global(const tca_params* prm, const tca_cache* cache, int seq, const int32_t* idx,
+                                     const void* Kg, const void* Vg, const int64_t* offs, const int32_t* n_rows,
+                                     void* stream) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  rc = check_cache(prm, cache);
+  if (rc) return rc;
+  const int Hs = sel_heads(prm);
+  if (!idx || !Kg || !Vg || !offs || !n_rows || seq < 0 || seq >= cache->batch)
+    return fail(TCA_ERR_INVALID, "tca_cache_load_global: NULL pointer argument or seq=%d outside the batch", seq);
+  if (offs[0] != 0 || offs[Hs] != cache->cap_rows)
+    return fail(TCA_ERR_INVALID, "tca_cache_load_global: offs[0] must be 0 and offs[Hs] must equal cap_rows");
+  DecodeHeads dh;
+  for (int h = 0; h < Hs; ++h) {
+    if (offs[h + 1] < offs[h]) return fail(TCA_ERR_INVALID, "tca_cache_load_global: offs not ascending at %d", h);
+    dh.offs[h] = offs[h];
+    dh.t_dec[h] = 0;
+  }
+  dh.offs[Hs] = offs[Hs];
+  if (cache->cap_rows == 0) return TCA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  dim3 grid((unsigned)((cache->cap_rows + 15) / 16));
+  const bool d128 = prm->head_dim == 128;
+#define TCA_LOAD_GLOBAL(TT, KK, DD)                                                                      \
+  hipLaunchKernelGGL((load_global_kernel<TT, KK, DD>), grid, dim3(256), 0, st, *cache, seq, dh, Hs, idx, \
+                     (const TT*)Kg, (const TT*)Vg, n_rows)
+  if (cache->kv_format == TCA_KV_FP8) { if (d128) TCA_LOAD_GLOBAL(bf16_t, fp8_t, 128); else TCA_LOAD_GLOBAL(bf16_t, fp8_t, 64); }
+  else if (prm->dtype == TCA_BF16) { if (d128) TCA_LOAD_GLOBAL(bf16_t, bf16_t, 128); else TCA_LOAD_GLOBAL(bf16_t, bf16_t, 64); }
+  else { if (d128) TCA_LOAD_GLOBAL(float, float, 128); else TCA_LOAD_GLOBAL(float, float, 64); }
+#undef TCA_LOAD_GLOBAL
   TCA_HIP_CHECK(hipGetLastError());
   return TCA_OK;
 }
@@ -787,17 +935,14 @@ static int decode_step(const tca_params* prm, const tca_cache* cache, const int6
     return fail(TCA_ERR_WORKSPACE, "%s: scratch needs %zu bytes, 256-byte aligned; %zu available", who, need,
                 ws_bytes);
   hipStream_t st = (hipStream_t)stream;
-  if (prm->dtype == TCA_BF16) {
-    using T = bf16_t;
-    rc = prm->head_dim == 128
-             ? run_decode<T, 128>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st)
-             : run_decode<T, 64>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st);
-  } else {
-    using T = float;
-    rc = prm->head_dim == 128
-             ? run_decode<T, 128>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st)
-             : run_decode<T, 64>(prm, cache, dh, max_rows, (const T*)q, (const T*)k_new, (const T*)v_new, (T*)O, ws, st);
-  }
+#define TCA_RUN_DECODE(TT, KK)                                                                                         \
+  (prm->head_dim == 128                                                                                                \
+       ? run_decode<TT, KK, 128>(prm, cache, dh, max_rows, (const TT*)q, (const TT*)k_new, (const TT*)v_new, (TT*)O, ws, st) \
+       : run_decode<TT, KK, 64>(prm, cache, dh, max_rows, (const TT*)q, (const TT*)k_new, (const TT*)v_new, (TT*)O, ws, st))
+  if (cache->kv_format == TCA_KV_FP8) rc = TCA_RUN_DECODE(bf16_t, fp8_t);
+  else if (prm->dtype == TCA_BF16) rc = TCA_RUN_DECODE(bf16_t, bf16_t);
+  else rc = TCA_RUN_DECODE(float, float);
+#undef TCA_RUN_DECODE
   if (rc) return rc;
   TCA_HIP_CHECK(hipGetLastError());
   return TCA_OK;

@@ -11,6 +11,25 @@ constexpr int kWave = 64;
 
 struct bf16_t { uint16_t bits; };   // storage only; arithmetic is done after widening
 
+struct fp8_t { uint8_t bits; };     // OCP FP8 E4M3 code of the decode cache; read back as code * row scale
+
+// Four E4M3 codes of one dword widened to float (two at a time on the conversion unit).
+__device__ __forceinline__ void fp8x4_to_f32(uint32_t w, float& a, float& b, float& c, float& d) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  a = lo.x; b = lo.y; c = hi.x; d = hi.y;
+}
+// Four floats (already divided by the row scale, magnitude <= 448 up to rounding) to four codes,
+// round to nearest even; the clamp keeps a quotient that rounding pushed past 448 finite.
+__device__ __forceinline__ uint32_t f32x4_to_fp8(float a, float b, float c, float d) {
+  const float lim = 448.f;
+  a = fminf(fmaxf(a, -lim), lim); b = fminf(fmaxf(b, -lim), lim);
+  c = fminf(fmaxf(c, -lim), lim); d = fminf(fmaxf(d, -lim), lim);
+  int p = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  p = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, p, true);
+  return (uint32_t)p;
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // Round-to-nearest-even float -> bf16 bits (inputs are finite here; NaN stays NaN).
@@ -96,10 +115,12 @@ template <> __device__ __forceinline__ void load_slice<bf16_t, 4>(const bf16_t* 
 // loads issued ahead of their use cost few registers.
 template <typename T, int N>
 struct RawSlice {
-  static constexpr int W = N * (int)sizeof(T) / 4;       // dwords: 2, 4 or 8
+  static constexpr int W = N * (int)sizeof(T) / 4;       // dwords: 1, 2, 4 or 8
   uint32_t w[W];
   __device__ __forceinline__ void load(const T* p) {
-    if constexpr (W == 2) {
+    if constexpr (W == 1) {
+      w[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (W == 2) {
       const uint2 v = *reinterpret_cast<const uint2*>(p);
       w[0] = v.x; w[1] = v.y;
     } else {
@@ -114,6 +135,9 @@ struct RawSlice {
     if constexpr (sizeof(T) == 4) {
 #pragma unroll
       for (int i = 0; i < N; ++i) out[i] = __uint_as_float(w[i]);
+    } else if constexpr (sizeof(T) == 1) {
+#pragma unroll
+      for (int i = 0; i < W; ++i) fp8x4_to_f32(w[i], out[4 * i], out[4 * i + 1], out[4 * i + 2], out[4 * i + 3]);
     } else {
 #pragma unroll
       for (int i = 0; i < W; ++i) {

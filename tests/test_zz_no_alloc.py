@@ -80,7 +80,7 @@ def test_decode_static_matches_decode_twice_then_rejects_what_does_not_fit():
     assert tb.tca_decode_workspace_bytes(prm_big, 16, rows) > tb.TCA_DECODE_STATIC_BYTES
     offs = np.arange(129, dtype=np.int64) * rows
     dummy = torch.zeros(16, 128, d, dtype=torch.bfloat16, device="cuda")
-    cache = tb.tca_cache(16, int(offs[-1]), *([dummy.data_ptr()] * 7))
+    cache = tb.make_cache(16, int(offs[-1]), *([dummy] * 7))
     with pytest.raises(tb.TcaError) as e:
         tb.tca_decode_static(prm_big, cache, offs, dummy, dummy, dummy, Pb, dummy)
     assert e.value.code == tb.TCA_ERR_WORKSPACE
