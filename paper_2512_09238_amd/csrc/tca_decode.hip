@@ -269,7 +269,7 @@ __device__ __forceinline__ void partial_rows(const KV* __restrict__ kbase, const
   constexpr float kSlack = 8.f;
   // Rows are fetched one iteration ahead of their use (kUnr rows of K and of V per group,
   // kept as loaded until then), so that a lane has 2*kUnr loads in flight while it computes.
-  constexpr int kUnr = 2;
+  constexpr int kUnr = 2;                              // (4 for the FP8 rows, half the bytes each, measured no faster)
   using Raw = RawSlice<KV, EL>;
   Raw kr[kUnr], vr[kUnr];
   float ksc[kUnr], vsc[kUnr];                          // row scales (FP8 rows only)
