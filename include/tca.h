@@ -303,6 +303,31 @@ int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, const void* K
                           double* p_star, int32_t* cand_idx, double* a_out, int64_t* n_out,
                           int32_t* fallback, void* ws, size_t ws_bytes, void* stream);
 
+/* Alg. 1 for every layer of a model (the determination is made once per model and covers all
+ * heads of all layers, Sec. IV and IV-A): tca_calibrate_budgets once per layer, on that layer's
+ * sample, results layer-major.
+ *   Qcal, Kcal : host arrays of n_layers device pointers, [Hq, L_cal, d] and [Hkv, L_cal, d] each
+ *   p_star [n_layers][Hs][nk], cand_idx [n_layers][Hs], a_out [n_layers][Hs][M] or NULL,
+ *   n_out [n_layers][Hs][M] or NULL, fallback [n_layers][Hs] or NULL: host
+ *   ws : as for tca_calibrate_budgets (reused by every layer).
+ * Waits for `stream` before returning.  Stops at the first layer that fails. */
+int tca_calibrate_layers(const tca_params* prm, int n_layers, const void* const* Qcal,
+                         const void* const* Kcal, int64_t L_cal, int M, double sigma, double tau,
+                         double* p_star, int32_t* cand_idx, double* a_out, int64_t* n_out,
+                         int32_t* fallback, void* ws, size_t ws_bytes, void* stream);
+
+/* Rotary position embedding of Q or K rows in place, the step that precedes this path in a
+ * model layer (an extension: the paper takes Q and K as given, after position encoding).
+ * Row r of every head sits at position pos0 + r; its pair i, (x_i, x_{i+d/2}) with
+ * TCA_ROPE_HALF (the layout of Llama-family checkpoints) or (x_{2i}, x_{2i+1}) with
+ * TCA_ROPE_INTERLEAVED, is turned by the angle (pos0 + r) * base^(-2i/d) (the RoFormer rotation).
+ *   X : device [n_heads, n_rows, d] of tca_params.dtype (n_heads: Hq for Q, Hkv for K)
+ * Angles and products are fp64, rounded once to the storage type.  Does not synchronise. */
+#define TCA_ROPE_HALF        0
+#define TCA_ROPE_INTERLEAVED 1
+int tca_rope(const tca_params* prm, void* X, int n_heads, int64_t n_rows, int64_t pos0, double base,
+             int pairing, void* stream);
+
 const char* tca_strerror(int code);
 const char* tca_last_error(void);
 

@@ -12,6 +12,6 @@ def __getattr__(name):
     if name.startswith("__"):
         raise AttributeError(name)
     import importlib
-    if name in ("binding", "buffers", "schedule", "build"):
+    if name in ("binding", "buffers", "schedule", "build", "calibration"):
         return importlib.import_module("." + name, __name__)
     return getattr(importlib.import_module(".binding", __name__), name)

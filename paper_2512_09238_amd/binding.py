@@ -20,6 +20,7 @@ TCA_BF16, TCA_F32 = 0, 1
 TCA_METRIC_HHI, TCA_METRIC_ENTROPY = 0, 1
 TCA_SHARE_HEAD, TCA_SHARE_GROUP = 0, 1
 TCA_KV_NATIVE, TCA_KV_FP8 = 0, 1
+TCA_ROPE_HALF, TCA_ROPE_INTERLEAVED = 0, 1
 TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
 
 if not os.path.exists(LIB_PATH):
@@ -90,6 +91,10 @@ EXPORTS = {
                                         C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_diag_prefill_clocks": (None, [C.c_int]),
     "tca_diag_prefill_variant": (C.c_int, [C.c_int]),
+    "tca_calibrate_layers": (C.c_int, [_P(tca_params), C.c_int, _P(C.c_void_p), _P(C.c_void_p), C.c_int64, C.c_int,
+                                       C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_rope": (C.c_int, [_P(tca_params), C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_void_p]),
     "tca_strerror": (C.c_char_p, [C.c_int]),
     "tca_last_error": (C.c_char_p, []),
 }
@@ -265,6 +270,29 @@ def tca_calibrate_budgets(prm, Qcal, Kcal, L_cal, M, sigma, tau, ws, stream=None
                                      a.ctypes.data_as(_dbl_p), n.ctypes.data_as(_i64_p),
                                      fb.ctypes.data_as(_i32_p), wsp, wsb, _stream(stream)))
     return {"p_star": p_star, "cand_idx": cand, "a": a, "n": n, "fallback": fb}
+
+
+def tca_calibrate_layers(prm, Qcals, Kcals, L_cal, M, sigma, tau, ws, stream=None):
+    """Qcals, Kcals: one device tensor per layer.  Returns dict(p_star [layers,Hs,nk], cand_idx [layers,Hs],
+    a [layers,Hs,M], n [layers,Hs,M], fallback [layers,Hs])."""
+    nl, Hs, nk = len(Qcals), tca_selection_heads(prm), tca_num_counts(prm.block)
+    qp = (C.c_void_p * nl)(*[_dp(t) for t in Qcals])
+    kp = (C.c_void_p * nl)(*[_dp(t) for t in Kcals])
+    p_star = np.empty((nl, Hs, nk), np.float64)
+    cand = np.empty((nl, Hs), np.int32)
+    a = np.empty((nl, Hs, M), np.float64)
+    n = np.empty((nl, Hs, M), np.int64)
+    fb = np.empty((nl, Hs), np.int32)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_calibrate_layers(C.byref(prm), nl, qp, kp, L_cal, M, sigma, tau,
+                                    p_star.ctypes.data_as(_dbl_p), cand.ctypes.data_as(_i32_p),
+                                    a.ctypes.data_as(_dbl_p), n.ctypes.data_as(_i64_p), fb.ctypes.data_as(_i32_p),
+                                    wsp, wsb, _stream(stream)))
+    return {"p_star": p_star, "cand_idx": cand, "a": a, "n": n, "fallback": fb}
+
+
+def tca_rope(prm, X, n_heads, n_rows, pos0, base=10000.0, pairing=TCA_ROPE_HALF, stream=None):
+    _check(lib.tca_rope(C.byref(prm), _dp(X), n_heads, n_rows, pos0, base, pairing, _stream(stream)))
 
 
 # --------------------------------------------------------- diagnostics --

@@ -20,6 +20,7 @@ SOURCES = [
     "tca_prefill_mfma.hip",
     "tca_decode.hip",
     "tca_calibrate.hip",
+    "tca_rope.hip",
     "tca_diag.hip",
 ]
 

@@ -303,3 +303,26 @@ extern "C" int tca_calibrate_budgets(const tca_params* prm, const void* Qcal, co
   }
   return TCA_OK;
 }
+
+// Alg. 1 for every layer of a model (Sec. IV-A: the determination is made once per model and
+// covers all heads of all layers): one tca_calibrate_budgets pass per layer on that layer's
+// sample, on the same workspace, results laid out layer-major.
+extern "C" int tca_calibrate_layers(const tca_params* prm, int n_layers, const void* const* Qcal,
+                                    const void* const* Kcal, int64_t L_cal, int M, double sigma, double tau,
+                                    double* p_star, int32_t* cand_idx, double* a_out, int64_t* n_out,
+                                    int32_t* fallback, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(prm);
+  if (rc) return rc;
+  if (n_layers < 1 || !Qcal || !Kcal || !p_star || !cand_idx)
+    return fail(TCA_ERR_INVALID, "tca_calibrate_layers: n_layers=%d or NULL pointer argument", n_layers);
+  const int Hs = sel_heads(prm), nk = block_log2(prm->block) + 1;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!Qcal[l] || !Kcal[l]) return fail(TCA_ERR_INVALID, "tca_calibrate_layers: NULL sample of layer %d", l);
+    rc = tca_calibrate_budgets(prm, Qcal[l], Kcal[l], L_cal, M, sigma, tau, p_star + (size_t)l * Hs * nk,
+                               cand_idx + (size_t)l * Hs, a_out ? a_out + (size_t)l * Hs * M : nullptr,
+                               n_out ? n_out + (size_t)l * Hs * M : nullptr,
+                               fallback ? fallback + (size_t)l * Hs : nullptr, ws, ws_bytes, stream);
+    if (rc) return rc;
+  }
+  return TCA_OK;
+}

@@ -121,3 +121,29 @@ def test_binding_loads_torch_before_the_library():
             "assert 'torch' in sys.modules; print(tb.tca_num_counts(128))")
     r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and r.stdout.strip() == "8", r.stderr[-500:]
+
+
+def test_calibration_file_round_trip(tmp_path):
+    """The calibrated configurations as a file: doubles come back bit for bit, a file made for
+    another layer shape is refused."""
+    import paper_2512_09238_amd.binding as tb
+    import paper_2512_09238_amd.calibration as calib
+    prm = tb.make_params(4, 2, 128, 128, 4096, tb.TCA_BF16)
+    cands = tb.tca_make_candidates(128, 14, 1.0)
+    pick = np.array([[3, 7, 7, 13], [0, 5, 6, 8]])
+    cal = {"p_star": cands[pick], "cand_idx": pick.astype(np.int32), "fallback": np.array([[0, 0, 0, 1], [0, 0, 0, 0]], np.int32)}
+    path = os.path.join(tmp_path, "c.json")
+    calib.save_calibration(path, prm, cal, 14, 1.0, 0.9, 8192)
+    back = calib.load_calibration(path, prm)
+    assert np.array_equal(back["p_star"], cal["p_star"]) and back["p_star"].dtype == np.float64
+    assert np.array_equal(back["cand_idx"], cal["cand_idx"]) and np.array_equal(back["fallback"], cal["fallback"])
+    assert (back["n_layers"], back["n_selection_heads"], back["candidates"], back["calibration_tokens"]) == (2, 4, 14, 8192)
+    one = {"p_star": cands[pick[0]], "cand_idx": pick[0].astype(np.int32), "fallback": np.zeros(4, np.int32)}
+    calib.save_calibration(path, prm, one, 14, 1.0, 0.9, 8192)          # a single tca_calibrate_budgets result is one layer
+    assert calib.load_calibration(path)["p_star"].shape == (1, 4, 8)
+    with pytest.raises(ValueError):
+        calib.load_calibration(path, tb.make_params(8, 2, 128, 128, 4096, tb.TCA_BF16))
+    with open(path, "w") as f:
+        f.write('{"format": "something else"}')
+    with pytest.raises(ValueError):
+        calib.load_calibration(path)
