@@ -160,6 +160,8 @@ size_t tca_calibrate_workspace_bytes(const tca_params* prm, int64_t L_cal, int M
  *   offs   : host [Hs+1]
  *   n_rows : device int32 [Hs], in/out (zero it before the first call)
  *   idx    : device int32 [offs[Hs]]; Kg, Vg: device [offs[Hs], d]
+ * Kg and Vg may both be NULL: only the positions (idx) and n_rows are written, for a caller that
+ * keeps no compacted copy and calls tca_prefill the same way.
  * All scoring arithmetic is fp64.  Inside a block, tokens whose scores agree to within
  * 2^-44 relative are ordered by position, like exact ties (the ranking key drops the last
  * 8 mantissa bits), so the selected sets agree with an fp64 reference except at such
@@ -180,7 +182,10 @@ int tca_select(const tca_params* prm, const void* q_last, const void* K, const v
  *   K, V   : device [Hkv, kv_stride, d], dense rows; q_pos0 + n_queries <= kv_stride
  *   idx, Kg, Vg, offs, n_rows : as written by tca_select (n_rows: device int32 [Hs])
  *   lse    : device float [Hq, n_queries] or NULL: natural-log sum of exp of the scaled logits
- * TCA_BF16: bf16 MFMA products, fp32 softmax and accumulation.  TCA_F32: fp32 throughout.
+ * Kg and Vg may both be NULL (gather-free call): the global rows are read from K and V through
+ * idx, for a prefill whose kept rows are not needed afterwards as a compacted cache.
+ * TCA_BF16: bf16 MFMA products, fp32 softmax and accumulation.  TCA_F32: fp64 logits, fp32
+ * exponentials and accumulation.
  * TCA_BF16 limit: (q_pos0 + n_queries + w + 128) * d * 2 bytes and every head's region must stay
  * below 2 GiB (8M positions at d = 128); beyond that the call returns TCA_ERR_UNSUPPORTED.
  * Does not synchronise. */

@@ -19,8 +19,10 @@ extern "C" int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0,
                            void* O, float* lse, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(prm);
   if (rc) return rc;
-  if (!Q || !K || !V || !idx || !Kg || !Vg || !offs || !n_rows || !O)
+  if (!Q || !K || !V || !idx || !offs || !n_rows || !O)
     return fail(TCA_ERR_INVALID, "tca_prefill: NULL pointer argument");
+  if ((Kg == nullptr) != (Vg == nullptr))
+    return fail(TCA_ERR_INVALID, "tca_prefill: Kg and Vg must both be given, or both be NULL (gather-free call)");
   if (n_queries < 0 || q_pos0 < 0 || q_pos0 + n_queries > kv_stride)
     return fail(TCA_ERR_INVALID, "tca_prefill: q_pos0=%lld n_queries=%lld kv_stride=%lld",
                 (long long)q_pos0, (long long)n_queries, (long long)kv_stride);

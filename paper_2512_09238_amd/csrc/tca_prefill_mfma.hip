@@ -72,8 +72,10 @@ template <int D>
 __global__ __launch_bounds__(256) void transpose_tiles_kernel(
     const uint16_t* __restrict__ src, int64_t group_stride_rows, const int32_t* group_valid,
     int64_t valid_all, int64_t first_row, uint16_t* __restrict__ dst, int tiles_per_group,
-    PrefillHeads ph, int mode, unsigned long long* clk) {
-  // mode 0: global regions (group = selection head; rows from ph.offs, valid rows from group_valid)
+    PrefillHeads ph, int mode, unsigned long long* clk, const int32_t* __restrict__ gather_idx, int sel_per_kv) {
+  // mode 0: global regions (group = selection head; rows from ph.offs, valid rows from group_valid).
+  //         gather_idx != NULL: src is the dense [KV head][group_stride_rows][D] matrix and row r of the
+  //         region is its row gather_idx[ph.offs[g] + r] of KV head g / sel_per_kv (no compacted copy exists)
   // mode 1: dense K/V (group = KV head; absolute rows first_row + 64*tile, valid while < valid_all)
   __shared__ uint16_t tile[kBN][D + 8];
   const int g = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
@@ -97,7 +99,11 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(
   for (int c = tid; c < kBN * CPR; c += 256) {
     const int r = c / CPR, part = c - r * CPR;
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < n_valid) v = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + r) * D + part * 8);
+    if (r < n_valid) {
+      size_t row = (size_t)(row0 + r);
+      if (mode == 0 && gather_idx) row = (size_t)(g / sel_per_kv) * group_stride_rows + gather_idx[row0 + r];
+      v = *reinterpret_cast<const uint4*>(src + row * D + part * 8);
+    }
     *reinterpret_cast<uint4*>(&tile[r][part * 8]) = v;
   }
   __syncthreads();
@@ -248,7 +254,10 @@ __device__ __forceinline__ void copy16_to_lds(__amdgpu_buffer_rsrc_t rsrc, int l
 // K(t+RING) and V^T(t+RING-1) are copied global -> LDS during iteration t, into the places
 // of K(t) and V^T(t-1); the rings hold RING = 2 or 3 tiles each; one barrier per iteration.
 // Positions and byte offsets are 32-bit here: the host checks (q_pos0 + n_queries) * D * 2 < 2^31.
-template <int D, int NW, int QB>
+// GATHER: no compacted K exists; the K rows of a region tile are fetched from the dense K through
+// idx (the position of every row is read one iteration ahead and becomes the lane's offset of the
+// tile copy); the V^T tiles were built through idx by the pre-pass.
+template <int D, int NW, int QB, bool GATHER>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2 / QB, 2 / QB)))
 void prefill_mfma_kernel(
     const uint16_t* __restrict__ Q, int64_t q_pos0, int64_t n_queries, const uint16_t* __restrict__ K,
@@ -333,7 +342,7 @@ void prefill_mfma_kernel(
   using Copy = TileCopy<D, NW>;
   constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
   const __amdgpu_buffer_rsrc_t krs_g = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(Kg + (size_t)base * D), 0, nr * (D * 2), kRsrcFlags);
+      (void*)(GATHER ? K : Kg + (size_t)base * D), 0, GATHER ? 0 : nr * (D * 2), kRsrcFlags);   // GATHER: never read
   const __amdgpu_buffer_rsrc_t krs_d = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(K + (size_t)kvh * kv_stride * D), 0, (last_pos + 1) * (D * 2), kRsrcFlags);
   const __amdgpu_buffer_rsrc_t vrs_g = __builtin_amdgcn_make_buffer_rsrc(
@@ -342,8 +351,12 @@ void prefill_mfma_kernel(
       (void*)(Vt + (size_t)kvh * dense_tiles * (D * kBN)), 0, dense_tiles * VBYTES, kRsrcFlags);
   const int vdshift = dshift - (int)dense_tile0;   // tile t >= n_gt is tile t + vdshift of the dense V^T buffer
   int klo[Copy::NK], vlo[Copy::NV];                // this lane's byte offsets inside a tile, per wave-load
+  int krow[Copy::NK];                              // the tile row this lane copies a chunk of, per K wave-load
 #pragma unroll
-  for (int j = 0; j < Copy::NK; ++j) klo[j] = Copy::k_lane_offset(wv * Copy::NK + j, lane);
+  for (int j = 0; j < Copy::NK; ++j) {
+    klo[j] = Copy::k_lane_offset(wv * Copy::NK + j, lane);
+    krow[j] = ((wv * Copy::NK + j) * 64 + lane) / Copy::CPR;
+  }
 #pragma unroll
   for (int j = 0; j < Copy::NV; ++j) vlo[j] = Copy::v_lane_offset(wv * Copy::NV + j, lane);
   // One K tile and one V^T tile to copy: descriptors and scalar offsets chosen once, then
@@ -353,21 +366,45 @@ void prefill_mfma_kernel(
     int koff, voff;
     unsigned char* kdst;
     unsigned char* vdst;
+    bool k_through_idx;              // GATHER: a region tile, its rows fetched from the dense K
+    int kgo[Copy::NK];               // GATHER: this lane's byte offset into the dense K, per wave-load
   };
-  auto copy_job = [&](int tk, int tv, unsigned char* kstage, unsigned char* vstage) {
+  // GATHER: positions of the rows this lane copies from region tile t (rows past the region's end get
+  // an offset beyond the buffer, which the descriptor's range check turns into zeros)
+  struct TileRows { int pos[Copy::NK]; };
+  auto load_tile_rows = [&](int t) {
+    TileRows tr;
+#pragma unroll
+    for (int j = 0; j < Copy::NK; ++j) {
+      const int r = t * kBN + krow[j];
+      tr.pos[j] = (t < n_gt && r < nr) ? idx[base + r] : -1;
+    }
+    return tr;
+  };
+  auto copy_job = [&](int tk, int tv, unsigned char* kstage, unsigned char* vstage, const TileRows& rows_k) {
     CopyJob j;
     const bool kg = tk < n_gt, vg = tv < n_gt;
-    j.krs = kg ? krs_g : krs_d;
+    j.krs = (kg && !GATHER) ? krs_g : krs_d;
     j.vrs = vg ? vrs_g : vrs_d;
     j.koff = (tk + (kg ? 0 : dshift)) * KBYTES;
     j.voff = (tv + (vg ? 0 : vdshift)) * VBYTES;
     j.kdst = kstage + wv * (Copy::NK * 1024);
     j.vdst = vstage + wv * (Copy::NV * 1024);
+    j.k_through_idx = GATHER && kg;
+    if constexpr (GATHER) {
+#pragma unroll
+      for (int q = 0; q < Copy::NK; ++q)       // the chunk inside the row stays the swizzled one of klo
+        j.kgo[q] = rows_k.pos[q] >= 0 ? rows_k.pos[q] * (D * 2) + (klo[q] - krow[q] * (D * 2)) : 0x7FFFFFF0;
+    }
     return j;
   };
   auto copy_load = [&](const CopyJob& job, int j) {
-    if (j < Copy::NK) copy16_to_lds(job.krs, klo[j], job.koff, job.kdst + j * 1024);
-    else copy16_to_lds(job.vrs, vlo[j - Copy::NK], job.voff, job.vdst + (j - Copy::NK) * 1024);
+    if (j < Copy::NK) {
+      if (GATHER && job.k_through_idx) copy16_to_lds(job.krs, job.kgo[j], 0, job.kdst + j * 1024);
+      else copy16_to_lds(job.krs, klo[j], job.koff, job.kdst + j * 1024);
+    } else {
+      copy16_to_lds(job.vrs, vlo[j - Copy::NK], job.voff, job.vdst + (j - Copy::NK) * 1024);
+    }
   };
 
   f32x16_t o[QB][DS];
@@ -550,6 +587,7 @@ void prefill_mfma_kernel(
   bf16x8_t pf[QB][2][2];                 // P of block 0: formed and used inside a step; of block 1: formed one step ahead
 
   int rpos = 0;                          // it % RING of the step about to run
+  TileRows rows_ahead = {};              // GATHER: row positions of tile it + RING, read during step it - 1
   static_assert((RING - 2) * Copy::N < 16, "the wait below encodes its count in four bits");
 
   // One pipeline step: tile `it` (scores in sc; with QB = 2 those of block 1 are already in pf[1])
@@ -562,7 +600,10 @@ void prefill_mfma_kernel(
     __syncthreads();
     const int tk = it + RING < last ? it + RING : last, tv = it + RING - 1 < last ? it + RING - 1 : last;   // past the end: a harmless reload
     const int r_next = rpos + 1 == RING ? 0 : rpos + 1, r_prev = rpos == 0 ? RING - 1 : rpos - 1;   // (it +- 1) % RING
-    const CopyJob job = copy_job(tk, tv, kring + rpos * KBYTES, vring + r_prev * VBYTES);
+    const CopyJob job = copy_job(tk, tv, kring + rpos * KBYTES, vring + r_prev * VBYTES, rows_ahead);
+    // GATHER: the positions for the copies of the next step are requested before this step's copies,
+    // so that the wait at the top of the next step, which lets only the newest copies pass, covers them
+    if constexpr (GATHER) rows_ahead = load_tile_rows(it + 1 + RING < last ? it + 1 + RING : last);
     const unsigned char* kb = kring + r_next * KBYTES;
     const unsigned char* vb = vring + rpos * VBYTES;
     rpos = r_next;
@@ -641,18 +682,21 @@ void prefill_mfma_kernel(
   f32x16_t sa[QB][2], sb[QB][2];
   {
     auto tile_or_last = [&](int t) { return t < last ? t : last; };
-    const CopyJob first = copy_job(0, 0, kring, vring);
+    const CopyJob first = copy_job(0, 0, kring, vring, load_tile_rows(0));
 #pragma unroll
     for (int j = 0; j < Copy::N; ++j) copy_load(first, j);
-    const CopyJob second = copy_job(tile_or_last(1), 0, kring + KBYTES, vring);
+    const CopyJob second = copy_job(tile_or_last(1), 0, kring + KBYTES, vring, load_tile_rows(tile_or_last(1)));
 #pragma unroll
     for (int j = 0; j < Copy::NK; ++j) copy_load(second, j);
     if constexpr (RING == 3) {
-      const CopyJob third = copy_job(tile_or_last(2), tile_or_last(1), kring + 2 * KBYTES, vring + VBYTES);
+      const CopyJob third = copy_job(tile_or_last(2), tile_or_last(1), kring + 2 * KBYTES, vring + VBYTES,
+                                     load_tile_rows(tile_or_last(2)));
 #pragma unroll
       for (int j = 0; j < Copy::N; ++j) copy_load(third, j);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (Copy::NK + (RING - 2) * Copy::N));   // K(0), V^T(0) are in
+    if constexpr (GATHER) rows_ahead = load_tile_rows(tile_or_last(RING));    // for the copies of step 0
+    // K(0), V^T(0) are in (GATHER: the positions just requested count among the newest as well)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (Copy::NK + (RING - 2) * Copy::N + (GATHER ? Copy::NK : 0)));
     __syncthreads();
     s_tile(kring, sa, [&](int) {});
     if constexpr (QB == 2) {            // block 1 runs half a step ahead with its exponentials
@@ -747,11 +791,21 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hs, offs[Hs]), max_dense_tiles(n_queries, w));
   unsigned long long* clk = diag_prefill_clocks() ? mw.clk : nullptr;   // cycle counters only when asked for
 
-  if (max_tiles > 0)
-    hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, Vg, (int64_t)0,
-                       n_rows, (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr);
+  // gather-free call (no compacted copy of the kept rows): V^T tiles of the regions are built from the
+  // dense V through idx, and the attention kernel fetches the K rows of its region tiles the same way
+  const bool gather = Kg == nullptr;
+  if (max_tiles > 0) {
+    if (gather)
+      hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, V, kv_stride, n_rows,
+                         (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr, idx, Hs / Hkv);
+    else
+      hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, Vg, (int64_t)0, n_rows,
+                         (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr,
+                         (const int32_t*)nullptr, 1);
+  }
   hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
-                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, clk);
+                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, clk,
+                     (const int32_t*)nullptr, 1);
 
   // Shape of a workgroup.  Long calls: eight waves of 32 queries (256 queries, one workgroup per CU,
   // two waves per SIMD, rings of three tiles).  Calls with few query tiles: four waves of 32 queries
@@ -759,18 +813,26 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   // queries (one wave per SIMD, every LDS fragment feeds two MFMAs, half the LDS reads) stay
   // selectable through the diagnostics switch: measured 5-8 % slower on 128K tokens, because a
   // lone wave cannot issue its vector, LDS and scalar instructions fast enough beside the MFMAs.
-  auto launch = [&](auto nw_tag, auto qb_tag) {
+  auto launch = [&](auto nw_tag, auto qb_tag, auto gather_tag) {
     constexpr int NW = decltype(nw_tag)::value, QB = decltype(qb_tag)::value;
+    constexpr bool GATHER = decltype(gather_tag)::value;
     const int n_qt = (int)((n_queries + NW * QB * 32 - 1) / (NW * QB * 32));
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB, GATHER>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
                        Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, clk);
   };
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I4 = std::integral_constant<int, 4>;
+  using I8 = std::integral_constant<int, 8>;
   const int variant = prefill_variant();
   const bool many = ((n_queries + 255) / 256) * Hq >= 1024;
-  if (variant == 3 || (variant == 0 && many)) launch(std::integral_constant<int, 8>{}, std::integral_constant<int, 1>{});
-  else if (variant == 2) launch(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
-  else launch(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
+  if (gather) {                                  // the two shapes the size of a call chooses between
+    if (variant == 3 || (variant != 1 && many)) launch(I8{}, I1{}, std::true_type{});
+    else launch(I4{}, I1{}, std::true_type{});
+  } else if (variant == 3 || (variant == 0 && many)) launch(I8{}, I1{}, std::false_type{});
+  else if (variant == 2) launch(I4{}, I2{}, std::false_type{});
+  else launch(I4{}, I1{}, std::false_type{});
 }
 
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,

@@ -66,8 +66,14 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     const T *kr = K, *vr = V;
     if (ok) {
       if (k < n_glob) {
-        kr = Kg + (size_t)(base + k) * D;
-        vr = Vg + (size_t)(base + k) * D;
+        if (Kg) {
+          kr = Kg + (size_t)(base + k) * D;
+          vr = Vg + (size_t)(base + k) * D;
+        } else {                                       // gather-free call: the kept rows are read where they lie
+          const size_t row = (size_t)kvh * kv_stride + idx[base + k];
+          kr = K + row * D;
+          vr = V + row * D;
+        }
       } else {
         const size_t row = (size_t)kvh * kv_stride + (win0 + (k - n_glob));
         kr = K + row * D;

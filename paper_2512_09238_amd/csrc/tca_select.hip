@@ -523,6 +523,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   const int sub = tid % LPR;
   int n_keep = t;
   if (dst0 + n_keep > cap) n_keep = cap > dst0 ? (int)(cap - dst0) : 0;
+  if (!Kg) {                                           // positions only: no compacted copy is kept
+    for (int k = tid; k < n_keep; k += kGatherThreads) idx[base + dst0 + k] = (int32_t)(pos0 + j * b + sel[k]);
+    return;
+  }
   for (int k0 = tid / LPR; k0 < n_keep; k0 += kRows * RPI) {
     uint4 kr[kRows], vr[kRows];
     int64_t pos[kRows];
@@ -674,8 +678,10 @@ extern "C" int tca_select(const tca_params* prm, const void* q_last, const void*
                           void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(prm);
   if (rc) return rc;
-  if (!q_last || !K || !V || !p || !offs || !n_rows || !idx || !Kg || !Vg || !ws)
+  if (!q_last || !K || !V || !p || !offs || !n_rows || !idx || !ws)
     return fail(TCA_ERR_INVALID, "tca_select: NULL pointer argument");
+  if ((Kg == nullptr) != (Vg == nullptr))
+    return fail(TCA_ERR_INVALID, "tca_select: Kg and Vg must both be given, or both be NULL (positions only)");
   const int b = prm->block, Hs = sel_heads(prm);
   if (n_tokens < 0 || pos0 < 0 || pos0 % b != 0 || pos0 + n_tokens > kv_stride)
     return fail(TCA_ERR_INVALID, "tca_select: pos0=%lld n_tokens=%lld kv_stride=%lld (pos0 must be a "

@@ -223,6 +223,61 @@ def test_prefill_every_workgroup_shape_matches_oracle(tb, bufs, case, variant):
             assert abs(lg[h, i] - lref) <= 5e-2
 
 
+@pytest.mark.parametrize("variant", [1, 3], ids=lambda v: {1: "4x32", 3: "8x32"}[v])
+@pytest.mark.parametrize("case", [PREFILL_CASES[0], PREFILL_CASES[1], PREFILL_CASES[2], PREFILL_CASES[4], PREFILL_CASES[6], PREFILL_CASES[7]],
+                         ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}-w{c[7]}")
+def test_gather_free_select_and_prefill(tb, bufs, case, variant):
+    """tca_select with no Kg / Vg writes the same positions; tca_prefill with no Kg / Vg reads the
+    kept rows through idx and gives the same output as the call on the compacted copy, bit for
+    bit (the same numbers reach the same arithmetic), which in turn matches the oracle."""
+    kind, Hq, Hkv, d, L, dtype, b, w, seed = case
+    if dtype == "f32" and variant == 3:
+        pytest.skip("the fp32 row kernel has one shape")
+    print("case", case, "variant", variant, flush=True)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+    # positions only
+    idx2 = torch.full_like(gb.idx, -1)
+    n2 = torch.zeros_like(gb.n_rows)
+    ws = bufs.workspace(max(tb.tca_select_workspace_bytes(prm, L), tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1]))))
+    tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P_gpu, gb.offs, n2, idx2, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(n2, gb.n_rows)
+    for h in range(Hq):
+        o, n = int(gb.offs[h]), int(gb.n_rows[h].item())
+        assert torch.equal(idx2[o:o + n], gb.idx[o:o + n]), f"head {h}"
+    O1 = torch.full_like(Qd, float("nan"))
+    O2 = torch.full_like(Qd, float("nan"))
+    q0 = L // 3                                         # a chunk of queries at q_pos0 > 0 as well
+    Qt = Qd[:, q0:].contiguous()
+    O1t, O2t = torch.full_like(Qt, float("nan")), torch.full_like(Qt, float("nan"))
+    try:
+        tb.tca_diag_prefill_variant(variant)
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O1, None, ws)
+        tb.tca_prefill(prm, Qt, q0, L - q0, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O1t, None, ws)
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, idx2, None, None, gb.offs, n2, O2, None, ws)
+        tb.tca_prefill(prm, Qt, q0, L - q0, Kd, Vd, L, idx2, None, None, gb.offs, n2, O2t, None, ws)
+        torch.cuda.synchronize()
+    finally:
+        tb.tca_diag_prefill_variant(0)
+    assert not torch.isnan(O2.float()).any()
+    assert torch.equal(O1, O2) and torch.equal(O1t, O2t)
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    for h in range(Hq):
+        got = H.head_indices(gb, h)
+        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+            Oref[h] = orc.tca_attention(Qf[h], Kf[h // (Hq // Hkv)], Vf[h // (Hq // Hkv)], got, w)
+    err = np.abs(bufs.to_host_f64(O2) - Oref).max()
+    print("max abs err", err, flush=True)
+    assert err <= H.TOL[dtype]
+    with pytest.raises(tb.TcaError):                    # one of the two without the other
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, idx2, gb.Kg, None, gb.offs, n2, O2, None, ws)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_prefill_full_budget_is_dense_and_chunked_queries(tb, bufs, dtype):
     """One-hot at k=b keeps everything: the result is dense causal attention
