@@ -195,6 +195,43 @@ int tca_prefill(const tca_params* prm, const void* Q, int64_t q_pos0, int64_t n_
                 const int64_t* offs, const int32_t* n_rows,
                 void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/* Eq. 2 over one of the two key subsets alone, and the merge of two such results: the pieces of
+ * tca_select_prefill_overlapped below, usable on their own.
+ * tca_prefill_part: as tca_prefill, restricted to TCA_PART_WINDOW (the dense keys of each query's
+ * window; idx, Kg, Vg, n_rows are not read and need not be filled yet) or TCA_PART_GLOBAL (the
+ * global rows with idx <= i-w); TCA_PART_ALL is tca_prefill.  O holds the attention normalised
+ * over that subset, lse (required for a part) the log-sum-exp of its scaled logits; a query
+ * that sees nothing of the subset gets zeros and lse = -inf.
+ * tca_prefill_merge: O_a <- (e^{lse_a} O_a + e^{lse_b} O_b) / (e^{lse_a} + e^{lse_b}), row by row:
+ * the one softmax of Eq. 2 over the union of two disjoint key sets.  O_a, O_b: device
+ * [Hq, n_queries, d]; lse_a, lse_b: device float [Hq, n_queries]; lse_out: the same or NULL. */
+#define TCA_PART_ALL    0
+#define TCA_PART_WINDOW 1
+#define TCA_PART_GLOBAL 2
+int tca_prefill_part(const tca_params* prm, int part, const void* Q, int64_t q_pos0, int64_t n_queries,
+                     const void* K, const void* V, int64_t kv_stride,
+                     const int32_t* idx, const void* Kg, const void* Vg,
+                     const int64_t* offs, const int32_t* n_rows,
+                     void* O, float* lse, void* ws, size_t ws_bytes, void* stream);
+int tca_prefill_merge(const tca_params* prm, int64_t n_queries, void* O_a, const float* lse_a,
+                      const void* O_b, const float* lse_b, float* lse_out, void* stream);
+
+/* tca_select followed by tca_prefill over the same tokens [pos0, pos0 + n_tokens), with the
+ * window part of the attention overlapped with the selection (App. C names this overlap as a
+ * further optimisation): the window part runs on side_stream from the point `stream` has reached
+ * at the call, the selection and the global part on `stream`, which then waits for the window
+ * part and merges.  Arguments as for tca_select (q_last .. Vg) and tca_prefill (Q with q_pos0 =
+ * pos0, O); O_part: device scratch shaped like O; lse_parts: device float [2][Hq][n_tokens];
+ * the two workspaces as for tca_select and tca_prefill (one prefill workspace serves both parts).
+ * Results equal tca_select + tca_prefill up to the rounding of the two partial outputs to the
+ * storage type.  Creates and destroys two events; does not synchronise. */
+int tca_select_prefill_overlapped(const tca_params* prm, const void* q_last, const void* Q,
+                                  const void* K, const void* V, int64_t kv_stride, int64_t pos0,
+                                  int64_t n_tokens, const double* p, const int64_t* offs,
+                                  int32_t* n_rows, int32_t* idx, void* Kg, void* Vg, void* O,
+                                  void* O_part, float* lse_parts, void* ws_select, size_t ws_select_bytes,
+                                  void* ws_prefill, size_t ws_prefill_bytes, void* stream, void* side_stream);
+
 /* Storage of the rows of the decode cache.  TCA_KV_NATIVE: rows of tca_params.dtype.
  * TCA_KV_FP8 (an extension, not in the paper; requires dtype TCA_BF16): a row x of d numbers is
  * kept as d FP8 E4M3 codes (OCP 8-bit floating point: bias 7, largest finite value 448, no

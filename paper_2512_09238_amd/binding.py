@@ -20,6 +20,7 @@ TCA_BF16, TCA_F32 = 0, 1
 TCA_METRIC_HHI, TCA_METRIC_ENTROPY = 0, 1
 TCA_SHARE_HEAD, TCA_SHARE_GROUP = 0, 1
 TCA_KV_NATIVE, TCA_KV_FP8 = 0, 1
+TCA_PART_ALL, TCA_PART_WINDOW, TCA_PART_GLOBAL = 0, 1, 2
 TCA_ROPE_HALF, TCA_ROPE_INTERLEAVED = 0, 1
 TCA_OK, TCA_ERR_INVALID, TCA_ERR_UNSUPPORTED, TCA_ERR_WORKSPACE, TCA_ERR_HIP = 0, -1, -2, -3, -4
 
@@ -78,6 +79,16 @@ EXPORTS = {
     "tca_prefill": (C.c_int, [_P(tca_params), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                               C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, _i64_p, C.c_void_p,
                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_prefill_part": (C.c_int, [_P(tca_params), C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                   C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, _i64_p, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "tca_prefill_merge": (C.c_int, [_P(tca_params), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]),
+    "tca_select_prefill_overlapped": (C.c_int, [_P(tca_params), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_int64, C.c_int64, C.c_int64, _dbl_p, _i64_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t,
+                                                C.c_void_p, C.c_void_p]),
     "tca_cache_load_window": (C.c_int, [_P(tca_params), _P(tca_cache), C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_int64, C.c_int64, C.c_void_p]),
     "tca_cache_load_global": (C.c_int, [_P(tca_params), _P(tca_cache), C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -217,6 +228,32 @@ def tca_prefill(prm, Q, q_pos0, n_queries, K, V, kv_stride, idx, Kg, Vg, offs, n
     _check(lib.tca_prefill(C.byref(prm), _dp(Q), q_pos0, n_queries, _dp(K), _dp(V), kv_stride, _dp(idx),
                            _dp(Kg), _dp(Vg), offs.ctypes.data_as(_i64_p), _dp(n_rows), _dp(O), _dp(lse),
                            wsp, wsb, _stream(stream)))
+
+
+def tca_prefill_part(prm, part, Q, q_pos0, n_queries, K, V, kv_stride, idx, Kg, Vg, offs, n_rows, O, lse, ws, stream=None):
+    offs = _host(offs, np.int64)
+    wsp, wsb = _ws_args(ws)
+    _check(lib.tca_prefill_part(C.byref(prm), part, _dp(Q), q_pos0, n_queries, _dp(K), _dp(V), kv_stride, _dp(idx),
+                                _dp(Kg), _dp(Vg), offs.ctypes.data_as(_i64_p), _dp(n_rows), _dp(O), _dp(lse),
+                                wsp, wsb, _stream(stream)))
+
+
+def tca_prefill_merge(prm, n_queries, O_a, lse_a, O_b, lse_b, lse_out=None, stream=None):
+    _check(lib.tca_prefill_merge(C.byref(prm), n_queries, _dp(O_a), _dp(lse_a), _dp(O_b), _dp(lse_b), _dp(lse_out),
+                                 _stream(stream)))
+
+
+def tca_select_prefill_overlapped(prm, q_last, Q, K, V, kv_stride, pos0, n_tokens, p, offs, n_rows, idx, Kg, Vg, O,
+                                  O_part, lse_parts, ws_select, ws_prefill, side_stream, stream=None):
+    p = _host(p, np.float64)
+    offs = _host(offs, np.int64)
+    wsp, wsb = _ws_args(ws_select)
+    wpp, wpb = _ws_args(ws_prefill)
+    _check(lib.tca_select_prefill_overlapped(C.byref(prm), _dp(q_last), _dp(Q), _dp(K), _dp(V), kv_stride, pos0,
+                                             n_tokens, p.ctypes.data_as(_dbl_p), offs.ctypes.data_as(_i64_p),
+                                             _dp(n_rows), _dp(idx), _dp(Kg), _dp(Vg), _dp(O), _dp(O_part),
+                                             _dp(lse_parts), wsp, wsb, wpp, wpb, _stream(stream),
+                                             C.c_void_p(int(side_stream))))
 
 
 def make_cache(batch, cap_rows, idx, Kg, Vg, n_rows, ringK, ringV, length, kv_format=TCA_KV_NATIVE,

@@ -12,13 +12,13 @@ namespace tca {
 template <typename T>
 int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64_t n_queries, const T* K,
                         const T* V, int64_t kv_stride, const int32_t* idx, const T* Kg, const T* Vg,
-                        const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st);
+                        const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st, int part);
 
 // bf16 MFMA flash kernel.
 size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, int64_t cap_rows);
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
                         const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
                         const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,
-                        bf16_t* O, float* lse, void* ws, hipStream_t st);
+                        bf16_t* O, float* lse, void* ws, hipStream_t st, int part);
 
 }  // namespace tca

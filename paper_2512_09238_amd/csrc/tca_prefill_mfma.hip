@@ -264,7 +264,9 @@ void prefill_mfma_kernel(
     int64_t kv_stride, const int32_t* __restrict__ idx, const uint16_t* __restrict__ Kg,
     const int32_t* __restrict__ n_rows, const uint16_t* __restrict__ Vgt, const uint16_t* __restrict__ Vt,
     int64_t dense_tile0, int dense_tiles, PrefillHeads ph, int Hq, int G, int GS, int w, float scale,
-    uint16_t* __restrict__ O, float* __restrict__ lse, unsigned long long* __restrict__ clk) {
+    uint16_t* __restrict__ O, float* __restrict__ lse, unsigned long long* __restrict__ clk, int part) {
+  // part: TCA_PART_ALL, or one of the two key subsets alone (TCA_PART_WINDOW: the dense window;
+  // TCA_PART_GLOBAL: the region), each normalised by itself, to be merged through lse
   constexpr int KK = D / 16;             // MFMA k-steps over the head dimension
   constexpr int DS = D / 32;             // 32-row slices of O^T
   constexpr int WQ = QB * 32;            // queries per wave
@@ -309,7 +311,7 @@ void prefill_mfma_kernel(
   // ---- per-lane query state (lane column c = one query of each block)
   const int hs = h / GS;                           // the selection this query head reads (GS query heads share it)
   const int64_t base = ph.offs[hs];
-  const int nr = n_rows[hs];
+  const int nr = part == TCA_PART_WINDOW ? 0 : n_rows[hs];     // without the region nothing below sees a global row
   int qpos[QB], nvis[QB];
   bf16x8_t qf[QB][KK];
 #pragma unroll
@@ -334,8 +336,23 @@ void prefill_mfma_kernel(
   const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
   const int win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
   const int wt0 = win_lo / kBN, wt1 = wg_last / kBN;                      // absolute dense tiles [wt0, wt1]
-  const int n_tiles = n_gt + (wt1 - wt0 + 1);
+  const int n_tiles = n_gt + (part == TCA_PART_GLOBAL ? 0 : wt1 - wt0 + 1);
   const int last = n_tiles - 1;
+  if (n_tiles == 0) {                              // TCA_PART_GLOBAL with no visible global row: an empty part
+#pragma unroll
+    for (int blk = 0; blk < QB; ++blk) {
+      const int64_t r = r0 + wv * WQ + blk * 32 + c;
+      if (r <= last_row) {
+        uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
+#pragma unroll
+        for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) *reinterpret_cast<uint2*>(orow + sl * 32 + 8 * q4 + 4 * hh) = make_uint2(0u, 0u);
+        if (lse && hh == 0) lse[(size_t)h * n_queries + r] = -INFINITY;
+      }
+    }
+    return;
+  }
   const int dshift = wt0 - n_gt;                   // tile t >= n_gt is the dense tile t + dshift
 
   // ---- sources of the tile copies: one descriptor per buffer, the tile chosen by a scalar byte offset
@@ -723,7 +740,7 @@ void prefill_mfma_kernel(
     const float lt = half_sum(l[blk]);
     if constexpr (QB == 2) settle_acc(o[blk]);
     if (r <= last_row) {
-      const float inv = 1.f / lt;
+      const float inv = lt > 0.f ? 1.f / lt : 0.f;    // a query that sees nothing of this part: zeros, lse = -inf
       uint16_t* orow = O + ((size_t)h * n_queries + r) * D;
 #pragma unroll
       for (int sl = 0; sl < DS; ++sl)
@@ -734,7 +751,7 @@ void prefill_mfma_kernel(
           for (int j = 0; j < 4; ++j) pk[j] = (__bf16)(o[blk][sl][4 * q4 + j] * inv);
           *reinterpret_cast<bf16x4_t*>(orow + sl * 32 + 8 * q4 + 4 * hh) = pk;
         }
-      if (lse && hh == 0) lse[(size_t)h * n_queries + r] = m[blk] * scale + __logf(lt);
+      if (lse && hh == 0) lse[(size_t)h * n_queries + r] = lt > 0.f ? m[blk] * scale + __logf(lt) : -INFINITY;
     }
   }
 }
@@ -771,7 +788,7 @@ template <int D>
 static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, int64_t n_queries,
                      const uint16_t* K, const uint16_t* V, int64_t kv_stride, const int32_t* idx,
                      const uint16_t* Kg, const uint16_t* Vg, const int64_t* offs, const int32_t* n_rows,
-                     uint16_t* O, float* lse, void* ws, hipStream_t st) {
+                     uint16_t* O, float* lse, void* ws, hipStream_t st, int part) {
   const int Hq = prm->n_q_heads, Hkv = prm->n_kv_heads, Hs = sel_heads(prm), w = prm->window;
   PrefillHeads ph;
   int32_t run = 0;
@@ -789,12 +806,14 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   const int64_t dt0 = win_lo / kBN, dt1 = (q_pos0 + n_queries - 1) / kBN;
   const int d_tiles = (int)(dt1 - dt0 + 1);
   MfmaWs mw = carve_mfma_ws(ws, prm, max_region_tiles(Hs, offs[Hs]), max_dense_tiles(n_queries, w));
-  unsigned long long* clk = diag_prefill_clocks() ? mw.clk : nullptr;   // cycle counters only when asked for
+  // cycle counters only when asked for (and not for a part: two parts may run side by side on one workspace,
+  // where the window part touches only the dense V^T tiles and the global part only the regions')
+  unsigned long long* clk = diag_prefill_clocks() && part == TCA_PART_ALL ? mw.clk : nullptr;
 
   // gather-free call (no compacted copy of the kept rows): V^T tiles of the regions are built from the
   // dense V through idx, and the attention kernel fetches the K rows of its region tiles the same way
   const bool gather = Kg == nullptr;
-  if (max_tiles > 0) {
+  if (max_tiles > 0 && part != TCA_PART_WINDOW) {
     if (gather)
       hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(max_tiles, Hs), dim3(256), 0, st, V, kv_stride, n_rows,
                          (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr, idx, Hs / Hkv);
@@ -803,9 +822,10 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
                          (int64_t)0, (int64_t)0, mw.Vgt, 0, ph, 0, (unsigned long long*)nullptr,
                          (const int32_t*)nullptr, 1);
   }
-  hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
-                     (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, clk,
-                     (const int32_t*)nullptr, 1);
+  if (part != TCA_PART_GLOBAL)
+    hipLaunchKernelGGL((transpose_tiles_kernel<D>), dim3(d_tiles, Hkv), dim3(256), 0, st, V, kv_stride,
+                       (const int32_t*)nullptr, q_pos0 + n_queries, dt0 * kBN, mw.Vt, d_tiles, ph, 1, clk,
+                       (const int32_t*)nullptr, 1);
 
   // Shape of a workgroup.  Long calls: eight waves of 32 queries (256 queries, one workgroup per CU,
   // two waves per SIMD, rings of three tiles).  Calls with few query tiles: four waves of 32 queries
@@ -819,7 +839,7 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
     const int n_qt = (int)((n_queries + NW * QB * 32 - 1) / (NW * QB * 32));
     hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB, GATHER>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
-                       Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, clk);
+                       Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, clk, part);
   };
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
@@ -838,7 +858,7 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,
                         const bf16_t* K, const bf16_t* V, int64_t kv_stride, const int32_t* idx,
                         const bf16_t* Kg, const bf16_t* Vg, const int64_t* offs, const int32_t* n_rows,
-                        bf16_t* O, float* lse, void* ws, hipStream_t st) {
+                        bf16_t* O, float* lse, void* ws, hipStream_t st, int part) {
   // the kernel addresses tiles with 32-bit byte offsets inside each buffer
   const int64_t row_bytes = (int64_t)prm->head_dim * 2;
   int64_t max_rows = q_pos0 + n_queries + prm->window + 2 * kBN;
@@ -850,10 +870,10 @@ int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, 
   auto u = [](const bf16_t* p) { return reinterpret_cast<const uint16_t*>(p); };
   if (prm->head_dim == 128)
     run_mfma<128>(prm, u(Q), q_pos0, n_queries, u(K), u(V), kv_stride, idx, u(Kg), u(Vg), offs, n_rows,
-                  reinterpret_cast<uint16_t*>(O), lse, ws, st);
+                  reinterpret_cast<uint16_t*>(O), lse, ws, st, part);
   else
     run_mfma<64>(prm, u(Q), q_pos0, n_queries, u(K), u(V), kv_stride, idx, u(Kg), u(Vg), offs, n_rows,
-                 reinterpret_cast<uint16_t*>(O), lse, ws, st);
+                 reinterpret_cast<uint16_t*>(O), lse, ws, st, part);
   return TCA_OK;
 }
 

@@ -36,7 +36,7 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     const T* __restrict__ V, int64_t kv_stride, const int32_t* __restrict__ idx,
     const T* __restrict__ Kg, const T* __restrict__ Vg, HeadOffs ho,
     const int32_t* __restrict__ n_rows, int G, int GS, int w, double scale, T* __restrict__ O,
-    float* __restrict__ lse) {
+    float* __restrict__ lse, int part) {
   constexpr int EL = D / 16;                       // elements of a row per lane
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int grp = lane >> 4, sub = lane & 15;
@@ -51,9 +51,10 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
 
   const int hs = h / GS;                           // the selection this query head reads
   const int64_t base = ho.offs[hs];
-  const int n_glob = count_le(idx + base, n_rows[hs], i - w);
+  // part: both key subsets, or one of them alone (normalised by itself; merged later through lse)
+  const int n_glob = part == TCA_PART_WINDOW ? 0 : count_le(idx + base, n_rows[hs], i - w);
   const int64_t win0 = i - w + 1 > 0 ? i - w + 1 : 0;
-  const int64_t n_keys = n_glob + (i - win0 + 1);
+  const int64_t n_keys = n_glob + (part == TCA_PART_GLOBAL ? 0 : i - win0 + 1);
 
   double m = -INFINITY;
   float l = 0.f, acc[EL];
@@ -108,17 +109,17 @@ __global__ __launch_bounds__(kRowThreads) void prefill_rows_kernel(
     m = mn;
   }
   if (grp == 0) {
-    const float inv = 1.f / l;
+    const float inv = l > 0.f ? 1.f / l : 0.f;         // an empty part: zeros, lse = -inf
 #pragma unroll
     for (int e = 0; e < EL; ++e) store_f32(O + ((size_t)h * n_queries + r) * D + sub * EL + e, acc[e] * inv);
-    if (lse && sub == 0) lse[(size_t)h * n_queries + r] = (float)(m + log((double)l));
+    if (lse && sub == 0) lse[(size_t)h * n_queries + r] = l > 0.f ? (float)(m + log((double)l)) : -INFINITY;
   }
 }
 
 template <typename T>
 int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64_t n_queries, const T* K,
                         const T* V, int64_t kv_stride, const int32_t* idx, const T* Kg, const T* Vg,
-                        const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st) {
+                        const int64_t* offs, const int32_t* n_rows, T* O, float* lse, hipStream_t st, int part) {
   HeadOffs ho;
   for (int h = 0; h <= sel_heads(prm); ++h) ho.offs[h] = offs[h];
   const int GS = sel_group(prm);
@@ -127,19 +128,19 @@ int launch_prefill_rows(const tca_params* prm, const T* Q, int64_t q_pos0, int64
   const double scale = logit_scale(prm);
   if (prm->head_dim == 128)
     hipLaunchKernelGGL((prefill_rows_kernel<T, 128>), grid, dim3(kRowThreads), 0, st, Q, q_pos0, n_queries,
-                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse);
+                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse, part);
   else
     hipLaunchKernelGGL((prefill_rows_kernel<T, 64>), grid, dim3(kRowThreads), 0, st, Q, q_pos0, n_queries,
-                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse);
+                       K, V, kv_stride, idx, Kg, Vg, ho, n_rows, G, GS, prm->window, scale, O, lse, part);
   return TCA_OK;
 }
 
 template int launch_prefill_rows<float>(const tca_params*, const float*, int64_t, int64_t, const float*,
                                         const float*, int64_t, const int32_t*, const float*, const float*,
-                                        const int64_t*, const int32_t*, float*, float*, hipStream_t);
+                                        const int64_t*, const int32_t*, float*, float*, hipStream_t, int);
 template int launch_prefill_rows<bf16_t>(const tca_params*, const bf16_t*, int64_t, int64_t, const bf16_t*,
                                          const bf16_t*, int64_t, const int32_t*, const bf16_t*,
                                          const bf16_t*, const int64_t*, const int32_t*, bf16_t*, float*,
-                                         hipStream_t);
+                                         hipStream_t, int);
 
 }  // namespace tca

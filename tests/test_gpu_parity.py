@@ -278,6 +278,74 @@ def test_gather_free_select_and_prefill(tb, bufs, case, variant):
         tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, idx2, gb.Kg, None, gb.offs, n2, O2, None, ws)
 
 
+@pytest.mark.parametrize("variant", [1, 3], ids=lambda v: {1: "4x32", 3: "8x32"}[v])
+@pytest.mark.parametrize("case", [PREFILL_CASES[0], PREFILL_CASES[1], PREFILL_CASES[2], PREFILL_CASES[4], PREFILL_CASES[6]],
+                         ids=lambda c: f"{c[0]}-Hq{c[1]}-d{c[3]}-L{c[4]}-{c[5]}-b{c[6]}-w{c[7]}")
+def test_window_part_overlapped_with_selection(tb, bufs, case, variant):
+    """Alg. 2 with the window part of Eq. 2 started before the selection (the overlap App. C names):
+    the window part alone is attention with an empty global subset, the merged result is Eq. 2."""
+    kind, Hq, Hkv, d, L, dtype, b, w, seed = case
+    if dtype == "f32" and variant == 3:
+        pytest.skip("the fp32 row kernel has one shape")
+    print("case", case, "variant", variant, flush=True)
+    x = wl.prefill_inputs(kind, Hq, Hkv, d, L, dtype, seed)
+    fr = wl.budget_fractions(seed + 1, Hq)
+    P_gpu, P_orc = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
+    gb = bufs.GlobalBuffers(prm, rows)
+    Qd, Kd, Vd = bufs.to_device(x["Q"]), bufs.to_device(x["K"]), bufs.to_device(x["V"])
+    q_last = Qd[:, L - 1].contiguous()
+    ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    ws_pf = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    O = torch.full_like(Qd, float("nan"))
+    O_part = torch.full_like(Qd, float("nan"))
+    lse_parts = torch.full((2, Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    try:
+        tb.tca_diag_prefill_variant(variant)
+        tb.tca_select_prefill_overlapped(prm, q_last, Qd, Kd, Vd, L, 0, L, P_gpu, gb.offs, gb.n_rows, gb.idx, gb.Kg,
+                                         gb.Vg, O, O_part, lse_parts, ws_sel, ws_pf, side.cuda_stream)
+        torch.cuda.synchronize()
+    finally:
+        tb.tca_diag_prefill_variant(0)
+    Qf, Kf, Vf = wl.to_f64(x["Q"]), wl.to_f64(x["K"]), wl.to_f64(x["V"])
+    Oref, sels = orc.tca_prefill(Qf, Kf, Vf, b, w, P_orc, 0.5)
+    none = np.zeros(0, np.int64)
+    worst_w = 0.0
+    for h in range(Hq):
+        g = h // (Hq // Hkv)
+        got = H.head_indices(gb, h)
+        if not H.assert_selection(sels[h], got, b, P_orc[h], tag=f"head {h}"):
+            Oref[h] = orc.tca_attention(Qf[h], Kf[g], Vf[g], got, w)
+        worst_w = max(worst_w, np.abs(bufs.to_host_f64(O_part[h]) - orc.tca_attention(Qf[h], Kf[g], Vf[g], none, w)).max())
+    Og = bufs.to_host_f64(O)
+    assert not np.isnan(Og).any()
+    err = np.abs(Og - Oref).max()
+    print("max abs err: merged", err, "window part alone", worst_w, flush=True)
+    assert err <= H.TOL[dtype] and worst_w <= H.TOL[dtype]
+    # queries that see no global row: the global part is empty (lse = -inf) and the merge returns the window part
+    lg = lse_parts[1].cpu().numpy()
+    first_global = min(int(sels[h].S[0]) for h in range(Hq) if len(sels[h].S))
+    assert np.all(np.isneginf(lg[:, : first_global + w])) and np.isfinite(lg[:, L - 1]).all()
+    assert torch.equal(O[:, : first_global + w], O_part[:, : first_global + w])
+    # the pieces on their own, on one stream, give the same
+    O2, O2p = torch.full_like(Qd, float("nan")), torch.full_like(Qd, float("nan"))
+    l2 = torch.full_like(lse_parts, float("nan"))
+    lm = torch.full((Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    tb.tca_prefill_part(prm, tb.TCA_PART_WINDOW, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O2p, l2[0], ws_pf)
+    tb.tca_prefill_part(prm, tb.TCA_PART_GLOBAL, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O2, l2[1], ws_pf)
+    tb.tca_prefill_merge(prm, L, O2, l2[1], O2p, l2[0], lm)
+    lse_all = torch.full((Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    O3 = torch.full_like(Qd, float("nan"))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O3, lse_all, ws_pf)
+    torch.cuda.synchronize()
+    assert torch.equal(O2, O) and torch.equal(O2p, O_part)
+    assert (lm - lse_all).abs().max().item() <= (5e-2 if dtype == "bf16" else 1e-3)
+    with pytest.raises(tb.TcaError):                    # a part without lse cannot be merged
+        tb.tca_prefill_part(prm, tb.TCA_PART_WINDOW, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O2p, None, ws_pf)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_prefill_full_budget_is_dense_and_chunked_queries(tb, bufs, dtype):
     """One-hot at k=b keeps everything: the result is dense causal attention
