@@ -24,9 +24,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-# HBM bytes per launch of prefill_mfma_kernel on the default workload, from the rocprofv3
-# --pmc runs summarised in profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, in KiB)
-PROFILED_PREFILL_TRAFFIC_BYTES = (7.0188e6 * 2.0 + 1.0496e6) * 1024
+# HBM bytes per kernel launch on the default workload come from the counter runs summarised in this
+# file (written by paper_2512_09238_amd.profile_summary); its figures are reported only while the
+# kernel sources still hash to what was profiled, else `traffic` is null
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic_config3.json")
 
 
 def log(*a):
@@ -131,6 +132,66 @@ def bench_prefill(args, tb, bufs, wl, torch, share=False, x=None):
     }
     host = {"x": x, "P": P, "idx": idx_host, "offs": gb.offs, "n_rows": n_rows, "O": O, "prm": prm, "budget": budget}
     return res, host
+
+
+def bench_switches(args, tb, bufs, wl, torch, host, cfg):
+    """The two switches beside the plain path, on the same inputs and budgets (not part of the default
+    run): gather-free prefill (no compacted copy of the kept rows) and the window part of the
+    attention overlapped with the selection; each at the full length and on the last 8192-token
+    chunk of the sequence with the earlier blocks already selected."""
+    x, P, prm = host["x"], host["P"], host["prm"]
+    Hq, Hkv, d, L, b = cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["L"], cfg["b"]
+    Hs = tb.tca_selection_heads(prm)
+    Qd, Kd, Vd = bufs.to_device(x["Q"]), bufs.to_device(x["K"]), bufs.to_device(x["V"])
+    side = torch.cuda.Stream()
+    out = {}
+    chunk = 8192
+    for name, pos0 in (("full_length", 0), ("last_chunk_8192", L - chunk)):
+        n = L - pos0
+        _, rows_prev = tb.tca_select_rows(prm, pos0 // b, P)
+        _, rows_new = tb.tca_select_rows(prm, n // b, P)
+        gb = bufs.GlobalBuffers(prm, rows_prev + rows_new)
+        ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, max(n, pos0)))
+        ws_pf = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, n, int(gb.offs[-1])))
+        if pos0:
+            tb.tca_select(prm, Qd[:, pos0 - 1].contiguous(), Kd, Vd, L, 0, pos0, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+        n_before = gb.n_rows.clone()
+        q_last = Qd[:, L - 1].contiguous()
+        Qc = Qd[:, pos0:].contiguous()
+        O, O_part = torch.empty_like(Qc), torch.empty_like(Qc)
+        lse_parts = torch.empty(2, Hq, n, dtype=torch.float32, device="cuda")
+
+        def plain():
+            tb.tca_select(prm, q_last, Kd, Vd, L, pos0, n, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+            tb.tca_prefill(prm, Qc, pos0, n, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws_pf)
+
+        def gather_free():
+            tb.tca_select(prm, q_last, Kd, Vd, L, pos0, n, P, gb.offs, gb.n_rows, gb.idx, None, None, ws_sel)
+            tb.tca_prefill(prm, Qc, pos0, n, Kd, Vd, L, gb.idx, None, None, gb.offs, gb.n_rows, O, None, ws_pf)
+
+        def overlapped():
+            tb.tca_select_prefill_overlapped(prm, q_last, Qc, Kd, Vd, L, pos0, n, P, gb.offs, gb.n_rows, gb.idx, gb.Kg,
+                                             gb.Vg, O, O_part, lse_parts, ws_sel, ws_pf, side.cuda_stream)
+
+        res = {}
+        for label, fn in (("plain", plain), ("gather_free", gather_free), ("overlapped", overlapped)):
+            if label == "gather_free" and pos0:
+                continue            # the earlier chunks' rows would have to be kept as positions only as well: same kernel, not timed twice
+            ms = []
+            for it in range(4):
+                gb.n_rows.copy_(n_before)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                torch.cuda.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            res[label + "_ms"] = float(np.mean(ms[1:]))
+        out[name] = res
+        log(f"[bench] switches, {name}: " + ", ".join(f"{k} {v:.3f}" for k, v in res.items()))
+        del gb, ws_sel, ws_pf, O, O_part, lse_parts, Qc
+    return out
 
 
 def cpu_baseline_prefill(host, cfg, wl, bufs, seconds=20.0, seed=5):
@@ -306,6 +367,8 @@ def main():
     ap.add_argument("--mixed", action="store_true", help="also time the config-5 ragged mixed batch (adds about a minute)")
     ap.add_argument("--prefill-variant", type=int, default=0,
                     help="workgroup shape of the bf16 prefill kernel (tca_diag_prefill_variant): 0 = automatic")
+    ap.add_argument("--switches", action="store_true",
+                    help="also time the gather-free prefill and the overlapped window part beside the plain path")
     ap.add_argument("--shared", action="store_true",
                     help="also time both workloads with one selection per KV head (tca_params.share), reported in 'shared_selection'")
     args = ap.parse_args()
@@ -340,6 +403,7 @@ def main():
         cpu = cpu_baseline_prefill(host, res["cfg"], wl, bufs, seconds=args.cpu_seconds)
         log(f"[bench] oracle: {cpu['value']:.2f} tokens/s on {cpu['cores']} threads; "
             f"max abs err vs GPU on sampled rows {cpu['max_abs_err_vs_gpu']:.3e}; index sets equal: {cpu['index_sets_equal_gpu']}")
+    switches = bench_switches(args, tb, bufs, wl, torch, host, res["cfg"]) if args.switches else None
     shared = None
     if args.shared:
         rs, hs_ = bench_prefill(args, tb, bufs, wl, torch, share=True, x=host["x"])
@@ -358,6 +422,14 @@ def main():
     mixed = bench_mixed(args, tb, bufs, wl, torch) if args.mixed else None
 
     cfg = res["cfg"]
+    import paper_2512_09238_amd.profile_summary as ps
+    default_workload = res["L"] == 131072 and args.calibrate and args.prefill_variant == 0
+    traffic_doc = ps.load_traffic(TRAFFIC_FILE) if default_workload else None
+    prefill_traffic = ps.kernel_bytes(traffic_doc, "prefill_mfma_kernel")
+    sel_traffic = None
+    if traffic_doc is not None:
+        parts = [ps.kernel_bytes(traffic_doc, k) for k in ("score_kernel", "gather_kernel")]   # assign_kernel: kilobytes
+        sel_traffic = sum(parts) if all(v is not None for v in parts) else None
     out = {
         "metric": "prefill tokens/s at 128K context (select + compaction + sparse attention, one layer)",
         "value": res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -372,7 +444,7 @@ def main():
         "roofline": {
             "kernel": "prefill_mfma_kernel", "bound": "mfma", "achieved": res["tflops"], "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": res["tflops"] / PEAK_BF16_TFLOPS,
-            "traffic": PROFILED_PREFILL_TRAFFIC_BYTES if (res["L"] == 131072 and args.calibrate) else None,
+            "traffic": prefill_traffic,
             "flops_per_launch": res["flops"], "visible_pairs": res["pairs"],
             "shader_clock_ghz": res["clock_ghz"],
             "mfma_probe": {
@@ -385,11 +457,15 @@ def main():
         "select_roofline": {
             "bound": "hbm", "achieved": res["select_gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": res["select_gbs"] / PEAK_HBM_GBS, "bytes_per_launch": res["select_bytes"],
+            "traffic": sel_traffic,
+            "achieved_on_counted_traffic": sel_traffic / (res["select_ms"] * 1e-3) / 1e9 if sel_traffic else None,
         },
         "cpu_baseline": cpu,
         "decode": dec,
         "decode_fp8_cache": dec_fp8,
     }
+    if switches is not None:
+        out["switches"] = switches
     if mixed is not None:
         out["mixed_batch"] = mixed
     if shared is not None:

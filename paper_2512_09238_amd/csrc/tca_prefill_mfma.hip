@@ -24,18 +24,18 @@
 //   O^T accumulators: C[d = 32*s + 8*(r/4)+4*hh+r%4][query = c]: every register of
 //                  a lane belongs to the same query, so rescaling is a per-lane scalar.
 //
-// LDS holds a ring of two K tiles [64][D] and a ring of two V^T tiles [D][64] with
-// XOR-swizzled 16-byte chunks (conflict-free b128 reads without padding), filled by
-// direct global -> LDS loads.  The loop is software-pipelined by one tile (see the
-// kernel); one barrier per tile.
+// LDS holds a ring of K tiles [64][D] and a ring of V^T tiles [D][64] (two tiles each; three
+// in the two-blocks-per-wave shape) with XOR-swizzled 16-byte chunks (conflict-free b128
+// reads without padding), filled by direct global -> LDS loads.  The loop is
+// software-pipelined by one tile (see the kernel); one barrier per tile.
 //
-// Softmax bookkeeping.  The reference m of a query's exponentials is lazy: it is not
-// the running maximum but any earlier maximum of visible scores, raised only when a
-// tile's terms would come near the top of the fp32 range (row sum of the tile >=
-// kRaise).  Terms, sum and accumulators share the reference, so the quotient is the
-// same; the common tile then needs no maximum at all.  The sum l is formed from the
-// bf16-rounded terms, the very numbers that enter O^T = V^T P^T, so numerator and
-// denominator carry the same rounding.
+// Softmax bookkeeping.  One block per wave (the shapes the library launches by itself): the
+// reference m of a query's exponentials is the running maximum of its visible scores; the
+// state is rescaled, before a tile's exponentials, only when some query's maximum moved.
+// Two blocks per wave (a diagnostic shape): the reference is lazy - any earlier maximum of
+// visible scores, raised only when a tile's terms would come near the top of the fp32 range
+// (row sum of the tile >= kRaise); terms, sum and accumulators share the reference, so the
+// quotient is the same, and the common tile needs no maximum at all.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -46,11 +46,11 @@ namespace tca {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kBN = 64;              // keys per tile
 constexpr int kFragAhead = 4;        // LDS fragment reads in flight ahead of the MFMA that uses them
 constexpr float kRaise = 0x1p60f;    // a tile whose terms sum to this much raises the softmax reference
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 struct PrefillHeads {
   int64_t offs[TCA_MAX_HEADS + 1];      // row offsets of the heads' regions
@@ -276,10 +276,10 @@ void prefill_mfma_kernel(
   constexpr int VBYTES = D * kBN * 2;    // V^T tile
   // Rows are not padded; the 16-byte chunk index is XOR-swizzled with the row so that
   // the b128 reads of 16 consecutive rows at one chunk column fall into distinct banks.
-  // Tiles in flight: a workgroup that has its CU to itself keeps rings of three K and three V^T
-  // tiles (96 KB for d = 128), so that a copy has a whole iteration and more to arrive; where two
-  // workgroups share a CU the rings hold two.
-  constexpr int RING = (NW * QB >= 8) ? 3 : 2;
+  // Tiles in flight: rings of two K and two V^T tiles, a copy has one iteration to arrive (with two
+  // waves per SIMD a third tile measured no faster); the one-wave-per-SIMD shape, where nothing else
+  // covers a late copy, keeps three.
+  constexpr int RING = QB == 2 ? 3 : 2;
   __shared__ __attribute__((aligned(16))) unsigned char lds[RING * (KBYTES + VBYTES)];
   unsigned char* const kring = lds;
   unsigned char* const vring = lds + RING * KBYTES;
@@ -499,9 +499,15 @@ void prefill_mfma_kernel(
   };
 
   // exponentials of the scores s against the reference mb (already in base-2 units): bf16 terms in
-  // operand order, and the sum of those rounded terms over the lane's 32 keys
+  // operand order, and their sum over the lane's 32 keys.  With the running maximum as reference
+  // (QB = 1) the largest term of a query is exactly 1, which bf16 holds exactly, and the sum takes
+  // the fp32 terms; summing the bf16-rounded ones instead (one v_dot2_f32_bf16 per pair), so that
+  // numerator and denominator carry the same rounding, was measured: 1.2 % slower, and 8.3e-3
+  // instead of 9.7e-3 worst error on logits in the hundreds, both far inside the 2e-2 the outputs
+  // are held to.  With the lazy reference (QB = 2) the largest term is an arbitrary number whose
+  // rounding (2^-9 relative) goes straight into the output of a query that attends to one key:
+  // there the sum must take the rounded terms, so that the quotient cancels that rounding.
   auto exp_tile = [&](const f32x16_t (&s)[2], float mb, bf16x8_t (&pf)[2][2]) {
-    const bf16x2_t ones = {(__bf16)1.f, (__bf16)1.f};
     float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
@@ -509,11 +515,10 @@ void prefill_mfma_kernel(
       for (int g = 0; g < 2; ++g) {
         bf16x8_t pk;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pk[e] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[sub][8 * g + e], sl2e, -mb));
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {                // sums the rounded terms: what the P V product sees
-          const bf16x2_t pr = {pk[2 * e2], pk[2 * e2 + 1]};
-          ls[e2] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, ls[e2], false);
+        for (int e = 0; e < 8; ++e) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[sub][8 * g + e], sl2e, -mb));
+          pk[e] = (__bf16)p;
+          ls[e & 3] += QB == 2 ? (float)pk[e] : p;
         }
         pf[sub][g] = pk;
       }
@@ -531,7 +536,7 @@ void prefill_mfma_kernel(
     const bf16x2_t ones = {(__bf16)1.f, (__bf16)1.f};
     if (i >= 1) {
 #pragma unroll
-      for (int k = 0; k < EPC; k += 2) {
+      for (int k = 0; k < EPC; k += 2) {                 // the sum takes the rounded terms (see exp_tile)
         const int n = (i - 1) * EPC + k;                 // even element of a pair
         const bf16x2_t pr = {(__bf16)pend[k], (__bf16)pend[k + 1]};
         pf[n >> 4][(n >> 3) & 1][n & 7] = pr[0];
@@ -548,6 +553,12 @@ void prefill_mfma_kernel(
     }
   };
 
+  // Does every query of the wave see every key of tile t?  (wave-uniform)
+  auto mask_tile_is_clear = [&](int t) {
+    const bool is_glob = t < n_gt;
+    const int key0 = (t + (is_glob ? 0 : dshift)) * kBN;
+    return t <= last && (is_glob ? (key0 + kBN <= nv_wave_lo) : (key0 + kBN - 1 <= wave_first && key0 > wave_last - w));
+  };
   // Mask of tile t on the scores s of block blk (boundary tiles only; a tile this wave sees nothing
   // of, or past the last one, is fully masked).  Returns whether this lane's query sees any key of it.
   auto mask_tile = [&](int t, int blk, f32x16_t (&s)[2]) {
@@ -604,6 +615,7 @@ void prefill_mfma_kernel(
   bf16x8_t pf[QB][2][2];                 // P of block 0: formed and used inside a step; of block 1: formed one step ahead
 
   int rpos = 0;                          // it % RING of the step about to run
+  float mx_pre = -INFINITY;              // QB = 1: unmasked maximum of the scores the next step starts from
   TileRows rows_ahead = {};              // GATHER: row positions of tile it + RING, read during step it - 1
   static_assert((RING - 2) * Copy::N < 16, "the wait below encodes its count in four bits");
 
@@ -616,14 +628,18 @@ void prefill_mfma_kernel(
     __builtin_amdgcn_s_waitcnt(0x0F70 | ((RING - 2) * Copy::N));     // vmcnt((RING - 2) * N)
     __syncthreads();
     const int tk = it + RING < last ? it + RING : last, tv = it + RING - 1 < last ? it + RING - 1 : last;   // past the end: a harmless reload
-    const int r_next = rpos + 1 == RING ? 0 : rpos + 1, r_prev = rpos == 0 ? RING - 1 : rpos - 1;   // (it +- 1) % RING
-    const CopyJob job = copy_job(tk, tv, kring + rpos * KBYTES, vring + r_prev * VBYTES, rows_ahead);
+    // ring places (it - 1, it, it + 1) % RING; with two places they follow from the parity of `it`, which the
+    // twice-unrolled loop makes a constant of each copy of the step (LDS offsets fold into the instructions)
+    const int r_cur = RING == 2 ? (it & 1) : rpos;
+    const int r_next = RING == 2 ? ((it + 1) & 1) : (rpos + 1 == RING ? 0 : rpos + 1);
+    const int r_prev = RING == 2 ? r_next : (rpos == 0 ? RING - 1 : rpos - 1);
+    const CopyJob job = copy_job(tk, tv, kring + r_cur * KBYTES, vring + r_prev * VBYTES, rows_ahead);
     // GATHER: the positions for the copies of the next step are requested before this step's copies,
     // so that the wait at the top of the next step, which lets only the newest copies pass, covers them
     if constexpr (GATHER) rows_ahead = load_tile_rows(it + 1 + RING < last ? it + 1 + RING : last);
     const unsigned char* kb = kring + r_next * KBYTES;
-    const unsigned char* vb = vring + rpos * VBYTES;
-    rpos = r_next;
+    const unsigned char* vb = vring + r_cur * VBYTES;
+    if constexpr (RING != 2) rpos = r_next;
 
     // ---- slot A: scores of the next tile (MFMA) under the exponentials of this one (VALU), taken
     // against the reference as it stands
@@ -631,25 +647,47 @@ void prefill_mfma_kernel(
       const int kk = i >> 1;
       if ((i & 1) && (kk * Copy::N) % KK == 0 && kk * Copy::N / KK < Copy::N) copy_load(job, kk * Copy::N / KK);
     };
-    {
+    auto vfrag = [&](int j) {
+      return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
+    };
+    bf16x8_t vfr[kFragAhead];
+    if constexpr (QB == 1) {
+      // One block per wave, two waves per SIMD: the reference is the running maximum of the visible
+      // scores.  The maximum of this tile was taken under the previous step's P V MFMAs (again after
+      // masking on a boundary tile); the state is rescaled, before the exponentials, only when some
+      // query's maximum moved.  Everything from here to the end of the step is one basic block, so
+      // that the first P V MFMAs can start while the later exponentials are still being formed.
+      const bool masked = !mask_tile_is_clear(it);
+      float mx = mx_pre;
+      if (masked) {
+        mask_tile(it, 0, sc[0]);
+        mx = lane_max(sc[0]);
+      }
+      const float m_new = fmaxf(m[0], mx);
+      if (__any(m_new > m[0])) {
+        const float alpha = (m_new > m[0]) ? __builtin_amdgcn_exp2f((m[0] - m_new) * sl2e) : 1.f;   // 0 when m was -inf
+        l[0] *= alpha;
+#pragma unroll
+        for (int sl = 0; sl < DS; ++sl)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[0][sl][r] *= alpha;
+        m[0] = m_new;
+      }
+      s_tile(kb, sn, issue_copies);
+      l[0] += exp_tile(sc[0], (m_new == -INFINITY) ? 0.f : m_new * sl2e, pf[0]);
+    } else {
       const bool sees = mask_tile(it, 0, sc[0]);
       const bool cold = m[0] == -INFINITY;          // no reference yet: no key seen so far
       const float mb = cold ? 0.f : m[0] * sl2e;
-      float lt;
-      if constexpr (QB == 1) {
-        s_tile(kb, sn, issue_copies);
-        lt = exp_tile(sc[0], mb, pf[0]);
-      } else {
-        float ls[4] = {0.f, 0.f, 0.f, 0.f}, pend[EPC];
+      float ls[4] = {0.f, 0.f, 0.f, 0.f}, pend[EPC];
+      __builtin_amdgcn_sched_barrier(0);
+      s_tile(kb, sn, [&](int i) {
+        issue_copies(i);
+        exp_piece(i, sc[0], mb, pf[0], ls, pend);
         __builtin_amdgcn_sched_barrier(0);
-        s_tile(kb, sn, [&](int i) {
-          issue_copies(i);
-          exp_piece(i, sc[0], mb, pf[0], ls, pend);
-          __builtin_amdgcn_sched_barrier(0);
-        });
-        exp_piece(NCH, sc[0], mb, pf[0], ls, pend);
-        lt = (ls[0] + ls[1]) + (ls[2] + ls[3]);
-      }
+      });
+      exp_piece(NCH, sc[0], mb, pf[0], ls, pend);
+      float lt = (ls[0] + ls[1]) + (ls[2] + ls[3]);
       softmax_fixup(0, sc[0], cold, sees, lt, pf[0]);
       l[0] += lt;
     }
@@ -665,10 +703,6 @@ void prefill_mfma_kernel(
       mb1 = cold1 ? 0.f : m[1] * sl2e;
       __builtin_amdgcn_sched_barrier(0);
     }
-    auto vfrag = [&](int j) {
-      return *reinterpret_cast<const bf16x8_t*>(vb + vfa[j / DS] + (j % DS) * (32 * kBN * 2));
-    };
-    bf16x8_t vfr[kFragAhead];
 #pragma unroll
     for (int j = 0; j < kFragAhead; ++j) vfr[j] = vfrag(j);
 #pragma unroll
@@ -682,6 +716,7 @@ void prefill_mfma_kernel(
         __builtin_amdgcn_sched_barrier(0);
       }
     }
+    if constexpr (QB == 1) mx_pre = lane_max(sn[0]);    // vector ALU work for the shadow of the MFMAs above
     if constexpr (QB == 2) {
       exp_piece(NCH, sn[1], mb1, pn, ls1, pend1);
       float lt = (ls1[0] + ls1[1]) + (ls1[2] + ls1[3]);
@@ -716,6 +751,7 @@ void prefill_mfma_kernel(
     __builtin_amdgcn_s_waitcnt(0x0F70 | (Copy::NK + (RING - 2) * Copy::N + (GATHER ? Copy::NK : 0)));
     __syncthreads();
     s_tile(kring, sa, [&](int) {});
+    if constexpr (QB == 1) mx_pre = lane_max(sa[0]);
     if constexpr (QB == 2) {            // block 1 runs half a step ahead with its exponentials
       const bool sees = mask_tile(0, 1, sa[1]);
       float lt = exp_tile(sa[1], 0.f, pf[1]);
