@@ -717,6 +717,31 @@ void prefill_mfma_kernel(
       }
     }
     if constexpr (QB == 1) mx_pre = lane_max(sn[0]);    // vector ALU work for the shadow of the MFMAs above
+    if constexpr (QB == 1) {
+      // The order of the step's instructions, spelled out for the scheduler (the step is one scheduling
+      // region): behind every MFMA one fragment read and an even share of the plain vector ALU work, the
+      // exponentials left to fall where they may, which is two per MFMA of the S half.  Left to itself the
+      // scheduler starts the step with eight bare MFMAs and crowds the exponentials into the middle;
+      // measured 1.3 - 2 % faster than that.  Pinning the exponentials or the scalar instructions as well
+      // measured 8 % slower.
+      constexpr int kMfma = 0x008, kValu = 0x002, kDsRead = 0x100, kVmemRead = 0x020;
+      constexpr int VA = 512 / D, VB = 640 / D;        // plain vector ALU instructions behind an MFMA of S, of P V
+      __builtin_amdgcn_sched_group_barrier(kDsRead, kFragAhead, 0);
+#pragma unroll
+      for (int i = 0; i < 2 * KK; ++i) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+        if ((i & 1) && ((i >> 1) * Copy::N) % KK == 0 && (i >> 1) * Copy::N / KK < Copy::N)
+          __builtin_amdgcn_sched_group_barrier(kVmemRead, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kValu, VA, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < 4 * DS; ++j) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        if (j + kFragAhead < 4 * DS) __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kValu, VB, 0);
+      }
+    }
     if constexpr (QB == 2) {
       exp_piece(NCH, sn[1], mb1, pn, ls1, pend1);
       float lt = (ls1[0] + ls1[1]) + (ls1[2] + ls1[3]);

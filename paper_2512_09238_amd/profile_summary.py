@@ -7,6 +7,8 @@
       counter reading into bytes; the file records HBM bytes per launch of every libtca kernel.
   python -m paper_2512_09238_amd.profile_summary stats STATS_CSV
       prints the libtca rows of a `rocprofv3 --kernel-trace --stats` kernel_stats.csv as a table.
+  python -m paper_2512_09238_amd.profile_summary counters PMC_DIR
+      prints the mean per dispatch of every counter of a `rocprofv3 --pmc ...` run, per libtca kernel.
 
 bench.py reads the traffic file and reports its figures only while `source_sha` still equals the
 hash of the kernel sources (source_sha() below): a changed kernel invalidates the measurement.
@@ -123,6 +125,25 @@ def cmd_stats(args):
               f"{float(r['MaxNs']) / 1e3:.1f} | {float(r['TotalDurationNs']) / 1e6:.2f} |")
 
 
+def cmd_counters(args):
+    files = glob.glob(os.path.join(args.pmc_dir, "**", "*counter_collection.csv"), recursive=True)
+    if not files:
+        raise SystemExit(f"no counter_collection.csv under {args.pmc_dir}")
+    acc, names = collections.defaultdict(lambda: collections.defaultdict(list)), []
+    for f in files:
+        for r in csv.DictReader(open(f)):
+            if "tca::" not in r["Kernel_Name"]:
+                continue
+            if r["Counter_Name"] not in names:
+                names.append(r["Counter_Name"])
+            acc[r["Kernel_Name"].split("(")[0].replace("void ", "")][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    print("| kernel | dispatches | " + " | ".join(names) + " |")
+    print("|---|---:|" + "---:|" * len(names))
+    for k, c in sorted(acc.items(), key=lambda kv: -sum(kv[1].get(names[0], [0.0]))):
+        n = max(len(v) for v in c.values())
+        print(f"| `{k}` | {n} | " + " | ".join(f"{sum(c[x]) / len(c[x]):.4g}" if c.get(x) else "-" for x in names) + " |")
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -134,6 +155,9 @@ def main():
     s = sub.add_parser("stats")
     s.add_argument("stats_csv")
     s.set_defaults(fn=cmd_stats)
+    c = sub.add_parser("counters")
+    c.add_argument("pmc_dir")
+    c.set_defaults(fn=cmd_counters)
     args = ap.parse_args()
     args.fn(args)
 
