@@ -60,11 +60,12 @@ def read_counter(folder: str, counter: str):
 
 
 def copy_factor(values: dict, what: str) -> float:
-    """Bytes per counter unit from the 1 GiB copy of --copy-probe: the copy kernel is the one non-libtca
-    dispatch with the largest reading."""
-    best = max((max(v), k) for k, v in values.items() if "tca::" not in k)
-    if best[0] <= 0:
-        raise SystemExit(f"no copy kernel found for {what}")
+    """Bytes per counter unit from the 1 GiB copy of --copy-probe: the largest dispatch of the runtime's
+    buffer-copy kernel (the other dispatches of that kernel are the small copies of the set-up)."""
+    cands = [(max(v), k) for k, v in values.items() if "copyBuffer" in k]
+    if not cands or max(cands)[0] <= 0:
+        raise SystemExit(f"no buffer-copy kernel found for {what}: was bench.py run with --copy-probe?")
+    best = max(cands)
     return GIB_IN_KIB * 1024.0 / best[0], best[1]
 
 
