@@ -1,0 +1,83 @@
+"""Diagnostics of the bf16 prefill kernel (not part of the hot path; uses include/tca_diag.h).
+
+  python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2]
+
+`occupancy`: the attention kernel on the last 2048 queries of a 131072-token sequence (config 3's
+recipe, budget 57 % for every head) with 32, 16 and 8 query heads: 256, 128 and 64 workgroups of the
+same work each, i.e. the whole chip, half and a quarter of it.  Prints per call the event-timed
+duration, the mean workgroup duration and the shader clock, both from the kernel's own counters
+(cycle counter and 100 MHz counter, tca_diag_prefill_clocks), and the cycles per workgroup.  Equal
+cycles at different clocks separate what the code costs from what the power limit costs.
+--variants names the workgroup shapes to run (tca_diag_prefill_variant: 1 = 4 waves x 32 queries,
+2 = 4 x 64, 3 = 8 x 32, the shape of long calls and the default here).
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def occupancy(args):
+    import torch
+    import workloads as wl
+    from paper_2512_09238_amd import binding as tb, buffers as bufs
+    L, d, b, w, n = 131072, 128, 128, 4096, 2048
+    tb.tca_diag_prefill_clocks(True)
+    try:
+        for Hq in args.heads:
+            Hkv = max(1, Hq // 4)
+            x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+            prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, 0.5, 0.0, tb.TCA_METRIC_HHI, tb.TCA_SHARE_HEAD)
+            P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.57) for _ in range(Hq)])
+            Qd, Kd, Vd = bufs.to_device(x["Q"]), bufs.to_device(x["K"]), bufs.to_device(x["V"])
+            _, rows = tb.tca_select_rows(prm, L // b, P)
+            gb = bufs.GlobalBuffers(prm, rows)
+            ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+            tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+            ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, n, int(gb.offs[-1])))
+            Qc = Qd[:, L - n:].contiguous()
+            O = torch.empty_like(Qc)
+            for variant in args.variants:
+                tb.tca_diag_prefill_variant(variant)
+                per_wg_queries = 128 if variant == 1 else 256
+                nwg = Hq * (n // per_wg_queries)
+                res = []
+                for _ in range(args.repeats + 1):
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    tb.tca_prefill(prm, Qc, L - n, n, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    c = ws[:16].view(torch.int64).cpu().numpy()
+                    res.append((e0.elapsed_time(e1), c[1] / nwg / 100.0, c[0] / (c[1] * 10.0), c[0] / nwg / 1e6))
+                t, u, g, cyc = (float(np.mean([r[i] for r in res[1:]])) for i in range(4))
+                print(f"heads {Hq:3d}  shape {variant}  workgroups {nwg:4d}:  call {t:.3f} ms   workgroup {u:7.1f} us   "
+                      f"clock {g:.2f} GHz   {cyc:.2f} M cycles per workgroup", flush=True)
+            tb.tca_diag_prefill_variant(0)
+            del gb, ws, ws_sel, Qd, Kd, Vd, Qc, O
+            torch.cuda.empty_cache()
+    finally:
+        tb.tca_diag_prefill_variant(0)
+        tb.tca_diag_prefill_clocks(False)
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    o = sub.add_parser("occupancy")
+    o.add_argument("--heads", type=int, nargs="+", default=[32, 16, 8])
+    o.add_argument("--variants", type=int, nargs="+", default=[3], choices=[1, 2, 3])
+    o.add_argument("--repeats", type=int, default=3)
+    o.set_defaults(fn=occupancy)
+    args = ap.parse_args()
+    args.fn(args)
+
+
+if __name__ == "__main__":
+    main()
