@@ -98,13 +98,14 @@ def test_calibration_full_length_two_heads(tb, bufs):
             assert got["cand_idx"][h] == ref[h].index and bool(got["fallback"][h]) == ref[h].fallback
 
 
-def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
+def _decode_full_size(tb, bufs, fp8):
     """Config 4: batch 16 at 128K context, all 64 steps queued back to back.  Cache contents are
-    drawn on the device with a seeded torch generator; for sampled (sequence, head) pairs the host
-    keeps what the query can see (global rows, window, appended rows) and replays the steps with
-    the oracle's routines: outputs at the first step, at every step that completes a block of the
-    pair's sequence, at the step after it and at the last step; the global subsets (positions and
-    K rows) after the 64 steps bit for bit, which covers every block completed on the way."""
+    drawn on the device with a seeded torch generator (fp8: codes and scales drawn directly, as
+    bench.py does); for sampled (sequence, head) pairs the host keeps what the query can see
+    (global rows, window, appended rows) and replays the steps with the oracle's routines: outputs
+    at the first step, at every step that completes a block of the pair's sequence, at the step
+    after it and at the last step; the global subsets (positions and rows as stored) after the 64
+    steps bit for bit, which covers every block completed on the way."""
     c = wl.CONFIGS[4]
     Hq, Hkv, d, T0, b, w, B, steps = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"], c["batch"], c["steps"]
     G = Hq // Hkv
@@ -114,7 +115,7 @@ def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
     P_orc = np.stack([orc.config_from_budget(b, c["sigma"], f) for f in fr])
     n_glob = np.round(fr * (T0 - w)).astype(np.int64)
     t_dec = np.array([tb.tca_decode_budget(b, p) for p in P_gpu])
-    cache = bufs.DecodeCache(prm, B, n_glob + 2 * t_dec)
+    cache = bufs.DecodeCache(prm, B, n_glob + 2 * t_dec, kv_format=tb.TCA_KV_FP8 if fp8 else tb.TCA_KV_NATIVE)
     g = torch.Generator(device="cuda").manual_seed(wl.data_seed(4))
     rng = np.random.default_rng(wl.data_seed(4))
     pend = rng.integers(0, b, size=B)
@@ -124,16 +125,33 @@ def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
     lengths = T0 + pend
     done_at = {s: int(b - 1 - pend[s]) for s in range(B) if b - 1 - pend[s] < steps}
     print("blocks complete at steps", done_at, flush=True)
+
+    def fill(rows, scales):
+        if not fp8:
+            rows.copy_(torch.randn(rows.shape, generator=g, device="cuda", dtype=torch.float32))
+            return
+        codes = torch.randint(0, 256, rows.shape, generator=g, device="cuda", dtype=torch.uint8)
+        codes[(codes & 0x7F) == 0x7F] = 0              # the two NaN codes
+        rows.copy_(codes)
+        scales.copy_(torch.rand(scales.shape, generator=g, device="cuda") * 0.015 + 0.005)
+
+    def stored(name, *ix):
+        """What the cache holds at an index, as the oracle's routines read it: float64 rows."""
+        t = getattr(cache, name)[ix]
+        if not fp8:
+            return t.double().cpu().numpy()
+        return orc.dequantize_rows_fp8(t.cpu().numpy(), getattr(cache, name + "_scale")[ix].cpu().numpy())
+
     for s in range(B):
-        cache.Kg[s].copy_(torch.randn(cache.Kg[s].shape, generator=g, device="cuda", dtype=torch.float32))
-        cache.Vg[s].copy_(torch.randn(cache.Vg[s].shape, generator=g, device="cuda", dtype=torch.float32))
+        fill(cache.Kg[s], cache.Kg_scale[s] if fp8 else None)
+        fill(cache.Vg[s], cache.Vg_scale[s] if fp8 else None)
         for h in range(Hq):
             o = int(cache.offs[h])
             pos = np.sort(rng.choice(T0 - w, size=int(n_glob[h]), replace=False)).astype(np.int32)
             cache.idx[s, o:o + len(pos)] = torch.from_numpy(pos).cuda()
     cache.n_rows.copy_(torch.from_numpy(np.tile(n_glob.astype(np.int32), (B, 1))))
-    cache.ringK.copy_(torch.randn(cache.ringK.shape, generator=g, device="cuda", dtype=torch.float32))
-    cache.ringV.copy_(torch.randn(cache.ringV.shape, generator=g, device="cuda", dtype=torch.float32))
+    fill(cache.ringK, cache.ringK_scale)
+    fill(cache.ringV, cache.ringV_scale)
     cache.length.copy_(torch.from_numpy(lengths.astype(np.int64)))
     q = torch.randn(steps, B, Hq, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     kn = torch.randn(steps, B, Hkv, d, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
@@ -147,8 +165,8 @@ def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
         o, n = int(cache.offs[h]), int(n_glob[h])
         kvh = h // G
         before[(s, h)] = dict(idx=cache.idx[s, o:o + n].cpu().numpy().astype(np.int64),
-                              Kg=cache.Kg[s, o:o + n].double().cpu().numpy(), Vg=cache.Vg[s, o:o + n].double().cpu().numpy(),
-                              ringK=cache.ringK[s, kvh].double().cpu().numpy(), ringV=cache.ringV[s, kvh].double().cpu().numpy())
+                              Kg=stored("Kg", s, slice(o, o + n)), Vg=stored("Vg", s, slice(o, o + n)),
+                              ringK=stored("ringK", s, kvh), ringV=stored("ringV", s, kvh))
     for st in range(steps):                            # no host sync between the steps
         tb.tca_decode(prm, cache.view, cache.offs, q[st], kn[st], vn[st], P_gpu, O[st], ws)
     torch.cuda.synchronize()
@@ -156,6 +174,8 @@ def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
     assert not torch.isnan(O.float()).any()
     assert cache.length.cpu().tolist() == (lengths + steps).tolist()
     qh, knh, vnh, Oh = q.double().cpu().numpy(), kn.double().cpu().numpy(), vn.double().cpu().numpy(), O.double().cpu().numpy()
+    if fp8:                                            # a new row enters the cache as codes and a scale
+        knh, vnh = orc.roundtrip_rows_fp8(knh), orc.roundtrip_rows_fp8(vnh)
     worst, n_checked, n_completed = 0.0, 0, 0
     for (s, h) in pairs:
         kvh = h // G
@@ -186,11 +206,27 @@ def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
         assert n_now == len(S), (s, h)
         assert np.array_equal(cache.idx[s, o:o + n_now].cpu().numpy(), S), (s, h)
         new_rows = S[len(bf["idx"]):]
-        assert np.array_equal(cache.Kg[s, o + len(bf["idx"]):o + n_now].double().cpu().numpy(), Kfull[new_rows]), (s, h)
-        assert np.array_equal(cache.Vg[s, o + len(bf["idx"]):o + n_now].double().cpu().numpy(), Vfull[new_rows]), (s, h)
+        new_at = slice(o + len(bf["idx"]), o + n_now)
+        assert np.array_equal(stored("Kg", s, new_at), Kfull[new_rows]), (s, h)
+        assert np.array_equal(stored("Vg", s, new_at), Vfull[new_rows]), (s, h)
+        if fp8 and len(new_rows):
+            # kept rows are copied as stored: the codes and scales of the ring's rows, not a second quantisation
+            slots = new_rows % w
+            for name, ring in (("Kg", "ringK"), ("Vg", "ringV")):
+                assert torch.equal(getattr(cache, name)[s, new_at], getattr(cache, ring)[s, kvh][slots]), (name, s, h)
+                assert torch.equal(getattr(cache, name + "_scale")[s, new_at], getattr(cache, ring + "_scale")[s, kvh][slots]), (name, s, h)
     assert n_completed >= 5
     print("max abs err on", n_checked, "sampled (step, sequence, head) outputs:", worst, "; blocks completed:", n_completed, flush=True)
     assert worst <= H.TOL["bf16"]
+
+
+def test_decode_full_size_all_steps_sampled_heads(tb, bufs):
+    _decode_full_size(tb, bufs, fp8=False)
+
+
+def test_decode_full_size_fp8_cache_all_steps_sampled_heads(tb, bufs):
+    """The same with the FP8 cache (TCA_KV_FP8), the workload of bench.py's decode_fp8_cache line."""
+    _decode_full_size(tb, bufs, fp8=True)
 
 
 def test_config5_ragged_mixed_batch_sampled(tb, bufs):
