@@ -356,6 +356,50 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     print("max abs err on", len(pos) * len(heads), "rows:", worst, flush=True)
     assert worst <= H.TOL["bf16"]
 
+    # the two switches at the same size (bench.py --switches).  Gather-free: positions only from
+    # tca_select, rows read through idx by tca_prefill; the same numbers reach the same arithmetic,
+    # so the output equals the plain one bit for bit.
+    n2, idx2 = torch.zeros_like(gb.n_rows), torch.full_like(gb.idx, -1)
+    ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    q_last = Qd[:, L - 1].contiguous()
+    tb.tca_select(prm, q_last, Kd, Vd, L, 0, L, cal["p_star"], gb.offs, n2, idx2, None, None, ws_sel)
+    O2 = torch.full_like(O, float("nan"))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, idx2, None, None, gb.offs, n2, O2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(n2, gb.n_rows)
+    for h in range(Hq):
+        o, n = int(gb.offs[h]), int(gb.n_rows[h].item())
+        assert torch.equal(idx2[o:o + n], gb.idx[o:o + n]), f"gather-free positions, head {h}"
+    assert torch.equal(O2, O), "gather-free output"
+    print("gather-free equals the plain path", flush=True)
+    del idx2
+    # Overlapped: window part on a side stream while the selection runs, merged through the
+    # log-sum-exp; two more roundings to bf16 than the one-pass kernel, so compared with the oracle
+    # on the sampled rows, and the positions with the plain call's.
+    n3 = torch.zeros_like(gb.n_rows)
+    gb.idx.fill_(-1)
+    O2.fill_(float("nan"))
+    O_part = torch.empty_like(O)
+    lse_parts = torch.empty(2, Hq, L, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    tb.tca_select_prefill_overlapped(prm, q_last, Qd, Kd, Vd, L, 0, L, cal["p_star"], gb.offs, n3, gb.idx, gb.Kg, gb.Vg,
+                                     O2, O_part, lse_parts, ws_sel, ws, side.cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(n3, n2) and not torch.isnan(O2.float()).any()
+    Og = O2[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
+    worst_o = 0.0
+    for h in heads:
+        Kf, Vf = wl.to_f64(x["K"][h // G]), wl.to_f64(x["V"][h // G])
+        o, n = int(gb.offs[h]), int(n3[h].item())
+        got = gb.idx[o:o + n].cpu().numpy().astype(np.int64)
+        qh = wl.to_f64(x["Q"][h][pos])
+        for k, i in enumerate(pos):
+            ref = orc.attention_row(qh[k], int(i), Kf, Vf, got, w)
+            worst_o = max(worst_o, float(np.abs(ref - Og[h, k]).max()))
+    print("overlapped: max abs err on the same rows:", worst_o, "; against the plain output:",
+          float((O2.float() - O.float()).abs().max().item()), flush=True)
+    assert worst_o <= H.TOL["bf16"]
+
 
 def test_longest_single_call_4096_blocks_512k_tokens(tb, bufs):
     """The most one tca_select call ranks (4096 blocks of 128 = 524288 tokens), with prefill over
