@@ -498,6 +498,51 @@ def test_decode_step_replayed_from_a_hip_graph(tb, bufs):
     assert torch.equal(cache2.n_rows, n_eager) and torch.equal(cache2.idx, idx_eager)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_select_and_prefill_replayed_from_a_hip_graph(tb, bufs, dtype):
+    """tca_select and tca_prefill only launch kernels on the given stream, so the pair can be captured
+    into a HIP graph (with a fill kernel in front that empties the global region) and replayed on
+    new inputs.  Three replays on three different sequences, eager copies and synchronisations in
+    between, each compared bit for bit with the eager calls on the same inputs."""
+    Hq, Hkv, d, L, b, w = 8, 2, 128, 2048 + 77, 128, 512
+    fr = wl.budget_fractions(91, Hq)
+    P_gpu, _ = budgets_to_configs(tb, b, fr)
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
+    xs = [wl.prefill_inputs("lowrank", Hq, Hkv, d, L, dtype, 92 + i) for i in range(3)]
+    eager = []
+    for x in xs:
+        gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
+        O = torch.empty_like(Qd)
+        ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+        torch.cuda.synchronize()
+        eager.append((O.clone(), gb.idx.clone(), gb.n_rows.clone()))
+    Qs, Ks, Vs = (torch.empty_like(t) for t in (Qd, Kd, Vd))
+    q_last = torch.empty_like(Qd[:, 0])
+    _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
+    gbs = bufs.GlobalBuffers(prm, rows)
+    Os = torch.empty_like(Qd)
+    ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    ws_pf = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gbs.offs[-1])))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gbs.n_rows.zero_()
+        tb.tca_select(prm, q_last, Ks, Vs, L, 0, L, P_gpu, gbs.offs, gbs.n_rows, gbs.idx, gbs.Kg, gbs.Vg, ws_sel)
+        tb.tca_prefill(prm, Qs, 0, L, Ks, Vs, L, gbs.idx, gbs.Kg, gbs.Vg, gbs.offs, gbs.n_rows, Os, None, ws_pf)
+    for rep in range(2):
+        for i, x in enumerate(xs):
+            Qs.copy_(bufs.to_device(x["Q"])); Ks.copy_(bufs.to_device(x["K"])); Vs.copy_(bufs.to_device(x["V"]))
+            q_last.copy_(Qs[:, L - 1])
+            Os.fill_(float("nan"))
+            graph.replay()
+            if i != 1:
+                torch.cuda.synchronize()
+            O_e, idx_e, n_e = eager[i]
+            assert torch.equal(gbs.n_rows, n_e), (rep, i)
+            assert torch.equal(gbs.idx, idx_e), (rep, i)
+            assert torch.equal(Os, O_e), f"replay {rep}.{i} differs from the eager calls"
+
+
 CALIB_CASES = [
     # kind, Hq, Hkv, d, L, dtype, b, M, seed
     ("lowrank", 4, 2, 64, 512, "f32", 16, 6, 71),
