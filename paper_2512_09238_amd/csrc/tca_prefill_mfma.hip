@@ -889,7 +889,7 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
                        (const int32_t*)nullptr, 1);
 
   // Shape of a workgroup.  Long calls: eight waves of 32 queries (256 queries, one workgroup per CU,
-  // two waves per SIMD, rings of three tiles).  Calls with few query tiles: four waves of 32 queries
+  // two waves per SIMD).  Calls with few query tiles: four waves of 32 queries
   // (128 queries, two workgroups per CU), which keeps more of the chip busy.  Four waves of 64
   // queries (one wave per SIMD, every LDS fragment feeds two MFMAs, half the LDS reads) stay
   // selectable through the diagnostics switch: measured 5-8 % slower on 128K tokens, because a

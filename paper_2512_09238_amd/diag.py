@@ -1,6 +1,6 @@
 """Diagnostics of the bf16 prefill kernel (not part of the hot path; uses include/tca_diag.h).
 
-  python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2]
+  python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2] [--queries 2048]
 
 `occupancy`: the attention kernel on the last 2048 queries of a 131072-token sequence (config 3's
 recipe, budget 57 % for every head) with 32, 16 and 8 query heads: 256, 128 and 64 workgroups of the
@@ -26,7 +26,7 @@ def occupancy(args):
     import torch
     import workloads as wl
     from paper_2512_09238_amd import binding as tb, buffers as bufs
-    L, d, b, w, n = 131072, 128, 128, 4096, 2048
+    L, d, b, w, n = 131072, 128, 128, 4096, args.queries
     tb.tca_diag_prefill_clocks(True)
     try:
         for Hq in args.heads:
@@ -74,6 +74,7 @@ def main():
     o.add_argument("--heads", type=int, nargs="+", default=[32, 16, 8])
     o.add_argument("--variants", type=int, nargs="+", default=[3], choices=[1, 2, 3])
     o.add_argument("--repeats", type=int, default=3)
+    o.add_argument("--queries", type=int, default=2048, help="queries of the call: the last so many of the sequence")
     o.set_defaults(fn=occupancy)
     args = ap.parse_args()
     args.fn(args)
