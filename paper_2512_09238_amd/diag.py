@@ -2,6 +2,15 @@
 
   python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2] [--queries 2048]
 
+  python -m paper_2512_09238_amd.diag loop {prefill,probe-random,probe-constant} [--seconds 10]
+
+`loop`: keeps the GPU on one kind of work for some seconds, so that the board's energy counter can be
+read meanwhile from another shell (`rocm-smi --showenergycounter` every few hundred milliseconds;
+power = energy difference over time difference): `prefill` repeats config 3's tca_select + tca_prefill
+(131072 tokens, budget 57 % for every head), the probes repeat tca_probe_mfma with operands of
+random sign and magnitude, or constant.  Prints the start and end times of the loop, the mean step
+time or rate, and the shader clock.
+
 `occupancy`: the attention kernel on the last 2048 queries of a 131072-token sequence (config 3's
 recipe, budget 57 % for every head) with 32, 16 and 8 query heads: 256, 128 and 64 workgroups of the
 same work each, i.e. the whole chip, half and a quarter of it.  Prints per call the event-timed
@@ -67,6 +76,51 @@ def occupancy(args):
         tb.tca_diag_prefill_clocks(False)
 
 
+def loop(args):
+    import time
+    import torch
+    import workloads as wl
+    from paper_2512_09238_amd import binding as tb, buffers as bufs
+    if args.what == "prefill":
+        c = wl.CONFIGS[3]
+        Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
+        x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+        prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, c["alpha"], 0.0, tb.TCA_METRIC_HHI, tb.TCA_SHARE_HEAD)
+        P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.57) for _ in range(Hq)])
+        Qd, Kd, Vd = bufs.to_device(x["Q"]), bufs.to_device(x["K"]), bufs.to_device(x["V"])
+        _, rows = tb.tca_select_rows(prm, L // b, P)
+        gb = bufs.GlobalBuffers(prm, rows)
+        ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+        ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+        q_last, O = Qd[:, L - 1].contiguous(), torch.empty_like(Qd)
+        tb.tca_diag_prefill_clocks(True)
+
+        def once():
+            gb.n_rows.zero_()
+            tb.tca_select(prm, q_last, Kd, Vd, L, 0, L, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+            tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+            torch.cuda.synchronize()
+            return tb.prefill_shader_clock_ghz(ws)
+    else:
+        wsp = bufs.workspace(tb.tca_probe_workspace_bytes())
+
+        def once():
+            return tb.tca_probe_mfma(args.what == "probe-random", 20000, wsp)
+    once()
+    t0, out = time.time(), []
+    print(f"loop start {t0:.3f}", flush=True)
+    while time.time() - t0 < args.seconds:
+        out.append(once())
+    t1 = time.time()
+    if args.what == "prefill":
+        print(f"loop end {t1:.3f}: {len(out)} steps, {(t1 - t0) / len(out) * 1e3:.2f} ms per step, "
+              f"shader clock {float(np.mean(out)):.2f} GHz", flush=True)
+        tb.tca_diag_prefill_clocks(False)
+    else:
+        print(f"loop end {t1:.3f}: {len(out)} calls, {float(np.mean([o[0] for o in out])):.0f} TFLOP/s, "
+              f"shader clock {float(np.mean([o[1] for o in out])):.2f} GHz", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -76,6 +130,10 @@ def main():
     o.add_argument("--repeats", type=int, default=3)
     o.add_argument("--queries", type=int, default=2048, help="queries of the call: the last so many of the sequence")
     o.set_defaults(fn=occupancy)
+    lp = sub.add_parser("loop")
+    lp.add_argument("what", choices=["prefill", "probe-random", "probe-constant"])
+    lp.add_argument("--seconds", type=float, default=10.0)
+    lp.set_defaults(fn=loop)
     args = ap.parse_args()
     args.fn(args)
 
