@@ -2,12 +2,15 @@
 
   python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2] [--queries 2048]
 
-  python -m paper_2512_09238_amd.diag loop {prefill,probe-random,probe-constant} [--seconds 10]
+  python -m paper_2512_09238_amd.diag loop {prefill,tail,probe-random,probe-constant} [--seconds 10]
+                                           [--heads 8] [--queries 2048] [--variant 3]
 
 `loop`: keeps the GPU on one kind of work for some seconds, so that the board's energy counter can be
 read meanwhile from another shell (`rocm-smi --showenergycounter` every few hundred milliseconds;
 power = energy difference over time difference): `prefill` repeats config 3's tca_select + tca_prefill
-(131072 tokens, budget 57 % for every head), the probes repeat tca_probe_mfma with operands of
+(131072 tokens, budget 57 % for every head), `tail` the attention kernel alone on the last queries
+of that sequence with few heads (the workload of `occupancy`: part of the chip, below the power
+limit, in a chosen workgroup shape), the probes repeat tca_probe_mfma with operands of
 random sign and magnitude, or constant.  Prints the start and end times of the loop, the mean step
 time or rate, and the shader clock.
 
@@ -101,6 +104,30 @@ def loop(args):
             tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
             torch.cuda.synchronize()
             return tb.prefill_shader_clock_ghz(ws)
+    elif args.what == "tail":
+        # the last `queries` queries of the sequence with `heads` query heads: few workgroups of identical
+        # work, below the power limit, in a forced workgroup shape
+        Hq, d, L, b, w, n = args.heads, 128, 131072, 128, 4096, args.queries
+        Hkv = max(1, Hq // 4)
+        x = wl.prefill_inputs("lowrank", Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+        prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, 0.5, 0.0, tb.TCA_METRIC_HHI, tb.TCA_SHARE_HEAD)
+        P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.57) for _ in range(Hq)])
+        Qd, Kd, Vd = bufs.to_device(x["Q"]), bufs.to_device(x["K"]), bufs.to_device(x["V"])
+        _, rows = tb.tca_select_rows(prm, L // b, P)
+        gb = bufs.GlobalBuffers(prm, rows)
+        ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+        tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+        ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, n, int(gb.offs[-1])))
+        Qc = Qd[:, L - n:].contiguous()
+        O = torch.empty_like(Qc)
+        tb.tca_diag_prefill_clocks(True)
+        tb.tca_diag_prefill_variant(args.variant)
+
+        def once():
+            for _ in range(50):
+                tb.tca_prefill(prm, Qc, L - n, n, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+            torch.cuda.synchronize()
+            return tb.prefill_shader_clock_ghz(ws)
     else:
         wsp = bufs.workspace(tb.tca_probe_workspace_bytes())
 
@@ -112,10 +139,12 @@ def loop(args):
     while time.time() - t0 < args.seconds:
         out.append(once())
     t1 = time.time()
-    if args.what == "prefill":
-        print(f"loop end {t1:.3f}: {len(out)} steps, {(t1 - t0) / len(out) * 1e3:.2f} ms per step, "
+    if args.what in ("prefill", "tail"):
+        per = 50 if args.what == "tail" else 1
+        print(f"loop end {t1:.3f}: {len(out) * per} steps, {(t1 - t0) / (len(out) * per) * 1e3:.3f} ms per step, "
               f"shader clock {float(np.mean(out)):.2f} GHz", flush=True)
         tb.tca_diag_prefill_clocks(False)
+        tb.tca_diag_prefill_variant(0)
     else:
         print(f"loop end {t1:.3f}: {len(out)} calls, {float(np.mean([o[0] for o in out])):.0f} TFLOP/s, "
               f"shader clock {float(np.mean([o[1] for o in out])):.2f} GHz", flush=True)
@@ -131,8 +160,11 @@ def main():
     o.add_argument("--queries", type=int, default=2048, help="queries of the call: the last so many of the sequence")
     o.set_defaults(fn=occupancy)
     lp = sub.add_parser("loop")
-    lp.add_argument("what", choices=["prefill", "probe-random", "probe-constant"])
+    lp.add_argument("what", choices=["prefill", "tail", "probe-random", "probe-constant"])
     lp.add_argument("--seconds", type=float, default=10.0)
+    lp.add_argument("--heads", type=int, default=8, help="tail: query heads (8 = a quarter of the chip)")
+    lp.add_argument("--queries", type=int, default=2048, help="tail: queries of the call")
+    lp.add_argument("--variant", type=int, default=3, choices=[1, 2, 3], help="tail: workgroup shape")
     lp.set_defaults(fn=loop)
     args = ap.parse_args()
     args.fn(args)
