@@ -1,7 +1,9 @@
 """Seeded sweep over small random shapes: selection sets, prefill outputs and a few decode
 steps of the GPU path against the oracle, every row.  Shapes cover both head dims, every
 group size 1..8, blocks 2..256, windows of 1..8 blocks, ragged lengths, both storage types.
-A second sweep runs other shapes with one selection per KV head (tca_params.share)."""
+A second sweep runs other shapes with one selection per KV head (tca_params.share).  Every case
+also runs the gather-free prefill, the window and global parts merged through the log-sum-exp,
+and, for bf16, the decode steps on an FP8 cache."""
 import numpy as np
 import pytest
 import torch
@@ -89,6 +91,30 @@ def run_case(mods, case, seed, share):
     assert not np.isnan(Og).any()
     err = np.abs(Og - Oref).max()
     assert err <= H.TOL[dtype], f"prefill max abs err {err}"
+
+    # the switches on the same shape.  Gather-free: the kept rows read through idx, bit for bit the
+    # output of the call on the compacted rows.
+    O2 = torch.full_like(Qd, float("nan"))
+    tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, cache.idx[0], None, None, cache.offs, cache.n_rows[0], O2, None, wsp)
+    torch.cuda.synchronize()
+    assert torch.equal(O2, O), "gather-free output differs"
+    # Window part and global part on their own, merged through the log-sum-exp: Eq. 2 again, up to the
+    # rounding of the two partial outputs to the storage type (half a unit in the last place of a
+    # part each, on top of the tolerance of the one-pass kernel).
+    O_w, O_g = torch.full_like(Qd, float("nan")), torch.full_like(Qd, float("nan"))
+    lse2 = torch.full((2, Hq, L), float("nan"), dtype=torch.float32, device="cuda")
+    tb.tca_prefill_part(prm, tb.TCA_PART_WINDOW, Qd, 0, L, Kd, Vd, L, cache.idx[0], cache.Kg[0], cache.Vg[0], cache.offs,
+                        cache.n_rows[0], O_w, lse2[0], wsp)
+    tb.tca_prefill_part(prm, tb.TCA_PART_GLOBAL, Qd, 0, L, Kd, Vd, L, cache.idx[0], cache.Kg[0], cache.Vg[0], cache.offs,
+                        cache.n_rows[0], O_g, lse2[1], wsp)
+    tb.tca_prefill_merge(prm, L, O_w, lse2[0], O_g, lse2[1], None)
+    torch.cuda.synchronize()
+    Om = bufs.to_host_f64(O_w)
+    assert not np.isnan(Om).any()
+    slack = 0.0 if dtype == "f32" else 2.0 ** -8 * max(1.0, float(np.abs(Oref).max()))
+    err_m = np.abs(Om - Oref).max()
+    assert err_m <= H.TOL[dtype] + slack, f"merged parts max abs err {err_m}"
+
     if not exact:
         return                                   # a sub-margin tie: the decode replay below needs identical sets
     ocache = orc.cache_after_prefill(Kf, Vf, sels)
@@ -109,3 +135,28 @@ def run_case(mods, case, seed, share):
     for h in range(Hs):
         o, n = int(cache.offs[h]), int(cache.n_rows[0, h].item())
         assert np.array_equal(cache.idx[0, o:o + n].cpu().numpy(), ocache.S[h]), f"head {h} after decode"
+
+    if dtype != "bf16":
+        return
+    # the same steps on an FP8 cache (codes and one scale per row), against the oracle reading the
+    # rows back through the same quantisation
+    gbs = bufs.GlobalBuffers(prm, rows + extra)
+    tb.tca_select(prm, Qd[:, L - 1].contiguous(), Kd, Vd, L, 0, L, P_gpu, gbs.offs, gbs.n_rows, gbs.idx, gbs.Kg, gbs.Vg, ws)
+    c8 = bufs.DecodeCache(prm, 1, rows + extra, kv_format=tb.TCA_KV_FP8)
+    tb.tca_cache_load_global(prm, c8.view, 0, gbs.idx, gbs.Kg, gbs.Vg, gbs.offs, gbs.n_rows)
+    tb.tca_cache_load_window(prm, c8.view, 0, Kd, Vd, L, L)
+    o8 = orc.cache_after_prefill(Kf, Vf, sels, kv_quant="fp8")
+    Od.fill_(float("nan"))
+    for s in range(steps):
+        tb.tca_decode(prm, c8.view, c8.offs, qd[s], kd[s], vd[s], P_gpu, Od[s], wsd)
+    torch.cuda.synchronize()
+    Odg = bufs.to_host_f64(Od)
+    worst = 0.0
+    for s in range(steps):
+        ref = orc.decode_step(o8, wl.to_f64(dec["q"][s, 0]), wl.to_f64(dec["k_new"][s, 0]),
+                              wl.to_f64(dec["v_new"][s, 0]), b, w, P_orc, share=share, kv_quant="fp8")
+        worst = max(worst, np.abs(Odg[s, 0] - ref).max())
+    assert worst <= H.TOL[dtype], f"fp8 cache decode max abs err {worst}"
+    for h in range(Hs):
+        o, n = int(c8.offs[h]), int(c8.n_rows[0, h].item())
+        assert np.array_equal(c8.idx[0, o:o + n].cpu().numpy(), o8.S[h]), f"head {h} after decode on the fp8 cache"
