@@ -722,10 +722,11 @@ void prefill_mfma_kernel(
       // region): behind every MFMA one fragment read and an even share of the plain vector ALU work, the
       // exponentials left to fall where they may, which is two per MFMA of the S half.  Left to itself the
       // scheduler starts the step with eight bare MFMAs and crowds the exponentials into the middle;
-      // measured 1.3 - 2 % faster than that.  Pinning the exponentials or the scalar instructions as well
-      // measured 8 % slower.
+      // measured 2 - 2.5 % faster than that (2 .. 6 instructions behind an MFMA of S and 3 .. 6 behind
+      // one of P V tried: within 1 % of each other).  Pinning the exponentials or the scalar
+      // instructions as well measured 8 % slower.
       constexpr int kMfma = 0x008, kValu = 0x002, kDsRead = 0x100, kVmemRead = 0x020;
-      constexpr int VA = 512 / D, VB = 640 / D;        // plain vector ALU instructions behind an MFMA of S, of P V
+      constexpr int VA = 384 / D, VB = 640 / D;        // plain vector ALU instructions behind an MFMA of S, of P V
       __builtin_amdgcn_sched_group_barrier(kDsRead, kFragAhead, 0);
 #pragma unroll
       for (int i = 0; i < 2 * KK; ++i) {
