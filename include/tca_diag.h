@@ -24,10 +24,11 @@ size_t tca_probe_workspace_bytes(void);
 int tca_probe_mfma(int random_operands, int iters, double* tflops, double* shader_ghz,
                    void* ws, size_t ws_bytes, void* stream);
 
-/* enable != 0: every later TCA_BF16 tca_prefill call leaves, in the first two uint64 of its
- * workspace, the sum over workgroups of elapsed shader-clock cycles and of elapsed 100 MHz
- * ticks (two atomic adds per workgroup); their ratio / 10 is the average shader clock in GHz
- * during the attention kernel.  Off by default: the kernel then records nothing. */
+/* enable != 0: every later TCA_BF16 tca_prefill call leaves, in the first four uint64 of its
+ * workspace, sums over the workgroups of its attention kernel (four atomic adds per workgroup):
+ * elapsed shader-clock cycles; elapsed 100 MHz ticks (cycles / ticks / 10 is the average
+ * shader clock in GHz); the cycles that passed before the first tile step; the 64-key tiles
+ * walked.  Off by default: the kernel then records nothing. */
 void tca_diag_prefill_clocks(int enable);
 
 /* Workgroup shape of the bf16 prefill kernel: 0 = chosen by the size of the call (default);

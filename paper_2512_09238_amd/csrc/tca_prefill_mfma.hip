@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void transpose_tiles_kernel(
   // mode 1: dense K/V (group = KV head; absolute rows first_row + 64*tile, valid while < valid_all)
   __shared__ uint16_t tile[kBN][D + 8];
   const int g = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
-  if (clk && g == 0 && t == 0 && tid < 2) clk[tid] = 0;      // the attention kernel that follows accumulates here
+  if (clk && g == 0 && t == 0 && tid < 4) clk[tid] = 0;      // the attention kernel that follows accumulates here
   int64_t row0;
   int64_t n_valid;
   size_t out_tile;
@@ -130,6 +130,24 @@ __device__ __forceinline__ int count_le_i32(const int32_t* idx, int n, int64_t b
   while (lo < hi) {
     const int mid = (lo + hi) >> 1;
     if ((int64_t)idx[mid] <= bound) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// The same count for a bound all 64 lanes share, found by the wave together: every round probes 64
+// evenly spaced elements of the remaining range at once, so 2^18 elements take three dependent loads
+// instead of eighteen.  n, bound: wave-uniform; the result is uniform as well.
+__device__ __forceinline__ int count_le_wave(const int32_t* idx, int n, int64_t bound, int lane) {
+  int lo = 0, len = n;                               // the count lies in [lo, lo + len]
+  while (len > 0) {
+    const int step = (len + 63) >> 6;
+    const int p = lo + (lane + 1) * step - 1;        // ascending probes: the lanes that pass form a prefix
+    const bool le = p < lo + len && (int64_t)idx[p] <= bound;
+    const int k = __builtin_popcountll(__ballot(le));
+    lo += k * step;
+    const int left = n - lo;                         // elements from lo to the end of the array
+    len = k == 64 ? 0 : (step - 1 < left ? step - 1 : left);
+    if (k == 64) lo = lo < n ? lo : n;
   }
   return lo;
 }
@@ -319,7 +337,6 @@ void prefill_mfma_kernel(
     int64_t qrow_i = r0 + wv * WQ + blk * 32 + c;
     if (qrow_i > last_row) qrow_i = last_row;       // clamped rows compute a duplicate; never stored
     qpos[blk] = (int)(q_pos0 + qrow_i);
-    nvis[blk] = count_le_i32(idx + base, nr, (int64_t)qpos[blk] - w);
     const uint16_t* qrow = Q + ((size_t)h * n_queries + qrow_i) * D;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[blk][kk] = *reinterpret_cast<const bf16x8_t*>(qrow + kk * 16 + hh * 8);
@@ -330,9 +347,24 @@ void prefill_mfma_kernel(
   const int wg_last = (int)(q_pos0 + i64min(r0 + BM - 1, last_row));
   const int wg_first = (int)(q_pos0 + r0);
   const int last_pos = (int)(q_pos0 + last_row);
-  // the searches below take wave-uniform arguments; readfirstlane keeps the results scalar
-  const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, (int64_t)wave_first - w));  // visible to every query of the wave
-  const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_i32(idx + base, nr, (int64_t)wg_last - w));
+  // Global rows visible to every query of the wave, to some query of the workgroup: two searches with
+  // wave-uniform bounds, done by the wave together (a workgroup has the CU to itself, so what its
+  // prologue waits for is lost; a binary search per lane was 17 dependent loads).  A lane's own count
+  // follows from the first: its query lies at most WQ - 1 positions behind the wave's first one, and
+  // positions are distinct and ascending, so only the next WQ rows can make the difference.
+  const int nv_wave_lo = __builtin_amdgcn_readfirstlane(count_le_wave(idx + base, nr, (int64_t)wave_first - w, lane));
+  const int nv_wg_hi = __builtin_amdgcn_readfirstlane(count_le_wave(idx + base, nr, (int64_t)wg_last - w, lane));
+  {
+    const int nxt = nv_wave_lo + lane < nr ? idx[base + nv_wave_lo + lane] : 0x7FFFFFFF;   // lane j: row nv_wave_lo + j
+#pragma unroll
+    for (int blk = 0; blk < QB; ++blk) nvis[blk] = nv_wave_lo;
+#pragma unroll
+    for (int j = 0; j < WQ - 1; ++j) {
+      const int pj = __builtin_amdgcn_readlane(nxt, j);
+#pragma unroll
+      for (int blk = 0; blk < QB; ++blk) nvis[blk] += (int64_t)pj <= (int64_t)qpos[blk] - w;
+    }
+  }
   const int n_gt = (nv_wg_hi + kBN - 1) / kBN;
   const int win_lo = wg_first - w + 1 > 0 ? wg_first - w + 1 : 0;
   const int wt0 = win_lo / kBN, wt1 = wg_last / kBN;                      // absolute dense tiles [wt0, wt1]
@@ -785,6 +817,7 @@ void prefill_mfma_kernel(
       l[1] += lt;
     }
   }
+  const unsigned long long clk_loop = __builtin_readcyclecounter();
   for (int it = 0; it < n_tiles; it += 2) {
     step(it, sa, sb);
     if (it + 1 < n_tiles) step(it + 1, sb, sa);
@@ -793,6 +826,8 @@ void prefill_mfma_kernel(
   if (clk && tid == 0) {                          // diagnostics only: elapsed shader-clock cycles and 100 MHz ticks of this workgroup
     atomicAdd(clk, (unsigned long long)__builtin_readcyclecounter() - clk_c0);
     atomicAdd(clk + 1, (unsigned long long)__builtin_amdgcn_s_memrealtime() - clk_r0);
+    atomicAdd(clk + 2, clk_loop - clk_c0);        // of which before the first step
+    atomicAdd(clk + 3, (unsigned long long)n_tiles);
   }
 
   // ---- normalise and store
@@ -820,7 +855,7 @@ void prefill_mfma_kernel(
 
 // ------------------------------------------------------------------ host side --
 struct MfmaWs {
-  unsigned long long* clk;   // {sum of workgroup shader-clock cycles, sum of workgroup 100 MHz ticks} of the last call
+  unsigned long long* clk;   // sums over the workgroups of the last call: {shader-clock cycles, 100 MHz ticks, cycles before the first step, tiles}
   uint16_t* Vgt;       // [g_tiles][D][64]
   uint16_t* Vt;        // [Hkv][dense_tiles][D][64]
   size_t bytes;
@@ -834,7 +869,7 @@ static MfmaWs carve_mfma_ws(void* ws, const tca_params* prm, int64_t g_tiles, in
   char* b = (char*)ws;
   size_t off = 0;
   const size_t tile_bytes = (size_t)prm->head_dim * kBN * 2;
-  m.clk = (unsigned long long*)(b + off); off = align_up(off + 2 * sizeof(unsigned long long), 256);
+  m.clk = (unsigned long long*)(b + off); off = align_up(off + 4 * sizeof(unsigned long long), 256);
   m.Vgt = (uint16_t*)(b + off); off = align_up(off + (size_t)g_tiles * tile_bytes, 256);
   m.Vt = (uint16_t*)(b + off);  off = align_up(off + (size_t)prm->n_kv_heads * d_tiles * tile_bytes, 256);
   m.bytes = off;

@@ -1,6 +1,6 @@
 """Diagnostics of the bf16 prefill kernel (not part of the hot path; uses include/tca_diag.h).
 
-  python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2] [--queries 2048]
+  python -m paper_2512_09238_amd.diag occupancy [--heads 32 16 8] [--variants 3 2] [--queries 2048] [--length 131072]
 
   python -m paper_2512_09238_amd.diag loop {prefill,tail,probe-random,probe-constant} [--seconds 10]
                                            [--heads 8] [--queries 2048] [--variant 3]
@@ -18,7 +18,8 @@ time or rate, and the shader clock.
 recipe, budget 57 % for every head) with 32, 16 and 8 query heads: 256, 128 and 64 workgroups of the
 same work each, i.e. the whole chip, half and a quarter of it.  Prints per call the event-timed
 duration, the mean workgroup duration and the shader clock, both from the kernel's own counters
-(cycle counter and 100 MHz counter, tca_diag_prefill_clocks), and the cycles per workgroup.  Equal
+(cycle counter and 100 MHz counter, tca_diag_prefill_clocks), the cycles per workgroup, how many of
+them pass before the first tile step, and the tiles a workgroup walks.  Equal
 cycles at different clocks separate what the code costs from what the power limit costs.
 --variants names the workgroup shapes to run (tca_diag_prefill_variant: 1 = 4 waves x 32 queries,
 2 = 4 x 64, 3 = 8 x 32, the shape of long calls and the default here).
@@ -38,7 +39,7 @@ def occupancy(args):
     import torch
     import workloads as wl
     from paper_2512_09238_amd import binding as tb, buffers as bufs
-    L, d, b, w, n = 131072, 128, 128, 4096, args.queries
+    L, d, b, w, n = args.length, 128, 128, 4096, args.queries
     tb.tca_diag_prefill_clocks(True)
     try:
         for Hq in args.heads:
@@ -67,10 +68,13 @@ def occupancy(args):
                     e1.record()
                     torch.cuda.synchronize()
                     c = ws[:16].view(torch.int64).cpu().numpy()
-                    res.append((e0.elapsed_time(e1), c[1] / nwg / 100.0, c[0] / (c[1] * 10.0), c[0] / nwg / 1e6))
-                t, u, g, cyc = (float(np.mean([r[i] for r in res[1:]])) for i in range(4))
+                    c4 = ws[:32].view(torch.int64).cpu().numpy()
+                    res.append((e0.elapsed_time(e1), c[1] / nwg / 100.0, c[0] / (c[1] * 10.0), c[0] / nwg / 1e6,
+                                c4[2] / nwg / 1e3, c4[3] / nwg))
+                t, u, g, cyc, pro, tiles = (float(np.mean([r[i] for r in res[1:]])) for i in range(6))
                 print(f"heads {Hq:3d}  shape {variant}  workgroups {nwg:4d}:  call {t:.3f} ms   workgroup {u:7.1f} us   "
-                      f"clock {g:.2f} GHz   {cyc:.2f} M cycles per workgroup", flush=True)
+                      f"clock {g:.2f} GHz   {cyc:.2f} M cycles per workgroup, {pro:.1f} K of them before the first of "
+                      f"{tiles:.0f} tiles", flush=True)
             tb.tca_diag_prefill_variant(0)
             del gb, ws, ws_sel, Qd, Kd, Vd, Qc, O
             torch.cuda.empty_cache()
@@ -158,6 +162,7 @@ def main():
     o.add_argument("--variants", type=int, nargs="+", default=[3], choices=[1, 2, 3])
     o.add_argument("--repeats", type=int, default=3)
     o.add_argument("--queries", type=int, default=2048, help="queries of the call: the last so many of the sequence")
+    o.add_argument("--length", type=int, default=131072, help="tokens of the sequence")
     o.set_defaults(fn=occupancy)
     lp = sub.add_parser("loop")
     lp.add_argument("what", choices=["prefill", "tail", "probe-random", "probe-constant"])
