@@ -131,28 +131,31 @@ extern "C" int tca_select_prefill_overlapped(const tca_params* prm, const void* 
     return fail(TCA_ERR_INVALID, "tca_select_prefill_overlapped: needs O_part, lse_parts and a second stream");
   const int64_t n_lse = (int64_t)prm->n_q_heads * n_tokens;
   hipStream_t st = (hipStream_t)stream, side = (hipStream_t)side_stream;
-  hipEvent_t ready, window_done;
-  TCA_HIP_CHECK(hipEventCreateWithFlags(&ready, hipEventDisableTiming));
-  TCA_HIP_CHECK(hipEventCreateWithFlags(&window_done, hipEventDisableTiming));
-  auto finish = [&](int code) {
-    (void)hipEventDestroy(ready);
-    (void)hipEventDestroy(window_done);
+  hipEvent_t ready = nullptr, window_done = nullptr;
+  auto finish = [&](int code) {                   // the events go on every way out
+    if (ready) (void)hipEventDestroy(ready);
+    if (window_done) (void)hipEventDestroy(window_done);
     return code;
   };
+  auto hip_ok = [&](hipError_t e, const char* what) {
+    return e == hipSuccess ? TCA_OK : fail(TCA_ERR_HIP, "tca_select_prefill_overlapped: %s: %s", what, hipGetErrorString(e));
+  };
+  if ((rc = hip_ok(hipEventCreateWithFlags(&ready, hipEventDisableTiming), "event"))) return finish(rc);
+  if ((rc = hip_ok(hipEventCreateWithFlags(&window_done, hipEventDisableTiming), "event"))) return finish(rc);
   // the inputs are ready where `stream` stands now
-  TCA_HIP_CHECK(hipEventRecord(ready, st));
-  TCA_HIP_CHECK(hipStreamWaitEvent(side, ready, 0));
+  if ((rc = hip_ok(hipEventRecord(ready, st), "record"))) return finish(rc);
+  if ((rc = hip_ok(hipStreamWaitEvent(side, ready, 0), "wait"))) return finish(rc);
   rc = prefill_checked(prm, Q, pos0, n_tokens, K, V, kv_stride, idx, Kg, Vg, offs, n_rows, O_part, lse_parts,
                        ws_prefill, ws_prefill_bytes, side, TCA_PART_WINDOW, "tca_select_prefill_overlapped (window)");
   if (rc) return finish(rc);
-  TCA_HIP_CHECK(hipEventRecord(window_done, side));
+  if ((rc = hip_ok(hipEventRecord(window_done, side), "record"))) return finish(rc);
   rc = tca_select(prm, q_last, K, V, kv_stride, pos0, n_tokens, p, offs, n_rows, idx, Kg, Vg, ws_select,
                   ws_select_bytes, stream);
   if (rc) return finish(rc);
   rc = prefill_checked(prm, Q, pos0, n_tokens, K, V, kv_stride, idx, Kg, Vg, offs, n_rows, O, lse_parts + n_lse,
                        ws_prefill, ws_prefill_bytes, stream, TCA_PART_GLOBAL, "tca_select_prefill_overlapped (global)");
   if (rc) return finish(rc);
-  TCA_HIP_CHECK(hipStreamWaitEvent(st, window_done, 0));
+  if ((rc = hip_ok(hipStreamWaitEvent(st, window_done, 0), "wait"))) return finish(rc);
   rc = tca_prefill_merge(prm, n_tokens, O, lse_parts + n_lse, O_part, lse_parts, nullptr, stream);
   return finish(rc);
 }
