@@ -147,3 +147,26 @@ def test_calibration_file_round_trip(tmp_path):
         f.write('{"format": "something else"}')
     with pytest.raises(ValueError):
         calib.load_calibration(path)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU: bench.py --gpus N with N above 1 ends with a message, before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout) or "1 GPU" in (r.stderr + r.stdout) or "--gpus" in (r.stderr + r.stdout)
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    """The product path has no fallback: with no libtca.so to load, importing the binding raises."""
+    import shutil
+    import subprocess
+    import sys
+    pkg = tmp_path / "paper_2512_09238_amd"
+    shutil.copytree(os.path.join(ROOT, "paper_2512_09238_amd"), pkg,
+                    ignore=shutil.ignore_patterns("*.so", "_build", "__pycache__", "csrc"))
+    code = "import paper_2512_09238_amd.binding"
+    r = subprocess.run([sys.executable, "-c", code], cwd=tmp_path, capture_output=True, text=True, timeout=300,
+                       env={**os.environ, "PYTHONPATH": str(tmp_path)})
+    assert r.returncode != 0 and "libtca" in r.stderr
