@@ -653,7 +653,10 @@ void prefill_mfma_kernel(
 
   // One pipeline step: tile `it` (scores in sc; with QB = 2 those of block 1 are already in pf[1])
   // goes through softmax and P V; the scores of tile it+1 go to sn.
-  auto step = [&](int it, f32x16_t (&sc)[QB][2], f32x16_t (&sn)[QB][2]) {
+  // clear_tag: std::true_type when the caller knows that this wave sees every key of tile `it` (the
+  // stretches of the loop below where no tile needs a mask), which saves the test per step
+  auto step = [&](int it, f32x16_t (&sc)[QB][2], f32x16_t (&sn)[QB][2], auto clear_tag) {
+    constexpr bool kKnownClear = decltype(clear_tag)::value;
     // K(it+1) and V^T(it) have landed for this wave (only the copies of the previous step may still
     // be on their way when the rings hold three tiles); after the barrier for every wave, and every
     // wave is done reading K(it) and V^T(it-1)
@@ -689,7 +692,7 @@ void prefill_mfma_kernel(
       // masking on a boundary tile); the state is rescaled, before the exponentials, only when some
       // query's maximum moved.  Everything from here to the end of the step is one basic block, so
       // that the first P V MFMAs can start while the later exponentials are still being formed.
-      const bool masked = !mask_tile_is_clear(it);
+      const bool masked = !kKnownClear && !mask_tile_is_clear(it);
       float mx = mx_pre;
       if (masked) {
         mask_tile(it, 0, sc[0]);
@@ -818,9 +821,43 @@ void prefill_mfma_kernel(
     }
   }
   const unsigned long long clk_loop = __builtin_readcyclecounter();
-  for (int it = 0; it < n_tiles; it += 2) {
-    step(it, sa, sb);
-    if (it + 1 < n_tiles) step(it + 1, sb, sa);
+  if constexpr (QB == 1) {
+    // The tiles this wave sees all of form two stretches: the region tiles below the rows visible to its
+    // first query, and the window tiles between its last query's window start and its first query.  Their
+    // ends are moved to even steps (a clear tile may always take the masked path), so that every stretch
+    // is a run of the twice-unrolled loop.
+    const int a0 = nv_wave_lo / kBN;                                         // region tiles [0, a0) are clear
+    const int t_lo = wave_last - w < 0 ? 0 : (wave_last - w) / kBN + 1;       // dense tiles [t_lo, t_hi] are clear
+    const int t_hi = wave_first - (kBN - 1) < 0 ? -1 : (wave_first - (kBN - 1)) / kBN;
+    int b0 = t_lo - dshift, c0 = t_hi + 1 - dshift;                           // as steps: [b0, c0)
+    if (b0 < n_gt) b0 = n_gt;
+    if (c0 > n_tiles) c0 = n_tiles;
+    const int a = a0 & ~1;
+    int b = (b0 + 1) & ~1, c = c0 & ~1;
+    if (b < a) b = a;
+    if (c < b) c = b;
+    if (b > n_tiles) b = c = n_tiles & ~1;
+    for (int it = 0; it < a; it += 2) {
+      step(it, sa, sb, std::true_type{});
+      step(it + 1, sb, sa, std::true_type{});
+    }
+    for (int it = a; it < b; it += 2) {
+      step(it, sa, sb, std::false_type{});
+      if (it + 1 < n_tiles) step(it + 1, sb, sa, std::false_type{});
+    }
+    for (int it = b; it < c; it += 2) {
+      step(it, sa, sb, std::true_type{});
+      step(it + 1, sb, sa, std::true_type{});
+    }
+    for (int it = c; it < n_tiles; it += 2) {
+      step(it, sa, sb, std::false_type{});
+      if (it + 1 < n_tiles) step(it + 1, sb, sa, std::false_type{});
+    }
+  } else {
+    for (int it = 0; it < n_tiles; it += 2) {
+      step(it, sa, sb, std::false_type{});
+      if (it + 1 < n_tiles) step(it + 1, sb, sa, std::false_type{});
+    }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);             // no copy into this workgroup's LDS may outlive it
   if (clk && tid == 0) {                          // diagnostics only: elapsed shader-clock cycles and 100 MHz ticks of this workgroup
