@@ -659,9 +659,12 @@ void prefill_mfma_kernel(
     constexpr bool kKnownClear = decltype(clear_tag)::value;
     // K(it+1) and V^T(it) have landed for this wave (only the copies of the previous step may still
     // be on their way when the rings hold three tiles); after the barrier for every wave, and every
-    // wave is done reading K(it) and V^T(it-1)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | ((RING - 2) * Copy::N));     // vmcnt((RING - 2) * N)
-    __syncthreads();
+    // wave is done reading K(it) and V^T(it-1).  With one block per wave this wait and barrier sit
+    // inside the previous step, before its last P V MFMAs (see there).
+    if constexpr (QB != 1) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | ((RING - 2) * Copy::N));     // vmcnt((RING - 2) * N)
+      __syncthreads();
+    }
     const int tk = it + RING < last ? it + RING : last, tv = it + RING - 1 < last ? it + RING - 1 : last;   // past the end: a harmless reload
     // ring places (it - 1, it, it + 1) % RING; with two places they follow from the parity of `it`, which the
     // twice-unrolled loop makes a constant of each copy of the step (LDS offsets fold into the instructions)
@@ -743,6 +746,15 @@ void prefill_mfma_kernel(
 #pragma unroll
     for (int j = 0; j < 4 * DS; ++j) {
       const int sl = j % DS, sg = j / DS;           // sg = sub*2 + g: 16 keys
+      if constexpr (QB == 1) {
+        // The barrier of the next step, taken as soon as the last V^T fragment of this tile has been
+        // requested (the reads run kFragAhead ahead): the MFMAs still to come work from registers and
+        // cover the first fragment reads of the next tile, which cannot start before the barrier.
+        if (j == 4 * DS - kFragAhead) {
+          __builtin_amdgcn_s_waitcnt(0x0F70);          // this wave's copies of K(it+2), V^T(it+1) have landed
+          __syncthreads();
+        }
+      }
 #pragma unroll
       for (int blk = 0; blk < QB; ++blk) pv_mfma<QB == 2>(o[blk][sl], vfr[j % kFragAhead], pf[blk][sg >> 1][sg & 1]);
       if (j + kFragAhead < 4 * DS) vfr[j % kFragAhead] = vfrag(j + kFragAhead);
@@ -822,6 +834,8 @@ void prefill_mfma_kernel(
   }
   const unsigned long long clk_loop = __builtin_readcyclecounter();
   if constexpr (QB == 1) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // K(1) is in: the barrier of step 0 (every later one sits in the step before)
+    __syncthreads();
     // The tiles this wave sees all of form two stretches: the region tiles below the rows visible to its
     // first query, and the window tiles between its last query's window start and its first query.  Their
     // ends are moved to even steps (a clear tile may always take the masked path), so that every stretch
