@@ -836,6 +836,10 @@ void prefill_mfma_kernel(
   if constexpr (QB == 1) {
     __builtin_amdgcn_s_waitcnt(0x0F70);              // K(1) is in: the barrier of step 0 (every later one sits in the step before)
     __syncthreads();
+  }
+  // (the stretches below pay off with eight waves; with four the scheduler no longer follows the order
+  // pinned in the step for the test-free copies of it, and the plain loop is faster)
+  if constexpr (QB == 1 && NW == 8) {
     // The tiles this wave sees all of form two stretches: the region tiles below the rows visible to its
     // first query, and the window tiles between its last query's window start and its first query.  Their
     // ends are moved to even steps (a clear tile may always take the masked path), so that every stretch
