@@ -401,6 +401,35 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     assert worst_o <= H.TOL["bf16"]
 
 
+def test_prefill_is_deterministic_at_full_size(tb, bufs):
+    """The bf16 attention kernel synchronises its workgroups' tile copies with one barrier per tile;
+    a copy that could land late, or a tile overwritten early, would show as run-to-run differences.
+    Config 3: six calls on the same inputs and workspace, every output equal to the first bit for
+    bit, with the selection rerun in between so that the workspace and caches are disturbed."""
+    c = wl.CONFIGS[3]
+    Hq, Hkv, d, L, b, w = c["Hq"], c["Hkv"], c["d"], c["L"], c["b"], c["w"]
+    prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
+    x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
+    fr = wl.budget_fractions(wl.budget_seed(3), Hq)
+    P = np.stack([tb.tca_config_from_budget(b, c["sigma"], f) for f in fr])
+    gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P)
+    ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
+    ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
+    q_last = Qd[:, L - 1].contiguous()
+    first = None
+    for rep in range(6):
+        O = torch.full_like(Qd, float("nan"))
+        tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
+        torch.cuda.synchronize()
+        if first is None:
+            first = O
+        else:
+            assert torch.equal(O, first), f"call {rep} differs from the first"
+        gb.n_rows.zero_()
+        tb.tca_select(prm, q_last, Kd, Vd, L, 0, L, P, gb.offs, gb.n_rows, gb.idx, gb.Kg, gb.Vg, ws_sel)
+    assert not torch.isnan(first.float()).any()
+
+
 def test_longest_single_call_4096_blocks_512k_tokens(tb, bufs):
     """The most one tca_select call ranks (4096 blocks of 128 = 524288 tokens), with prefill over
     the same range: 32-bit tile offsets close to their 2 GiB guard, 2048 query tiles per head."""
