@@ -55,6 +55,7 @@ constexpr float kRaise = 0x1p60f;    // a tile whose terms sum to this much rais
 struct PrefillHeads {
   int64_t offs[TCA_MAX_HEADS + 1];      // row offsets of the heads' regions
   int32_t tile_off[TCA_MAX_HEADS + 1];  // V^T tile offsets of the heads' regions
+  int32_t xcd_start[9];                 // the range of the (head, query tile) sequence each XCD works through
 };
 
 // position p (0..63) inside a stored V^T tile -> key (0..63) of the tile
@@ -312,11 +313,20 @@ void prefill_mfma_kernel(
   // the query tiles in flight on an XCD then belong to one head and stream the same K / V^T tiles
   // through its L2 (and the heads of a KV group, which share the dense tiles - with a shared
   // selection all tiles - follow each other on the same XCD).
+  // Heads differ in the rows they keep, so whole heads per XCD leave the XCDs unevenly loaded: the
+  // sequence (head-major, a head's query tiles longest first) is cut instead into eight ranges of equal
+  // estimated work (xcd_start, from the host).  An XCD takes the piece of the head its range ends in
+  // first (that head's longest tiles) and the rest in order, so that it ends on a head's shortest tiles.
   int h, qtile;
   if ((Hq & 7) == 0) {
-    const int u = bid >> 3;                        // position in the XCD's own sequence
-    h = (bid & 7) * (Hq >> 3) + u / n_qt;          // one head at a time per XCD
-    qtile = n_qt - 1 - u % n_qt;                   // longest tiles first
+    const int x = bid & 7, u = bid >> 3;           // XCD, position in the XCD's own sequence
+    const int s = ph.xcd_start[x], e = ph.xcd_start[x + 1];
+    if (u >= e - s) return;                        // the grid is sized for the longest range
+    const int he = e / n_qt * n_qt;                // where the head begins in which the range ends
+    const int len_e = he > s ? e - he : 0;
+    const int g = u < len_e ? he + u : s + (u - len_e);
+    h = g / n_qt;
+    qtile = n_qt - 1 - g % n_qt;
   } else {
     h = bid % Hq;
     qtile = n_qt - 1 - bid / Hq;
@@ -936,6 +946,40 @@ size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, in
                        max_dense_tiles(n_queries, prm->window)).bytes;
 }
 
+// Cuts the sequence of (head, query tile) work items, in the order the kernel walks it, into eight
+// ranges of equal estimated work and returns the length of the longest.  The estimate is in tile steps:
+// the dense tiles of the window, exactly; the visible part of a head's region as if its rows were spread
+// evenly over the positions seen so far (the host does not know idx); a constant for what a workgroup
+// does before and after its loop.  A poor estimate costs balance, never correctness.
+static int64_t plan_xcds(PrefillHeads& ph, const tca_params* prm, const int64_t* offs, int64_t q_pos0,
+                         int64_t n_queries, int BM, int part) {
+  const int Hq = prm->n_q_heads, GS = sel_group(prm), w = prm->window;
+  const int64_t n_qt = (n_queries + BM - 1) / BM, L_end = q_pos0 + n_queries;
+  constexpr int64_t kFixedSteps = 4;
+  auto cost = [&](int64_t cap, int64_t qt) {
+    const int64_t first = q_pos0 + qt * BM, lastq = first + BM - 1 < L_end - 1 ? first + BM - 1 : L_end - 1;
+    int64_t c = kFixedSteps;
+    if (part != TCA_PART_GLOBAL) c += lastq / kBN - (first - w + 1 > 0 ? first - w + 1 : 0) / kBN + 1;
+    if (part != TCA_PART_WINDOW && lastq >= w) c += (cap * (lastq - w + 1) / L_end + kBN - 1) / kBN;
+    return c;
+  };
+  int64_t total = 0;
+  for (int h = 0; h < Hq; ++h)
+    for (int64_t j = 0; j < n_qt; ++j) total += cost(offs[h / GS + 1] - offs[h / GS], n_qt - 1 - j);
+  int64_t acc = 0, g = 0, longest = 0;
+  int x = 0;
+  ph.xcd_start[0] = 0;
+  for (int h = 0; h < Hq; ++h)
+    for (int64_t j = 0; j < n_qt; ++j, ++g) {
+      acc += cost(offs[h / GS + 1] - offs[h / GS], n_qt - 1 - j);
+      while (x < 7 && acc * 8 >= total * (x + 1)) ph.xcd_start[++x] = (int32_t)(g + 1);
+    }
+  while (x < 8) ph.xcd_start[++x] = (int32_t)g;
+  for (x = 0; x < 8; ++x)
+    if (ph.xcd_start[x + 1] - ph.xcd_start[x] > longest) longest = ph.xcd_start[x + 1] - ph.xcd_start[x];
+  return longest;
+}
+
 template <int D>
 static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, int64_t n_queries,
                      const uint16_t* K, const uint16_t* V, int64_t kv_stride, const int32_t* idx,
@@ -989,7 +1033,9 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
     constexpr int NW = decltype(nw_tag)::value, QB = decltype(qb_tag)::value;
     constexpr bool GATHER = decltype(gather_tag)::value;
     const int n_qt = (int)((n_queries + NW * QB * 32 - 1) / (NW * QB * 32));
-    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB, GATHER>), dim3((unsigned)n_qt * Hq), dim3(NW * 64), 0, st, Q,
+    const unsigned n_wg = (Hq & 7) == 0 ? 8u * (unsigned)plan_xcds(ph, prm, offs, q_pos0, n_queries, NW * QB * 32, part)
+                                        : (unsigned)n_qt * Hq;
+    hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB, GATHER>), dim3(n_wg), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
                        Hq / Hkv, sel_group(prm), w, (float)logit_scale(prm), O, lse, clk, part);
   };

@@ -46,10 +46,11 @@ def test_prefill_full_size_sampled_rows(tb, bufs, cfg_id):
     P_orc = np.stack([orc.config_from_budget(b, c["sigma"], f) for f in fr])
     prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
     gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
     torch.cuda.synchronize()
+    assert not torch.isnan(O).any(), "a (head, query tile) of the output was never written"
     print("gpu done", flush=True)
 
     Kf, Vf = wl.to_f64(x["K"]), wl.to_f64(x["V"])
@@ -260,7 +261,7 @@ def test_config5_ragged_mixed_batch_sampled(tb, bufs):
     seqs = []
     for i, L in enumerate(lengths):
         x = wl.device_lowrank_inputs(Hq, Hkv, d, L, wl.data_seed(5) + 10 * i)
-        seqs.append(dict(Q=x["Q"], K=x["K"], V=x["V"], O=torch.empty_like(x["Q"])))
+        seqs.append(dict(Q=x["Q"], K=x["K"], V=x["V"], O=torch.full_like(x["Q"], float("nan"))))
     mb = sched.MixedBatch(prm, lengths, chunk, P_gpu)
     n_calls = len(mb.events)
     g = torch.Generator(device="cuda").manual_seed(77)
@@ -335,10 +336,11 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     del xc, wsc
     x = wl.prefill_inputs(c["kind"], Hq, Hkv, d, L, "bf16", wl.data_seed(3))
     gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, cal["p_star"])
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
     torch.cuda.synchronize()
+    assert not torch.isnan(O).any(), "a (head, query tile) of the output was never written"
     print("gpu done", flush=True)
     pos = _sample_positions(L, w, b, 10, 7)
     Og = O[:, torch.from_numpy(pos).cuda()].double().cpu().numpy()
@@ -379,7 +381,7 @@ def test_config3_as_benchmarked_calibrated_budgets(tb, bufs):
     n3 = torch.zeros_like(gb.n_rows)
     gb.idx.fill_(-1)
     O2.fill_(float("nan"))
-    O_part = torch.empty_like(O)
+    O_part = torch.full_like(O, float("nan"))
     lse_parts = torch.empty(2, Hq, L, dtype=torch.float32, device="cuda")
     side = torch.cuda.Stream()
     tb.tca_select_prefill_overlapped(prm, q_last, Qd, Kd, Vd, L, 0, L, cal["p_star"], gb.offs, n3, gb.idx, gb.Kg, gb.Vg,
@@ -446,10 +448,11 @@ def test_longest_single_call_4096_blocks_512k_tokens(tb, bufs):
     tb.tca_select(prm, x["Q"][:, L - 1].contiguous(), x["K"], x["V"], L, 0, L, P_gpu, gb.offs, gb.n_rows,
                   gb.idx, gb.Kg, gb.Vg, ws)
     del ws
-    O = torch.empty_like(x["Q"])
+    O = torch.full_like(x["Q"], float("nan"))
     wsp = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, x["Q"], 0, L, x["K"], x["V"], L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, wsp)
     torch.cuda.synchronize()
+    assert not torch.isnan(O).any(), "a (head, query tile) of the output was never written"
     print("gpu done", flush=True)
     Kf, Vf = x["K"][0].double().cpu().numpy(), x["V"][0].double().cpu().numpy()
     pos = _sample_positions(L, w, b, 6, 5)
@@ -484,7 +487,7 @@ def test_diagnostics_clock_and_mfma_probe(tb, bufs):
     P = np.stack([tb.tca_config_from_budget(b, 1.0, 0.3) for _ in range(Hq)])
     prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16")
     gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
     torch.cuda.synchronize()

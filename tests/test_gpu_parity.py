@@ -355,11 +355,11 @@ def test_prefill_full_budget_is_dense_and_chunked_queries(tb, bufs, dtype):
     P = np.zeros((Hq, 6)); P[:, -1] = 1
     prm = H.params_for(tb, Hq, Hkv, d, b, w, dtype)
     gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     half = 200
     Qa, Qb = Qd[:, :half].contiguous(), Qd[:, half:].contiguous()
-    Oa, Ob = torch.empty_like(Qa), torch.empty_like(Qb)
+    Oa, Ob = torch.full_like(Qa, float("nan")), torch.full_like(Qb, float("nan"))
     tb.tca_prefill(prm, Qa, 0, half, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, Oa, None, ws)
     tb.tca_prefill(prm, Qb, half, L - half, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, Ob, None, ws)
     torch.cuda.synchronize()
@@ -512,7 +512,7 @@ def test_select_and_prefill_replayed_from_a_hip_graph(tb, bufs, dtype):
     eager = []
     for x in xs:
         gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
-        O = torch.empty_like(Qd)
+        O = torch.full_like(Qd, float("nan"))
         ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
         tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
         torch.cuda.synchronize()
@@ -521,7 +521,7 @@ def test_select_and_prefill_replayed_from_a_hip_graph(tb, bufs, dtype):
     q_last = torch.empty_like(Qd[:, 0])
     _, rows = tb.tca_select_rows(prm, L // b, P_gpu)
     gbs = bufs.GlobalBuffers(prm, rows)
-    Os = torch.empty_like(Qd)
+    Os = torch.full_like(Qd, float("nan"))
     ws_sel = bufs.workspace(tb.tca_select_workspace_bytes(prm, L))
     ws_pf = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gbs.offs[-1])))
     graph = torch.cuda.CUDAGraph()

@@ -255,7 +255,7 @@ def test_shared_prefill_full_size_sampled_rows(mods):
     P_gpu, P_orc = configs(tb, b, wl.budget_fractions(wl.budget_seed(3), Hkv))
     prm = H.params_for(tb, Hq, Hkv, d, b, w, "bf16", share=True)
     gb, Qd, Kd, Vd = H.gpu_select(tb, bufs, prm, x, P_gpu)
-    O = torch.empty_like(Qd)
+    O = torch.full_like(Qd, float("nan"))
     ws = bufs.workspace(tb.tca_prefill_workspace_bytes(prm, L, int(gb.offs[-1])))
     tb.tca_prefill(prm, Qd, 0, L, Kd, Vd, L, gb.idx, gb.Kg, gb.Vg, gb.offs, gb.n_rows, O, None, ws)
     torch.cuda.synchronize()
