@@ -703,6 +703,23 @@ def rope_rotate(X, positions, base: float = 10000.0, pairing: str = "half") -> n
     return out
 
 
+def qkv_project(X, W, n_q_heads: int, n_kv_heads: int, d: int, bias=None):
+    """The projections that produce what the method takes as given (Sec. III: Q = X W_Q,
+    K = X W_K, V = X W_V, per head): X [n, hidden] are the layer's input rows; W [(Hq + 2 Hkv) d,
+    hidden] holds one row per output feature, the Hq query heads first, then the Hkv key heads,
+    then the Hkv value heads, d rows each (so W_Q of head h is W[h d : (h+1) d].T); bias, if
+    given, [(Hq + 2 Hkv) d] is added to the features.  Returns Q [Hq, n, d], K [Hkv, n, d],
+    V [Hkv, n, d]."""
+    X, W = np.asarray(X, F64), np.asarray(W, F64)
+    n, Hq, Hkv = X.shape[0], n_q_heads, n_kv_heads
+    assert W.shape == ((Hq + 2 * Hkv) * d, X.shape[1])
+    Y = X @ W.T                                          # [n, features]
+    if bias is not None:
+        Y = Y + np.asarray(bias, F64)[None, :]
+    Y = Y.reshape(n, Hq + 2 * Hkv, d).transpose(1, 0, 2)  # [head, n, d]
+    return Y[:Hq].copy(), Y[Hq:Hq + Hkv].copy(), Y[Hq + Hkv:].copy()
+
+
 def calibrate_layers(Qs, Ks, b: int, M: int, sigma: float, tau: float, alpha: float, share: bool = False):
     """Alg. 1 applied to every layer of a model in turn (Sec. IV-A: the determination is made
     once per model, for all heads of all layers): Qs[l] [Hq, L, d], Ks[l] [Hkv, L, d] are the

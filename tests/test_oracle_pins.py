@@ -733,6 +733,51 @@ def test_rope_hand_example_complex_rotation_and_invariants():
     np.testing.assert_allclose(orc.rope_rotate(X, pos, pairing="interleaved")[..., perm], orc.rope_rotate(X[..., perm], pos), atol=1e-12)
 
 
+def test_qkv_project_hand_example_selector_weights_and_brute_force():
+    rows = np.array([list(map(float, l.split())) for l in open(os.path.join(GOLD, "qkv_project_d2.txt"))
+                     if l.strip() and not l.startswith("#")])
+    X = np.array([[1.0, 2.0, 3.0], [0.0, -1.0, 2.0]])
+    W = np.array([[1, 0, 0], [0, 1, 0], [1, 1, 1], [2, 0, -1], [0, 0, 1], [1, -1, 0], [0.5, 0.5, 0], [-1, 2, 1]], float)
+    bias = np.array([0.5, 0, 0, 0, 0, 0, 0, -1.0])
+    for off, bs in ((0, None), (8, bias)):
+        Q, K, V = orc.qkv_project(X, W, 2, 1, 2, bias=bs)
+        assert Q.shape == (2, 2, 2) and K.shape == (1, 2, 2) and V.shape == (1, 2, 2)
+        got = np.concatenate([Q.reshape(4, 2), K.reshape(2, 2), V.reshape(2, 2)])
+        np.testing.assert_array_equal(got, rows[off:off + 8])
+    # weights that pick single hidden features: every output is an entry of X, by name
+    rng = np.random.default_rng(21)
+    n, hidden, Hq, Hkv, d = 5, 40, 3, 1, 4
+    X = rng.standard_normal((n, hidden))
+    pick = rng.permutation(hidden)[: (Hq + 2 * Hkv) * d]
+    W = np.zeros(((Hq + 2 * Hkv) * d, hidden))
+    W[np.arange(len(pick)), pick] = 1.0
+    Q, K, V = orc.qkv_project(X, W, Hq, Hkv, d)
+    for h in range(Hq):
+        for e in range(d):
+            assert np.array_equal(Q[h, :, e], X[:, pick[h * d + e]])
+    for e in range(d):
+        assert np.array_equal(K[0, :, e], X[:, pick[Hq * d + e]])
+        assert np.array_equal(V[0, :, e], X[:, pick[(Hq + Hkv) * d + e]])
+    # the definition, one multiply-add at a time
+    W = rng.standard_normal(((Hq + 2 * Hkv) * d, hidden))
+    bias = rng.standard_normal((Hq + 2 * Hkv) * d)
+    Q, K, V = orc.qkv_project(X, W, Hq, Hkv, d, bias=bias)
+    heads = [("q", h) for h in range(Hq)] + [("k", 0), ("v", 0)]
+    for f0, (kind, h) in enumerate(heads):
+        out = {"q": Q, "k": K, "v": V}[kind][h]
+        for t in range(n):
+            for e in range(d):
+                acc = bias[f0 * d + e]
+                for c in range(hidden):
+                    acc += X[t, c] * W[f0 * d + e, c]
+                assert abs(out[t, e] - acc) < 1e-12
+    # attention over projected rows is what the method's Eq. 1 is written for: Q K^T of head h uses
+    # that head's W_Q and its KV head's W_K
+    S = Q[1] @ K[0].T
+    Wq1, Wk = W[d:2 * d], W[Hq * d:(Hq + 1) * d]
+    np.testing.assert_allclose(S, (X @ Wq1.T + bias[d:2 * d]) @ (X @ Wk.T + bias[Hq * d:(Hq + 1) * d]).T, rtol=1e-12)
+
+
 def test_calibrate_layers_is_alg1_layer_by_layer():
     rng = np.random.default_rng(10)
     Hq, Hkv, d, L, b, M = 2, 1, 8, 64, 4, 5
