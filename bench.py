@@ -134,6 +134,37 @@ def bench_prefill(args, tb, bufs, wl, torch, share=False, x=None):
     return res, host
 
 
+def bench_projection(args, tb, bufs, wl, torch):
+    """The Q / K / V projections in front of the path (tca_qkv_project) on the rows of config 3: hidden
+    size 4096 (the model the configuration is shaped after), all 48 heads, head-major outputs.  Not
+    part of the default step: the metric's workload starts from Q, K, V."""
+    cfg = dict(wl.CONFIGS[3])
+    if args.L:
+        cfg["L"] = args.L
+    Hq, Hkv, d, L, hidden = cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["L"], 4096
+    x = wl.device_projection_inputs(Hq, Hkv, d, hidden, L, wl.data_seed(3) + 50)
+    prm = tb.make_params(Hq, Hkv, d, cfg["b"], cfg["w"], tb.TCA_BF16, cfg["alpha"], 0.0)
+    Q = torch.empty(Hq, L, d, dtype=torch.bfloat16, device="cuda")
+    K, V = torch.empty(Hkv, L, d, dtype=torch.bfloat16, device="cuda"), torch.empty(Hkv, L, d, dtype=torch.bfloat16, device="cuda")
+    run = lambda: tb.tca_qkv_project(prm, x["X"], L, hidden, x["W"], x["bias"], Q, d, L * d, K, V, d, L * d)
+    for _ in range(max(1, args.warmup)):
+        run()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        run()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
+    flops = 2.0 * L * hidden * (Hq + 2 * Hkv) * d
+    tflops = flops / (ms * 1e-3) / 1e12
+    log(f"[bench] tca_qkv_project: {ms:.3f} ms for {L} rows x {hidden} -> {(Hq + 2 * Hkv) * d} features = {tflops:.0f} TFLOP/s")
+    return {"what": f"tca_qkv_project, {L} rows, hidden {hidden}, {(Hq + 2 * Hkv) * d} output features, bf16, head-major outputs",
+            "ms": ms, "flops": flops, "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": tflops / PEAK_BF16_TFLOPS, "bound": "mfma"}
+
+
 def bench_switches(args, tb, bufs, wl, torch, host, cfg):
     """The two switches beside the plain path, on the same inputs and budgets (not part of the default
     run): gather-free prefill (no compacted copy of the kept rows) and the window part of the
@@ -364,6 +395,8 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--calibrate", action="store_true", default=True)
     ap.add_argument("--no-calibrate", dest="calibrate", action="store_false")
+    ap.add_argument("--projection", action="store_true",
+                    help="also time the Q / K / V projections in front of the path (tca_qkv_project, hidden size 4096)")
     ap.add_argument("--mixed", action="store_true", help="also time the config-5 ragged mixed batch (adds about a minute)")
     ap.add_argument("--prefill-variant", type=int, default=0,
                     help="workgroup shape of the bf16 prefill kernel (tca_diag_prefill_variant): 0 = automatic")
@@ -420,6 +453,7 @@ def main():
     if shared is not None and not args.no_decode:
         shared["decode"] = bench_decode(args, tb, bufs, wl, torch, share=True)
     mixed = bench_mixed(args, tb, bufs, wl, torch) if args.mixed else None
+    projection = bench_projection(args, tb, bufs, wl, torch) if args.projection else None
 
     cfg = res["cfg"]
     import paper_2512_09238_amd.profile_summary as ps
@@ -468,6 +502,8 @@ def main():
         out["switches"] = switches
     if mixed is not None:
         out["mixed_batch"] = mixed
+    if projection is not None:
+        out["qkv_project"] = projection
     if shared is not None:
         out["shared_selection"] = shared
     print(json.dumps(out), flush=True)

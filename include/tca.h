@@ -370,6 +370,28 @@ int tca_calibrate_layers(const tca_params* prm, int n_layers, const void* const*
 int tca_rope(const tca_params* prm, void* X, int n_heads, int64_t n_rows, int64_t pos0, double base,
              int pairing, void* stream);
 
+/* The projections that produce what the method takes as given (Sec. III: Q = X W_Q, K = X W_K,
+ * V = X W_V for every head), the step of a model layer that precedes tca_rope (an extension: the
+ * paper's method starts from Q, K, V).  All heads in one call; the results are written in the
+ * layout the next call reads, described by two strides per output, in elements: element e of head
+ * h of token t lands at  out + h * head_stride + t * token_stride + e.
+ *   head-major [H, n, d], what tca_select / tca_prefill / tca_rope read: token_stride = d,
+ *     head_stride = n d (n = the rows the buffer holds per head; point Q / K / V at the first row
+ *     to be written);   token-major [n, H, d], what tca_decode reads: token_stride = H d, head_stride = d.
+ *   X    : device [n_tokens, hidden], the layer's input rows, of tca_params.dtype
+ *   W    : device [(Hq + 2 Hkv) d, hidden], one row per output feature: the query heads first, then
+ *          the key heads, then the value heads, d rows each (the concatenated q/k/v projection weights)
+ *   bias : device [(Hq + 2 Hkv) d] or NULL, added to the features
+ *   Q    : device, Hq heads;  K, V : device, Hkv heads each, sharing kv_token_stride / kv_head_stride
+ * bf16: products are exact, sums fp32, one rounding to bf16; hidden must be a multiple of 64, the
+ * strides multiples of 4, X and W 16-byte and the outputs 8-byte aligned.  fp32: fp32 multiply-adds
+ * in the order of the hidden index; at most 65535 tokens per call.  Does not synchronise, takes no
+ * workspace.  Errors: TCA_ERR_INVALID (NULL pointer, negative size, stride below d, alignment),
+ * TCA_ERR_UNSUPPORTED (the limits above). */
+int tca_qkv_project(const tca_params* prm, const void* X, int64_t n_tokens, int hidden, const void* W,
+                    const void* bias, void* Q, int64_t q_token_stride, int64_t q_head_stride, void* K,
+                    void* V, int64_t kv_token_stride, int64_t kv_head_stride, void* stream);
+
 const char* tca_strerror(int code);
 const char* tca_last_error(void);
 

@@ -106,6 +106,8 @@ EXPORTS = {
                                        C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_rope": (C.c_int, [_P(tca_params), C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_int, C.c_void_p]),
+    "tca_qkv_project": (C.c_int, [_P(tca_params), C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]),
     "tca_strerror": (C.c_char_p, [C.c_int]),
     "tca_last_error": (C.c_char_p, []),
 }
@@ -127,9 +129,11 @@ def _check(rc: int) -> int:
 
 
 def _dp(t):
-    """Device pointer of a torch tensor (None -> NULL)."""
+    """Device pointer of a torch tensor (None -> NULL; an int is taken as a device address)."""
     if t is None:
         return None
+    if isinstance(t, int):                      # a device address (a row inside a caller's buffer)
+        return C.c_void_p(t)
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("device arguments must be contiguous CUDA tensors")
     return C.c_void_p(t.data_ptr())
@@ -330,6 +334,13 @@ def tca_calibrate_layers(prm, Qcals, Kcals, L_cal, M, sigma, tau, ws, stream=Non
 
 def tca_rope(prm, X, n_heads, n_rows, pos0, base=10000.0, pairing=TCA_ROPE_HALF, stream=None):
     _check(lib.tca_rope(C.byref(prm), _dp(X), n_heads, n_rows, pos0, base, pairing, _stream(stream)))
+
+
+def tca_qkv_project(prm, X, n_tokens, hidden, W, bias, Q, q_token_stride, q_head_stride, K, V, kv_token_stride,
+                    kv_head_stride, stream=None):
+    _check(lib.tca_qkv_project(C.byref(prm), _dp(X), n_tokens, hidden, _dp(W), _dp(bias) if bias is not None else None,
+                               _dp(Q), q_token_stride, q_head_stride, _dp(K), _dp(V), kv_token_stride,
+                               kv_head_stride, _stream(stream)))
 
 
 # --------------------------------------------------------- diagnostics --

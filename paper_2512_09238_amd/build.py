@@ -21,6 +21,7 @@ SOURCES = [
     "tca_decode.hip",
     "tca_calibrate.hip",
     "tca_rope.hip",
+    "tca_qkv.hip",
     "tca_diag.hip",
 ]
 

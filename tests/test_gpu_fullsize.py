@@ -500,3 +500,37 @@ def test_diagnostics_clock_and_mfma_probe(tb, bufs):
         tb.tca_diag_prefill_clocks(False)
     print("prefill shader clock %.3f GHz" % ghz, flush=True)
     assert 0.3 < ghz < 2.6
+
+
+def test_qkv_project_full_size_sampled_rows(tb, bufs):
+    """The Q / K / V projections at the size bench.py --projection times (131072 rows, hidden 4096, 32 + 8 + 8
+    heads of 128, head-major outputs, bias): every output element is written, and all 6144 features of
+    sampled rows (the first and last row of the call, rows either side of workgroup-tile boundaries,
+    random ones) equal the fp64 projections rounded to bf16 or their neighbour."""
+    c = wl.CONFIGS[3]
+    Hq, Hkv, d, L, hidden = c["Hq"], c["Hkv"], c["d"], c["L"], 4096
+    x = wl.device_projection_inputs(Hq, Hkv, d, hidden, L, wl.data_seed(3) + 50)
+    prm = H.params_for(tb, Hq, Hkv, d, c["b"], c["w"], "bf16")
+    Q = torch.full((Hq, L, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    K = torch.full((Hkv, L, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    V = torch.full((Hkv, L, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    tb.tca_qkv_project(prm, x["X"], L, hidden, x["W"], x["bias"], Q, d, L * d, K, V, d, L * d)
+    torch.cuda.synchronize()
+    print("gpu done", flush=True)
+    for name, T in zip("QKV", (Q, K, V)):
+        assert not torch.isnan(T).any(), f"{name}: an element was never written"
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, 2047, 2048, L // 2 - 1, L // 2, L - 257, L - 256, L - 2, L - 1],
+                                     rng.integers(0, L, size=40)]))
+    ri = torch.from_numpy(rows).cuda()
+    Xs = x["X"][ri].double().cpu().numpy()
+    ref = orc.qkv_project(Xs, x["W"].double().cpu().numpy(), Hq, Hkv, d, bias=x["bias"].double().cpu().numpy())
+    worst = 0.0
+    for name, T, r in zip("QKV", (Q, K, V), ref):
+        got = T[:, ri].double().cpu().numpy()
+        err = np.abs(got - r)
+        bound = 2.0 ** -8 * np.abs(r) + 1e-4
+        worst = max(worst, float((err / bound).max()))
+        assert (err <= bound).all(), f"{name}: worst error {err.max()}"
+        assert err.max() <= H.TOL["bf16"]
+    print("worst error in units of the bound on", len(rows), "rows:", worst, flush=True)

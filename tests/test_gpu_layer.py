@@ -1,5 +1,6 @@
-"""GPU parity of the layer-integration pieces around the path (extensions): rotary position
-embedding of Q / K rows, and Alg. 1 over several layers with its results kept in a file."""
+"""GPU parity of the layer-integration pieces around the path (extensions): the Q / K / V
+projections, rotary position embedding of Q / K rows, and Alg. 1 over several layers with its
+results kept in a file."""
 import os
 
 import numpy as np
@@ -126,3 +127,84 @@ def test_calibrate_layers_matches_oracle_and_survives_the_file(tb, bufs, tmp_pat
         calib.load_calibration(path, H.params_for(tb, Hq, Hkv, d, 2 * b, 2 * b, "bf16"))
     with pytest.raises(tb.TcaError):
         tb.tca_calibrate_layers(prm, Qs, [Ks[0], None, Ks[2]], L, M, 1.0, tau, ws)
+
+
+# ------------------------------------------------------------ Q / K / V projections --
+QKV_CASES = [
+    # Hq, Hkv, d, hidden, n, dtype, bias, layout, first row written
+    (4, 2, 128, 192, 300, "bf16", True, "head", 5),       # three stages, ragged token tile, rows written at an offset
+    (6, 2, 64, 64, 70, "bf16", True, "token", 0),         # one stage; 640 features: the last feature tile is half empty
+    (8, 8, 128, 128, 1, "bf16", False, "token", 0),       # one row (a decode step), two stages
+    (32, 8, 128, 512, 2100, "bf16", False, "head", 0),    # nine token tiles: more than one per XCD; 24 feature tiles
+    (4, 4, 64, 1024, 257, "bf16", True, "head", 0),       # sixteen stages, one row into the second token tile
+    (4, 1, 64, 100, 50, "f32", True, "head", 3),
+    (2, 2, 128, 48, 9, "f32", False, "token", 0),
+]
+
+
+@pytest.mark.parametrize("case", QKV_CASES, ids=lambda c: f"hq{c[0]}-hkv{c[1]}-d{c[2]}-hid{c[3]}-n{c[4]}-{c[5]}-{c[7]}")
+def test_qkv_project_matches_oracle(tb, bufs, case):
+    """Every element of Q, K and V against the fp64 projections.  bf16: products are exact and the
+    fp32 sum of `hidden` terms carries far less error than the one rounding to bf16, so the result
+    is the oracle's value rounded to bf16, or its neighbour where the two sums straddle a rounding
+    boundary: within 2^-8 relative (plus the sum's own error) everywhere."""
+    Hq, Hkv, d, hidden, n, dtype, with_bias, layout, row0 = case
+    print("case", case, flush=True)
+    x = wl.projection_inputs(Hq, Hkv, d, hidden, n, dtype, 700 + hidden + n)
+    prm = H.params_for(tb, Hq, Hkv, d, 16, 16, dtype)
+    Xd, Wd = bufs.to_device(x["X"]), bufs.to_device(x["W"])
+    bd = bufs.to_device(x["bias"]) if with_bias else None
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    cap = n + row0 + 3                                     # rows the output buffers hold
+    if layout == "head":
+        Q = torch.full((Hq, cap, d), float("nan"), dtype=tdt, device="cuda")
+        K = torch.full((Hkv, cap, d), float("nan"), dtype=tdt, device="cuda")
+        V = torch.full((Hkv, cap, d), float("nan"), dtype=tdt, device="cuda")
+        at = lambda T: T.data_ptr() + row0 * d * T.element_size()      # row `row0` of head 0
+        tb.tca_qkv_project(prm, Xd, n, hidden, Wd, bd, at(Q), d, cap * d, at(K), at(V), d, cap * d)
+        take = lambda T: T[:, row0:row0 + n].double().cpu().numpy()
+        rest = lambda T: torch.cat([T[:, :row0], T[:, row0 + n:]], dim=1)
+    else:
+        Q = torch.full((cap, Hq, d), float("nan"), dtype=tdt, device="cuda")
+        K = torch.full((cap, Hkv, d), float("nan"), dtype=tdt, device="cuda")
+        V = torch.full((cap, Hkv, d), float("nan"), dtype=tdt, device="cuda")
+        tb.tca_qkv_project(prm, Xd, n, hidden, Wd, bd, Q[row0:], Hq * d, d, K[row0:], V[row0:], Hkv * d, d)
+        take = lambda T: T[row0:row0 + n].permute(1, 0, 2).double().cpu().numpy()
+        rest = lambda T: torch.cat([T[:row0], T[row0 + n:]], dim=0)
+    torch.cuda.synchronize()
+    ref = orc.qkv_project(wl.to_f64(x["X"]), wl.to_f64(x["W"]), Hq, Hkv, d,
+                          bias=wl.to_f64(x["bias"]) if with_bias else None)
+    worst_rel, equal = 0.0, []
+    for name, got_t, r in zip("QKV", (Q, K, V), ref):
+        got = take(got_t)
+        assert not np.isnan(got).any(), f"{name}: an element was never written"
+        assert torch.isnan(rest(got_t)).all(), f"{name}: a row outside the call's range was written"
+        err = np.abs(got - r)
+        if dtype == "bf16":
+            bound = 2.0 ** -8 * np.abs(r) + 1e-4
+            equal.append(float((got == _storage_round(r, dtype)).mean()))
+        else:
+            bound = 1e-4 * np.maximum(1.0, np.abs(r))
+        worst_rel = max(worst_rel, float((err / bound).max()))
+        assert (err <= bound).all(), f"{name}: worst error {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+        assert err.max() <= H.TOL[dtype]
+    print("worst error in units of the bound:", worst_rel, "share equal to the rounded oracle:", equal, flush=True)
+    if dtype == "bf16":
+        assert min(equal) > 0.99
+
+
+def test_qkv_project_refuses_what_it_cannot_do(tb, bufs):
+    prm = H.params_for(tb, 4, 2, 128, 16, 16, "bf16")
+    x = wl.projection_inputs(4, 2, 128, 96, 8, "bf16", 5)
+    Xd, Wd = bufs.to_device(x["X"]), bufs.to_device(x["W"])
+    Q = torch.zeros(4, 8, 128, dtype=torch.bfloat16, device="cuda")
+    K, V = torch.zeros(2, 8, 128, dtype=torch.bfloat16, device="cuda"), torch.zeros(2, 8, 128, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(tb.TcaError, match="multiple of 64"):
+        tb.tca_qkv_project(prm, Xd, 8, 96, Wd, None, Q, 128, 8 * 128, K, V, 128, 8 * 128)
+    with pytest.raises(tb.TcaError, match="stride"):
+        tb.tca_qkv_project(prm, Xd, 8, 64, Wd, None, Q, 64, 8 * 128, K, V, 128, 8 * 128)
+    with pytest.raises(tb.TcaError, match="multiples of 4"):
+        tb.tca_qkv_project(prm, Xd, 8, 64, Wd, None, Q, 130, 8 * 130, K, V, 128, 8 * 128)
+    tb.tca_qkv_project(prm, Xd, 0, 64, Wd, None, Q, 128, 8 * 128, K, V, 128, 8 * 128)      # nothing to do
+    torch.cuda.synchronize()
+    assert float(Q.abs().sum()) == 0.0

@@ -168,6 +168,31 @@ def calib_seed(cfg_id: int) -> int:
     return 3000 + cfg_id
 
 
+def projection_inputs(Hq: int, Hkv: int, d: int, hidden: int, n: int, dtype: str, seed: int) -> dict:
+    """Inputs of the Q / K / V projections in front of the path: n rows of hidden states of unit
+    scale (what a normalisation layer hands on), one weight row per output feature of scale
+    1/sqrt(hidden) (outputs of unit scale), a bias of scale 0.1; each rounded once to the storage type."""
+    rng = np.random.default_rng(seed)
+    n_feat = (Hq + 2 * Hkv) * d
+    return {"X": store(rng.standard_normal((n, hidden), dtype=np.float32), dtype),
+            "W": store(rng.standard_normal((n_feat, hidden), dtype=np.float32) / np.float32(hidden ** 0.5), dtype),
+            "bias": store(np.float32(0.1) * rng.standard_normal(n_feat, dtype=np.float32), dtype)}
+
+
+def device_projection_inputs(Hq: int, Hkv: int, d: int, hidden: int, n: int, seed: int, device="cuda:0"):
+    """The recipe of `projection_inputs` in bf16, drawn on the GPU with a seeded torch generator."""
+    import torch
+    g = torch.Generator(device=device).manual_seed(seed)
+    n_feat = (Hq + 2 * Hkv) * d
+    X = torch.empty(n, hidden, device=device, dtype=torch.bfloat16)
+    for r0 in range(0, n, 16384):                        # in slabs: no fp32 copy of the whole array
+        r1 = min(n, r0 + 16384)
+        X[r0:r1] = torch.randn(r1 - r0, hidden, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    W = (torch.randn(n_feat, hidden, generator=g, device=device, dtype=torch.float32) / hidden ** 0.5).to(torch.bfloat16)
+    bias = (0.1 * torch.randn(n_feat, generator=g, device=device, dtype=torch.float32)).to(torch.bfloat16)
+    return {"X": X, "W": W, "bias": bias}
+
+
 # ------------------------------------------- device-side generation (large) --
 def device_lowrank_inputs(Hq: int, Hkv: int, d: int, L: int, seed: int, device="cuda:0", rank: int = 32,
                           noise_std: float = 0.1, dup_frac: float = 0.3, dup_noise_std: float = 0.01):
