@@ -36,6 +36,16 @@ void tca_diag_prefill_clocks(int enable);
  * feeds two MFMAs); 3 = 8 waves x 32 queries.  All shapes compute the same result. */
 int tca_diag_prefill_variant(int variant);
 
+/* How a TCA_BF16 tca_prefill call with these sizes spreads its work over the chip (host only, nothing is
+ * launched): the kernel walks the (head, query tile) items head by head, a head's query tiles from the
+ * last to the first, and XCD x takes the items [start_out[x], start_out[x + 1]).
+ *   offs : host [Hs + 1], as for tca_prefill;  part : TCA_PART_ALL / _WINDOW / _GLOBAL;
+ *   gather_free != 0 : the call would have Kg = Vg = NULL;  start_out : host int32 [9]
+ * Returns the number of workgroups of the attention kernel, or -1 (not a bf16 call, head count not a
+ * multiple of 8, invalid sizes). */
+int64_t tca_diag_prefill_xcd_plan(const tca_params* prm, const int64_t* offs, int64_t q_pos0, int64_t n_queries,
+                                  int part, int gather_free, int32_t* start_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -102,6 +102,7 @@ EXPORTS = {
                                         C.c_void_p, C.c_size_t, C.c_void_p]),
     "tca_diag_prefill_clocks": (None, [C.c_int]),
     "tca_diag_prefill_variant": (C.c_int, [C.c_int]),
+    "tca_diag_prefill_xcd_plan": (C.c_int64, [_P(tca_params), C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]),
     "tca_calibrate_layers": (C.c_int, [_P(tca_params), C.c_int, _P(C.c_void_p), _P(C.c_void_p), C.c_int64, C.c_int,
                                        C.c_double, C.c_double, _dbl_p, _i32_p, _dbl_p, _i64_p, _i32_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -363,6 +364,17 @@ def tca_diag_prefill_clocks(enable: bool) -> None:
 
 def tca_diag_prefill_variant(variant: int) -> None:
     _check(lib.tca_diag_prefill_variant(int(variant)))
+
+
+def tca_diag_prefill_xcd_plan(prm, offs, q_pos0: int, n_queries: int, part: int = 0, gather_free: bool = False):
+    """Returns (start[9], workgroups): the ranges of the (head, query tile) sequence the eight XCDs take."""
+    offs = np.ascontiguousarray(offs, dtype=np.int64)
+    start = np.zeros(9, dtype=np.int32)
+    n = lib.tca_diag_prefill_xcd_plan(C.byref(prm), offs.ctypes.data_as(C.c_void_p), q_pos0, n_queries, part,
+                                      int(bool(gather_free)), start.ctypes.data_as(C.c_void_p))
+    if n < 0:
+        raise ValueError("tca_diag_prefill_xcd_plan: not a bf16 call with a head count that is a multiple of 8")
+    return start, int(n)
 
 
 def prefill_shader_clock_ghz(ws) -> float:

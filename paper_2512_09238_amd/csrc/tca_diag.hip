@@ -12,6 +12,8 @@
 
 #include "tca_common.h"
 #include "tca_diag.h"
+#include "tca_device.h"
+#include "tca_prefill.h"
 
 namespace tca {
 
@@ -64,6 +66,13 @@ extern "C" int tca_diag_prefill_variant(int variant) {
   if (variant < 0 || variant > 3) return fail(TCA_ERR_INVALID, "tca_diag_prefill_variant: %d", variant);
   g_prefill_variant.store(variant);
   return TCA_OK;
+}
+
+extern "C" int64_t tca_diag_prefill_xcd_plan(const tca_params* prm, const int64_t* offs, int64_t q_pos0,
+                                             int64_t n_queries, int part, int gather_free, int32_t* start_out) {
+  if (check_params(prm) != TCA_OK || prm->dtype != TCA_BF16 || !offs || !start_out || q_pos0 < 0 || n_queries < 1) return -1;
+  if (part != TCA_PART_ALL && part != TCA_PART_WINDOW && part != TCA_PART_GLOBAL) return -1;
+  return prefill_mfma_xcd_plan(prm, offs, q_pos0, n_queries, part, gather_free != 0, start_out);
 }
 
 extern "C" size_t tca_probe_workspace_bytes(void) { return (size_t)kProbeBlocks * 3 * sizeof(unsigned long long); }

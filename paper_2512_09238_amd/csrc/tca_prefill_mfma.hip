@@ -39,6 +39,7 @@
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <vector>
 
 #include "tca_prefill.h"
 
@@ -946,38 +947,78 @@ size_t prefill_mfma_workspace_bytes(const tca_params* prm, int64_t n_queries, in
                        max_dense_tiles(n_queries, prm->window)).bytes;
 }
 
-// Cuts the sequence of (head, query tile) work items, in the order the kernel walks it, into eight
-// ranges of equal estimated work and returns the length of the longest.  The estimate is in tile steps:
-// the dense tiles of the window, exactly; the visible part of a head's region as if its rows were spread
-// evenly over the positions seen so far (the host does not know idx); a constant for what a workgroup
-// does before and after its loop.  A poor estimate costs balance, never correctness.
+// Chooses the ranges of the (head, query tile) sequence, in the order the kernel walks it, that the eight
+// XCDs work through, and returns the length of the longest.  Two candidates: whole heads per XCD, and
+// eight ranges of equal estimated work (heads keep different numbers of rows).  The estimate is in tile
+// steps: the dense tiles of the window, exactly; the visible part of a head's region as if its rows
+// were spread evenly over the positions seen so far (the host does not know idx); a constant for what a
+// workgroup does before and after its loop.  Each candidate is played through (`slots` workgroups at a
+// time per XCD, the next item to the first free slot) and the one that ends sooner is taken: with few
+// long items per slot a range of equal work but one item more than the slots divide costs a whole
+// round.  A poor estimate costs balance, never correctness.
 static int64_t plan_xcds(PrefillHeads& ph, const tca_params* prm, const int64_t* offs, int64_t q_pos0,
-                         int64_t n_queries, int BM, int part) {
+                         int64_t n_queries, int BM, int part, int slots) {
   const int Hq = prm->n_q_heads, GS = sel_group(prm), w = prm->window;
-  const int64_t n_qt = (n_queries + BM - 1) / BM, L_end = q_pos0 + n_queries;
+  const int64_t n_qt = (n_queries + BM - 1) / BM, L_end = q_pos0 + n_queries, n_items = Hq * n_qt;
   constexpr int64_t kFixedSteps = 4;
-  auto cost = [&](int64_t cap, int64_t qt) {
+  auto cost = [&](int64_t g) {                     // item g: head g / n_qt, its query tiles longest first
+    const int64_t h = g / n_qt, qt = n_qt - 1 - g % n_qt, cap = offs[h / GS + 1] - offs[h / GS];
     const int64_t first = q_pos0 + qt * BM, lastq = first + BM - 1 < L_end - 1 ? first + BM - 1 : L_end - 1;
     int64_t c = kFixedSteps;
     if (part != TCA_PART_GLOBAL) c += lastq / kBN - (first - w + 1 > 0 ? first - w + 1 : 0) / kBN + 1;
     if (part != TCA_PART_WINDOW && lastq >= w) c += (cap * (lastq - w + 1) / L_end + kBN - 1) / kBN;
     return c;
   };
+  std::vector<int32_t> c((size_t)n_items);
   int64_t total = 0;
-  for (int h = 0; h < Hq; ++h)
-    for (int64_t j = 0; j < n_qt; ++j) total += cost(offs[h / GS + 1] - offs[h / GS], n_qt - 1 - j);
-  int64_t acc = 0, g = 0, longest = 0;
+  for (int64_t g = 0; g < n_items; ++g) total += c[g] = (int32_t)cost(g);
+  int32_t by_head[9], by_work[9];
+  for (int x = 0; x <= 8; ++x) by_head[x] = (int32_t)(x * (Hq / 8) * n_qt);
+  int64_t acc = 0;
   int x = 0;
-  ph.xcd_start[0] = 0;
-  for (int h = 0; h < Hq; ++h)
-    for (int64_t j = 0; j < n_qt; ++j, ++g) {
-      acc += cost(offs[h / GS + 1] - offs[h / GS], n_qt - 1 - j);
-      while (x < 7 && acc * 8 >= total * (x + 1)) ph.xcd_start[++x] = (int32_t)(g + 1);
+  by_work[0] = 0;
+  for (int64_t g = 0; g < n_items; ++g) {
+    acc += c[g];
+    while (x < 7 && acc * 8 >= total * (x + 1)) by_work[++x] = (int32_t)(g + 1);
+  }
+  while (x < 8) by_work[++x] = (int32_t)n_items;
+  // when the slowest XCD ends, the kernel's own order inside a range: the piece of the head the range ends in first
+  auto makespan = [&](const int32_t* st) {
+    int64_t worst = 0, free_at[64];
+    for (int xc = 0; xc < 8; ++xc) {
+      const int64_t s = st[xc], e = st[xc + 1], he = e / n_qt * n_qt, len_e = he > s ? e - he : 0;
+      for (int i = 0; i < slots; ++i) free_at[i] = 0;
+      for (int64_t u = 0; u < e - s; ++u) {
+        int first = 0;
+        for (int i = 1; i < slots; ++i)
+          if (free_at[i] < free_at[first]) first = i;
+        free_at[first] += c[u < len_e ? he + u : s + (u - len_e)];
+      }
+      for (int i = 0; i < slots; ++i)
+        if (free_at[i] > worst) worst = free_at[i];
     }
-  while (x < 8) ph.xcd_start[++x] = (int32_t)g;
+    return worst;
+  };
+  // with many rounds per slot the last, shortest items even the ends out and equal work wins
+  const bool few_rounds = n_items < (int64_t)8 * slots * 16;
+  const int32_t* best = !few_rounds || makespan(by_work) < makespan(by_head) ? by_work : by_head;
+  int64_t longest = 0;
+  for (x = 0; x <= 8; ++x) ph.xcd_start[x] = best[x];
   for (x = 0; x < 8; ++x)
-    if (ph.xcd_start[x + 1] - ph.xcd_start[x] > longest) longest = ph.xcd_start[x + 1] - ph.xcd_start[x];
+    if (best[x + 1] - best[x] > longest) longest = best[x + 1] - best[x];
   return longest;
+}
+
+// The workgroup shape of a call: waves, and blocks of 32 queries per wave.  The size of the call chooses
+// between eight and four waves of 32 queries; the diagnostics switch can force a shape.
+struct WgShape { int nw, qb; };
+static WgShape choose_shape(const tca_params* prm, int64_t n_queries, bool gather) {
+  const int variant = prefill_variant();
+  const bool many = ((n_queries + 255) / 256) * prm->n_q_heads >= 1024;
+  if (gather) return {variant == 3 || (variant != 1 && many) ? 8 : 4, 1};
+  if (variant == 3 || (variant == 0 && many)) return {8, 1};
+  if (variant == 2) return {4, 2};
+  return {4, 1};
 }
 
 template <int D>
@@ -1033,7 +1074,9 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
     constexpr int NW = decltype(nw_tag)::value, QB = decltype(qb_tag)::value;
     constexpr bool GATHER = decltype(gather_tag)::value;
     const int n_qt = (int)((n_queries + NW * QB * 32 - 1) / (NW * QB * 32));
-    const unsigned n_wg = (Hq & 7) == 0 ? 8u * (unsigned)plan_xcds(ph, prm, offs, q_pos0, n_queries, NW * QB * 32, part)
+    // workgroups an XCD runs at a time: 32 CUs, one eight-wave workgroup or two four-wave ones each
+    const unsigned n_wg = (Hq & 7) == 0 ? 8u * (unsigned)plan_xcds(ph, prm, offs, q_pos0, n_queries, NW * QB * 32, part,
+                                                                   NW == 8 || QB == 2 ? 32 : 64)
                                         : (unsigned)n_qt * Hq;
     hipLaunchKernelGGL((prefill_mfma_kernel<D, NW, QB, GATHER>), dim3(n_wg), dim3(NW * 64), 0, st, Q,
                        q_pos0, n_queries, K, kv_stride, idx, Kg, n_rows, mw.Vgt, mw.Vt, dt0, d_tiles, ph, Hq,
@@ -1043,14 +1086,24 @@ static void run_mfma(const tca_params* prm, const uint16_t* Q, int64_t q_pos0, i
   using I2 = std::integral_constant<int, 2>;
   using I4 = std::integral_constant<int, 4>;
   using I8 = std::integral_constant<int, 8>;
-  const int variant = prefill_variant();
-  const bool many = ((n_queries + 255) / 256) * Hq >= 1024;
-  if (gather) {                                  // the two shapes the size of a call chooses between
-    if (variant == 3 || (variant != 1 && many)) launch(I8{}, I1{}, std::true_type{});
+  const WgShape sh = choose_shape(prm, n_queries, gather);
+  if (gather) {
+    if (sh.nw == 8) launch(I8{}, I1{}, std::true_type{});
     else launch(I4{}, I1{}, std::true_type{});
-  } else if (variant == 3 || (variant == 0 && many)) launch(I8{}, I1{}, std::false_type{});
-  else if (variant == 2) launch(I4{}, I2{}, std::false_type{});
+  } else if (sh.nw == 8) launch(I8{}, I1{}, std::false_type{});
+  else if (sh.qb == 2) launch(I4{}, I2{}, std::false_type{});
   else launch(I4{}, I1{}, std::false_type{});
+}
+
+int64_t prefill_mfma_xcd_plan(const tca_params* prm, const int64_t* offs, int64_t q_pos0, int64_t n_queries, int part,
+                              bool gather, int32_t* start_out) {
+  if ((prm->n_q_heads & 7) != 0) return -1;
+  const WgShape sh = choose_shape(prm, n_queries, gather);
+  PrefillHeads ph;
+  const int64_t longest = plan_xcds(ph, prm, offs, q_pos0, n_queries, sh.nw * sh.qb * 32, part,
+                                    sh.nw == 8 || sh.qb == 2 ? 32 : 64);
+  for (int x = 0; x <= 8; ++x) start_out[x] = ph.xcd_start[x];
+  return 8 * longest;
 }
 
 int launch_prefill_mfma(const tca_params* prm, const bf16_t* Q, int64_t q_pos0, int64_t n_queries,

@@ -114,15 +114,6 @@ void qkv_mfma_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict_
   for (int kk = 0; kk < KS; ++kk) fo[kk] = lrow * ROWB + (((kk * 2 + hh) ^ swz_of(lrow)) << 4);
   const unsigned char* const wbase = lds + wf * (128 * ROWB);
   const unsigned char* const xbase = lds + TILEB + wt * (WT * ROWB);
-  auto read = [&](int s, int kk, bf16x8_t (&a)[4], bf16x8_t (&b)[TB]) {
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb)
-      a[fb] = *reinterpret_cast<const bf16x8_t*>(wbase + s * STAGEB + fb * (32 * ROWB) + fo[kk]);
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-      b[tb] = *reinterpret_cast<const bf16x8_t*>(xbase + s * STAGEB + tb * (32 * ROWB) + fo[kk]);
-  };
-
   f32x16_t acc[4][TB];
 #pragma unroll
   for (int fb = 0; fb < 4; ++fb)
@@ -144,16 +135,16 @@ void qkv_mfma_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict_
   // is one copy of the stretch in the code (the place is a run-time offset; the first stretch
   // multiplies zeros for the stage that is not there, the last ones copy the last stage again instead
   // of stages that are not there), because every further copy of it costs registers the accumulators
-  // need.  A stretch is one scheduling region, whose order is spelled out for the scheduler: one MFMA,
-  // one copy while there are any, one fragment read while there are any.  Left to itself it issues the
-  // copies in one burst and the fragment reads in clumps.
-  static_assert(KS % 2 == 0 && NST >= 2, "fragment registers alternate per k-step");
+  // need.  The order of a stretch's instructions is written out and fenced (sched_barrier): one MFMA,
+  // behind every second one a fragment read of the next k-step in the order of need, behind each of the
+  // stretch's first ones a copy.  Left to itself the compiler issues the copies in one burst and the
+  // fragment reads in clumps (5 % slower, as is an order merely suggested through sched_group_barrier).
+  static_assert(KS == 4 && NST >= 2, "the stretch below is four k-steps");
   const int nk = hidden / BK;
   constexpr int kGroup = 2 * NL;                 // loads of one stage, per wave
   constexpr int kAhead = (NST - 2) * kGroup;     // loads that may still be in flight when the next stage must be in
   static_assert(kAhead < 64, "vmcnt is six bits wide");
   constexpr int kWaitNext = 0x0F70 | (kAhead & 15) | ((kAhead >> 4) << 14);   // vmcnt: bits [3:0] and [15:14]
-  constexpr int kMfma = 0x008, kDsRead = 0x100, kVmemRead = 0x020;
   bf16x8_t a0[4], b0[TB], a1[4], b1[TB];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -167,24 +158,45 @@ void qkv_mfma_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict_
   __builtin_amdgcn_s_waitcnt(kWaitNext);         // stage 0 is in
   __syncthreads();
   int s = 0;                                     // place of stage kt
+  // fragment i of k-step kk of the stage in place sp, in the order the MFMAs need them: W block 0, the X
+  // blocks, the other W blocks
+  auto read_one = [&](int sp, int kk, int i, bf16x8_t (&a)[4], bf16x8_t (&b)[TB]) {
+    if (i == 0) a[0] = *reinterpret_cast<const bf16x8_t*>(wbase + sp * STAGEB + fo[kk]);
+    else if (i <= TB) b[i - 1] = *reinterpret_cast<const bf16x8_t*>(xbase + sp * STAGEB + (i - 1) * (32 * ROWB) + fo[kk]);
+    else a[i - TB] = *reinterpret_cast<const bf16x8_t*>(wbase + sp * STAGEB + (i - TB) * (32 * ROWB) + fo[kk]);
+  };
+  // copy i of this wave's share of stage kt into place sp
+  auto issue_one = [&](int kt, int sp, int i) {
+    const int j = i >> 1;
+    unsigned char* dst = lds + sp * STAGEB + (wv * NL + j) * 1024;
+    if (i & 1) copy16_to_lds(rs_x, lo[j], kt * ROWB, dst + TILEB);
+    else copy16_to_lds(rs_w, lo[j], kt * ROWB, dst);
+  };
+  // one k-step: the MFMAs of the current fragments (ca, cb); the reads of the fragments (na, nb) of k-step
+  // kk of place sp; with COPY the copies of stage ckt into place cs
+  constexpr int NM = 4 * TB, NR = 4 + TB, RSTEP = NM / NR > 1 ? 2 : 1;
+  auto kstep = [&](const bf16x8_t (&ca)[4], const bf16x8_t (&cb)[TB], bf16x8_t (&na)[4], bf16x8_t (&nb)[TB], int sp, int kk,
+                   auto copy_tag, int ckt, int cs) {
+    constexpr bool COPY = decltype(copy_tag)::value;
+#pragma unroll
+    for (int j = 0; j < NM; ++j) {
+      const int fb = j / TB, tb = j % TB;
+      acc[fb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[fb], cb[tb], acc[fb][tb], 0, 0, 0);
+      if (j % RSTEP == 0 && j / RSTEP < NR) read_one(sp, kk, j / RSTEP, na, nb);
+      if (COPY && j < kGroup) issue_one(ckt, cs, j);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   for (int kt = 0; kt < nk; ++kt) {
     const int s_prev = s == 0 ? NST - 1 : s - 1;
-    issue(kt + NST - 1 < nk ? kt + NST - 1 : nk - 1, s_prev);
-    read(s, 0, a0, b0);
-    mma(a1, b1);                                 // the last k-step of stage kt - 1
-#pragma unroll
-    for (int kk = 1; kk < KS; ++kk) {
-      if (kk & 1) { read(s, kk, a1, b1); mma(a0, b0); }
-      else { read(s, kk, a0, b0); mma(a1, b1); }
-    }
+    const int ckt = kt + NST - 1 < nk ? kt + NST - 1 : nk - 1;
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(a1, b1, a0, b0, s, 0, std::true_type{}, ckt, s_prev);          // the last k-step of stage kt - 1
+    kstep(a0, b0, a1, b1, s, 1, std::false_type{}, 0, 0);
+    kstep(a1, b1, a0, b0, s, 2, std::false_type{}, 0, 0);
+    kstep(a0, b0, a1, b1, s, 3, std::false_type{}, 0, 0);
     __builtin_amdgcn_s_waitcnt(kWaitNext);       // this wave's share of stage kt + 1 has landed
     __syncthreads();                             // everyone's has, and nobody reads stage kt any more
-#pragma unroll
-    for (int i = 0; i < KS * 4 * TB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-      if (i < kGroup) __builtin_amdgcn_sched_group_barrier(kVmemRead, 1, 0);
-      if (i < KS * (4 + TB)) __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
-    }
     s = s + 1 == NST ? 0 : s + 1;
   }
   mma(a1, b1);                                   // the last k-step of the last stage

@@ -112,6 +112,56 @@ def test_probe_rejects_bad_arguments_without_a_gpu():
     assert rc == tb.TCA_ERR_WORKSPACE
 
 
+def test_prefill_work_split_over_the_xcds():
+    """Host logic of the bf16 prefill launch: the ranges the eight XCDs take cover the (head, query tile)
+    sequence once, in order; equal regions with few long items per CU keep whole heads per XCD (an item
+    more than the CUs divide would cost a whole round); unequal regions move the cuts towards the light
+    heads; and the grid is eight times the longest range."""
+    import paper_2512_09238_amd.binding as tb
+    Hq, Hkv, d, b, w = 32, 8, 128, 128, 4096
+    prm = tb.make_params(Hq, Hkv, d, b, w, tb.TCA_BF16, 0.5, 0.0)
+    L = 131072
+    n_qt = L // 256                                           # long calls: 256 queries per workgroup
+
+    def check(start, n_wg, items):
+        assert start[0] == 0 and start[8] == items and (np.diff(start) >= 0).all()
+        assert n_wg == 8 * int(np.diff(start).max())
+
+    # equal regions, the whole sequence: equal work is equal counts
+    offs = np.arange(Hq + 1, dtype=np.int64) * 70000
+    start, n_wg = tb.tca_diag_prefill_xcd_plan(prm, offs, 0, L)
+    check(start, n_wg, Hq * n_qt)
+    assert np.abs(np.diff(start) - 4 * n_qt).max() <= 1 and n_wg <= 8 * (4 * n_qt + 1)
+    # the last 8192-token chunk of it: 1024 long items on 256 CUs, four rounds only if every XCD takes 128
+    start, n_wg = tb.tca_diag_prefill_xcd_plan(prm, offs, L - 8192, 8192)
+    check(start, n_wg, Hq * 32)
+    assert np.array_equal(start, np.arange(9) * 128) and n_wg == 1024
+    # regions from 5 % to 50 % of the sequence, heavy heads first: the first XCDs take fewer items
+    rows = np.linspace(0.5, 0.05, Hq) * L
+    offs = np.concatenate([[0], np.cumsum(rows.astype(np.int64))])
+    start, n_wg = tb.tca_diag_prefill_xcd_plan(prm, offs, 0, L)
+    check(start, n_wg, Hq * n_qt)
+    counts = np.diff(start)
+    assert counts[0] < 4 * n_qt < counts[7] and (np.diff(counts) >= 0).all()
+    # the work of the ranges, recomputed here from the sizes: within a few per cent of each other
+    def work(g):
+        h, qt = g // n_qt, n_qt - 1 - g % n_qt
+        last = qt * 256 + 255
+        return 64 + 4 + (rows[h] * max(0, last - w + 1) / L) / 64
+    per_xcd = [sum(work(g) for g in range(start[x], start[x + 1])) for x in range(8)]
+    assert max(per_xcd) / min(per_xcd) < 1.05
+    # a window-only part has no regions to weigh: equal counts again
+    start, n_wg = tb.tca_diag_prefill_xcd_plan(prm, offs, 0, L, part=tb.TCA_PART_WINDOW)
+    check(start, n_wg, Hq * n_qt)
+    assert np.abs(np.diff(start) - 4 * n_qt).max() <= 2
+    # short calls use 128 queries per workgroup; head counts that are no multiple of 8 have no plan
+    start, n_wg = tb.tca_diag_prefill_xcd_plan(prm, np.arange(Hq + 1, dtype=np.int64) * 1000, 0, 4096)
+    check(start, n_wg, Hq * 32)
+    prm12 = tb.make_params(12, 4, d, b, w, tb.TCA_BF16, 0.5, 0.0)
+    with pytest.raises(ValueError):
+        tb.tca_diag_prefill_xcd_plan(prm12, np.arange(13, dtype=np.int64) * 1000, 0, 4096)
+
+
 def test_binding_loads_torch_before_the_library():
     """One HIP runtime per process: the binding imports torch (which ships its own copy) before it
     loads libtca.so, whatever the caller imported first."""
