@@ -193,6 +193,23 @@ def test_qkv_project_matches_oracle(tb, bufs, case):
         assert min(equal) > 0.99
 
 
+def _draw_projection(rng):
+    G, Hkv = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+    d = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    hidden = 64 * int(rng.integers(1, 13)) if dtype == "bf16" else int(rng.integers(3, 200))
+    n = int(rng.integers(1, 1300)) if dtype == "bf16" else int(rng.integers(1, 80))
+    return G * Hkv, Hkv, d, hidden, n, dtype, bool(rng.integers(0, 2)), str(rng.choice(["head", "token"])), int(rng.integers(0, 5))
+
+
+@pytest.mark.parametrize("case", [_draw_projection(np.random.default_rng(4100 + i)) for i in range(16)],
+                         ids=lambda c: f"hq{c[0]}-hkv{c[1]}-d{c[2]}-hid{c[3]}-n{c[4]}-{c[5]}-{c[7]}")
+def test_qkv_project_random_shapes(tb, bufs, case):
+    """A seeded sweep: every group size 1..8, both head dims, one to twelve stages, one to six token
+    tiles with ragged ends, feature counts that leave the last feature tile a quarter to full."""
+    test_qkv_project_matches_oracle(tb, bufs, case)
+
+
 def test_qkv_project_refuses_what_it_cannot_do(tb, bufs):
     prm = H.params_for(tb, 4, 2, 128, 16, 16, "bf16")
     x = wl.projection_inputs(4, 2, 128, 96, 8, "bf16", 5)
